@@ -1,0 +1,206 @@
+/* nerva_sparse.h -- C ABI of the truly sparse MLP training step on MI355X (gfx950).
+ *
+ * The library implements the four sparse operations that Section 4 of the paper
+ * ("Nerva: a Truly Sparse Implementation of Neural Networks") names as essential,
+ *
+ *     A = S B        feedforward              (sparse_linear_forward)
+ *     A = S^T B      backpropagation          (sparse_linear_backward, dX)
+ *     S = A B^T      on the pattern of S      (sparse_linear_backward, dvalues)
+ *     S = aS + bT    momentum, same pattern   (sgd_update_values)
+ *
+ * and one iteration of the training loop of the Appendix B listing
+ * (feedforward -> loss gradient / batch size -> backpropagate -> optimize) as
+ * mlp_train_step, for an MLP with ReLU hidden layers and a softmax cross-entropy
+ * loss (Section 5.1).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * - S (the weight matrix W of a layer) is CSR, rows = n_out, cols = n_in, zero-based
+ *   int32 row pointers `indptr[rows+1]` and column indices `indices[nnz]`, fp32
+ *   `values[nnz]`.  Column indices are strictly ascending inside a row.  Empty rows are
+ *   legal.  The pattern is static: no call ever writes indptr or indices.
+ * - Dense matrices hold one example per column (Appendix B listing: Xtrain[:, batch]).
+ *   They are fp32, row-major (features, ld): element (i, c) is at base[i*ld + c], with
+ *   ld >= batch.  Columns batch..ld-1 are padding: never written, and their contents
+ *   never influence a result.  Calls are fastest when every ld is a multiple of 4 and
+ *   every base pointer is 16-byte aligned; other values take a slower kernel.
+ * - Biases are dense fp32 vectors of length rows (Section 3: biases are not sparsified).
+ * - Every pointer is a DEVICE pointer owned by the caller unless the comment says
+ *   "host".  The library owns only what *_create builds and frees it in *_destroy.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Except for
+ *   the *_create calls, every call only enqueues kernels on that stream: it allocates
+ *   nothing, never synchronises, and may be captured in a HIP graph.  Calls on one
+ *   handle from several streams at once are not ordered by the library.
+ * - Return value: 0 on success, a negative nerva_status otherwise; nothing has been
+ *   enqueued when an argument error is returned.  nerva_last_error() gives a
+ *   thread-local message for the last failing call.
+ */
+#ifndef NERVA_SPARSE_H
+#define NERVA_SPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nerva_status {
+    NERVA_OK = 0,
+    NERVA_ERR_ARGUMENT = -1,   /* null pointer, negative size, unknown flag          */
+    NERVA_ERR_SHAPE = -2,      /* leading dimension < batch, layer sizes do not chain */
+    NERVA_ERR_CSR = -3,        /* pattern is not canonical CSR                        */
+    NERVA_ERR_WORKSPACE = -4,  /* workspace too small or misaligned                   */
+    NERVA_ERR_HIP = -5         /* a HIP runtime call failed                           */
+} nerva_status;
+
+typedef struct nerva_layer nerva_layer; /* one sparse linear layer: pattern, mirror, tables */
+typedef struct nerva_mlp nerva_mlp;     /* a chain of layers + optimiser state pointers     */
+
+enum { NERVA_ACT_NONE = 0, NERVA_ACT_RELU = 1 };
+
+/* Message of the last failing call on this thread ("" if none). Host pointer, valid
+ * until the next failing call on the thread. */
+const char *nerva_last_error(void);
+
+/* Library version and the GPU architecture the kernels were compiled for ("gfx950"). */
+const char *nerva_build_info(void);
+
+/* Check that HOST arrays describe a canonical CSR pattern: indptr[0] = 0, non-decreasing,
+ * indptr[rows] = nnz, every column index in [0, cols), strictly ascending per row.
+ * Returns NERVA_OK or NERVA_ERR_CSR / NERVA_ERR_ARGUMENT.  Needs no GPU. */
+int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz,
+                            const int32_t *indptr_host, const int32_t *indices_host);
+
+/* The static work partition the kernels use, computed on HOST arrays (needs no GPU; exposed so
+ * that it can be checked).  Rows are grouped by lg = log2(waves that share one row); a
+ * work-group of NERVA_WAVES_PER_BLOCK waves serves NERVA_WAVES_PER_BLOCK >> lg rows.
+ *   row_order_host[rows]      row ids in serving order (every row exactly once)
+ *   block_first_host[nb]      first position of row_order served by work-group b
+ *   block_info_host[nb]       lg | (number of rows served << 8)
+ *   *n_blocks_host            nb, at most `rows`
+ * Output arrays may be NULL (only the count is returned); otherwise they need `rows` entries. */
+enum { NERVA_WAVES_PER_BLOCK = 16 };
+int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
+                         int32_t *block_first_host, int32_t *block_info_host,
+                         int32_t *n_blocks_host);
+
+/* ---- layer -------------------------------------------------------------------------
+ * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays
+ * (which must outlive the layer) and builds, once, what a static pattern allows to be
+ * precomputed: the CSC mirror of W (CSR of W^T: indptr_t[cols+1], indices_t[nnz] = row
+ * indices ascending per column, values_t[nnz]) and the maps between CSR and mirror
+ * positions.  The paper leaves A = S^T B to the vendor library (Section 4); the mirror
+ * exists because the topology is static (Section 6).  The call copies the pattern to the
+ * host to validate it (NERVA_ERR_CSR if not canonical), allocates device memory and
+ * synchronises `stream`.  activation: NERVA_ACT_RELU for hidden layers, NERVA_ACT_NONE
+ * for the output layer (Section 5.1). `bias` may be NULL (no bias).  */
+int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz,
+                         const int32_t *indptr, const int32_t *indices,
+                         float *values, float *bias, int32_t activation, void *stream);
+void sparse_linear_destroy(nerva_layer *layer);
+
+/* Device pointers of the mirror, for inspection: indptr_t[cols+1], indices_t[nnz],
+ * values_t[nnz], perm[nnz] (mirror position -> CSR position). Any output may be NULL. */
+int sparse_linear_mirror(const nerva_layer *layer, const int32_t **indptr_t,
+                         const int32_t **indices_t, const float **values_t,
+                         const int32_t **perm);
+
+/* Feedforward, A = S B (Section 4) with the dense bias and the layer's activation:
+ *     Y[i,c] = act( bias[i] + sum_{p in row i} values[p] * X[indices[p], c] )
+ * X is (cols, ldx), Y is (rows, ldy), 0 < batch <= ldx, ldy.  X and Y must not overlap. */
+int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
+                          float *Y, int32_t ldy, int32_t batch, void *stream);
+
+/* Backpropagation through one layer (Section 4, A = S^T B and S = A B^T on S's pattern).
+ * With dZ = dY * [Y > 0] for a ReLU layer (the mask comes from the layer OUTPUT Y, as
+ * backpropagate(Y, dY) in the Appendix B listing; derivative 0 at 0) and dZ = dY otherwise:
+ *     dX[j,c]    = sum_{p : indices[p] = j} values[p] * dZ[row(p), c]     (skipped if dX == NULL)
+ *     dvalues[p] = sum_c dZ[row(p), c] * X[indices[p], c]                 (skipped if NULL)
+ *     dbias[i]   = sum_c dZ[i, c]                                         (skipped if NULL)
+ * X (cols, ldx) is the layer input of the forward pass, Y (rows, ldy) its output (may be
+ * NULL for NERVA_ACT_NONE), dY (rows, lddy), dX (cols, lddx).  All gradients use the
+ * current contents of values[]; dX first refreshes the mirror's values from values[], so
+ * the caller may have changed values[] by any means since the last call. */
+int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx,
+                           const float *Y, int32_t ldy, const float *dY, int32_t lddy,
+                           float *dX, int32_t lddx, float *dvalues, float *dbias,
+                           int32_t batch, void *stream);
+
+/* Momentum step on raw arrays that share one pattern (Section 4: S = aS + bT applied
+ * directly to the value arrays), used for values[] and for biases alike:
+ *     velocity[k] <- momentum * velocity[k] - lr * grad[k]
+ *     values[k]   <- values[k] + velocity[k]            for k in [0, n)
+ * No dampening, no weight decay.  The index arrays of the pattern are not arguments:
+ * the update cannot touch them. */
+int sgd_update_values(float *values, float *velocity, const float *grad, int64_t n,
+                      float lr, float momentum, void *stream);
+
+/* Softmax cross-entropy on logits Z (classes, ldz), mean over the batch, and its gradient
+ * divided by the batch size (Appendix B listing: loss.gradient(Y, T) / batch_size):
+ *     lse_c = log sum_i exp Z[i,c]      (computed with the column maximum subtracted)
+ *     *loss_out = (1/batch) sum_c ( lse_c - Z[labels[c], c] )
+ *     dZ[i,c]   = ( exp(Z[i,c] - lse_c) - [i == labels[c]] ) / batch
+ * labels: int32[batch] in [0, classes) (not checked on the device).  dZ may alias Z.
+ * loss_out: one device float (may be NULL). */
+int softmax_cross_entropy(const float *Z, int32_t ldz, const int32_t *labels,
+                          int32_t classes, int32_t batch, float *dZ, int32_t lddz,
+                          float *loss_out, void *stream);
+
+/* ---- MLP training step ---------------------------------------------------------------
+ * mlp_create chains n_layers layers (layer l's cols = layer l-1's rows; hidden layers
+ * ReLU, last layer NERVA_ACT_NONE) and binds the momentum buffers: velocities[l] is
+ * float[nnz_l], bias_velocities[l] is float[rows_l] (device, caller-owned, normally zero
+ * at the start; bias_velocities[l] may be NULL iff the layer has no bias).  The handle
+ * keeps the layer pointers: destroy the MLP before its layers.  max_batch bounds `batch`
+ * of later calls.  flags: bitwise OR of the NERVA_MLP_* values below. */
+enum {
+    NERVA_MLP_DEFAULT = 0,
+    /* Run S = A B^T, the momentum update and the mirror refresh as separate kernels that
+     * store the gradient arrays in the workspace (the composition of the calls above),
+     * instead of one fused kernel per layer that never stores dvalues. */
+    NERVA_MLP_UNFUSED = 1
+};
+int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers,
+               float *const *velocities, float *const *bias_velocities,
+               int32_t max_batch, int32_t flags);
+void mlp_destroy(nerva_mlp *mlp);
+
+/* Bytes of scratch mlp_train_step needs for `batch` columns (256-byte aligned base). */
+size_t mlp_workspace_bytes(const nerva_mlp *mlp, int32_t batch);
+
+/* Where mlp_train_step keeps its intermediates inside the workspace, so that a caller can
+ * read them after a step.  layout_host (HOST, int64[1 + 4*n_layers]) receives
+ *   [0]        ld, the leading dimension (in floats) of every matrix in the workspace
+ *   [1+4l+0]   byte offset of A_l   (rows_l, ld): output of layer l (last layer: logits)
+ *   [1+4l+1]   byte offset of dZ_l  (rows_l, ld): gradient w.r.t. the pre-activation
+ *   [1+4l+2]   byte offset of g_l   float[nnz_l]  (written only with NERVA_MLP_UNFUSED)
+ *   [1+4l+3]   byte offset of db_l  float[rows_l] (written only with NERVA_MLP_UNFUSED) */
+int mlp_workspace_layout(const nerva_mlp *mlp, int32_t batch, int64_t *layout_host);
+
+/* One iteration of the training loop (Appendix B listing) on one mini-batch:
+ *   feedforward:    A_l = act(W_l A_{l-1} + b_l), A_0 = X (cols_1, ldx)
+ *   loss gradient:  dZ_L = softmax-CE gradient / batch, *loss_out = mean cross-entropy
+ *   backpropagate:  dZ_{l-1} = (W_l^T dZ_l) * [A_{l-1} > 0]   (not for the first layer),
+ *                   g_l = (dZ_l A_{l-1}^T) on W_l's pattern, db_l = row sums of dZ_l;
+ *                   every gradient uses the weights as they were when the call started
+ *   optimize:       momentum step (see sgd_update_values) on values_l and bias_l.
+ * labels: int32[batch].  workspace: device scratch of at least mlp_workspace_bytes().
+ * loss_out: one device float (may be NULL). */
+int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels,
+                   int32_t batch, float lr, float momentum, void *workspace,
+                   size_t workspace_bytes, float *loss_out, void *stream);
+
+/* Forward pass only (inference on a batch): logits (rows_L, ld) are left in the
+ * workspace at the A_L offset. */
+int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Plain device copy dst[k] = src[k], k in [0, n): the known-size kernel that memory
+ * traffic counters are calibrated against.  Not part of the training path. */
+int nerva_copy_f32(float *dst, const float *src, int64_t n, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NERVA_SPARSE_H */

@@ -1,0 +1,540 @@
+// C ABI of the sparse MLP training step: argument checking, layer / MLP handles, the
+// one-off mirror build, and the kernel sequence of a training step.
+#include "../../include/nerva_sparse.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace nerva;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+int hip_fail(hipError_t e, const char *what)
+{
+    return fail(NERVA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(expr)                                        \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
+    } while (0)
+
+inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+}  // namespace
+
+struct nerva_layer {
+    int32_t rows = 0, cols = 0, nnz = 0, activation = 0;
+    // caller-owned
+    const int32_t *indptr = nullptr;
+    const int32_t *indices = nullptr;
+    float *values = nullptr;
+    float *bias = nullptr;
+    // owned: CSR of W^T and the position maps
+    int32_t *indptr_t = nullptr;   // [cols+1]
+    int32_t *indices_t = nullptr;  // [nnz] row index of each mirror entry
+    float *values_t = nullptr;     // [nnz]
+    int32_t *perm = nullptr;       // [nnz] mirror position -> CSR position
+    int32_t *pos_t = nullptr;      // [nnz] CSR position -> mirror position
+    // owned: static work partitions of W (by rows) and of the mirror (by W's columns)
+    int32_t *plan_mem = nullptr;
+    int32_t *plan_t_mem = nullptr;
+    RowBlocks plan{}, plan_t{};
+};
+
+struct nerva_mlp {
+    std::vector<nerva_layer *> layers;
+    std::vector<float *> vel;
+    std::vector<float *> bias_vel;
+    int32_t max_batch = 0;
+    int32_t flags = 0;
+};
+
+namespace {
+
+struct Layout {
+    int64_t ld = 0;
+    std::vector<int64_t> A, dZ, g, db;
+    int64_t bytes = 0;
+};
+
+Layout make_layout(const nerva_mlp *m, int32_t batch)
+{
+    Layout L;
+    L.ld = round_up(batch, 32);  // rows start on 128-byte boundaries
+    int64_t off = 0;
+    auto take = [&](int64_t floats) {
+        int64_t o = off;
+        off += round_up(floats * 4, 256);
+        return o;
+    };
+    for (const nerva_layer *l : m->layers) {
+        L.A.push_back(take(static_cast<int64_t>(l->rows) * L.ld));
+        L.dZ.push_back(take(static_cast<int64_t>(l->rows) * L.ld));
+        L.g.push_back(take(l->nnz));
+        L.db.push_back(take(l->rows));
+    }
+    L.bytes = off;
+    return L;
+}
+
+// Rows are grouped by the number of waves that share one row: 2^lg, the smallest power of two
+// that leaves each wave at most `target` stored entries, capped at a whole work-group.  `target`
+// aims at >= 16384 waves per launch (64 per compute unit) but never fewer than 8 entries per wave.
+int plan_rows(int32_t rows, const int32_t *indptr, std::vector<int32_t> &row_order,
+              std::vector<int32_t> &block_first, std::vector<int32_t> &block_info)
+{
+    const int64_t nnz = indptr[rows];
+    int64_t target = nnz / 16384;
+    if (target < 8) target = 8;
+    if (target > 64) target = 64;
+    int max_lg = 0;
+    while ((1 << max_lg) < kWavesPerBlock) ++max_lg;
+    std::vector<int8_t> lg_of(rows);
+    std::vector<int32_t> count(max_lg + 1, 0);
+    for (int32_t i = 0; i < rows; ++i) {
+        const int64_t n = indptr[i + 1] - indptr[i];
+        int lg = 0;
+        while (lg < max_lg && (n + (1 << lg) - 1) / (1 << lg) > target) ++lg;
+        lg_of[i] = static_cast<int8_t>(lg);
+        ++count[lg];
+    }
+    row_order.resize(rows);
+    block_first.clear();
+    block_info.clear();
+    int32_t slot = 0;
+    for (int lg = max_lg; lg >= 0; --lg) {
+        if (!count[lg]) continue;
+        const int32_t begin = slot;
+        for (int32_t i = 0; i < rows; ++i)
+            if (lg_of[i] == lg) row_order[slot++] = i;
+        const int32_t per_block = kWavesPerBlock >> lg;
+        for (int32_t f = begin; f < slot; f += per_block) {
+            const int32_t n_rows = slot - f < per_block ? slot - f : per_block;
+            block_first.push_back(f);
+            block_info.push_back(lg | (n_rows << 8));
+        }
+    }
+    return static_cast<int>(block_first.size());
+}
+
+hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, RowBlocks *plan, hipStream_t s,
+                       std::vector<int32_t> &staging)
+{
+    std::vector<int32_t> order, first, info;
+    const int nb = plan_rows(rows, indptr_host, order, first, info);
+    staging = order;
+    staging.insert(staging.end(), first.begin(), first.end());
+    staging.insert(staging.end(), info.begin(), info.end());
+    hipError_t e = hipMalloc(mem, staging.size() * 4);
+    if (e != hipSuccess) return e;
+    e = hipMemcpyAsync(*mem, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, s);
+    plan->row_order = *mem;
+    plan->block_first = *mem + rows;
+    plan->block_info = *mem + rows + nb;
+    plan->n_blocks = nb;
+    return e;
+}
+
+void free_layer_buffers(nerva_layer *l)
+{
+    (void)hipFree(l->plan_mem);
+    (void)hipFree(l->plan_t_mem);
+    (void)hipFree(l->indptr_t);
+    (void)hipFree(l->indices_t);
+    (void)hipFree(l->values_t);
+    (void)hipFree(l->perm);
+    (void)hipFree(l->pos_t);
+}
+
+int check_batch(int32_t batch, int32_t ld, const char *name)
+{
+    if (batch <= 0) return fail(NERVA_ERR_ARGUMENT, "batch must be positive (got %d)", batch);
+    if (ld < batch) return fail(NERVA_ERR_SHAPE, "%s = %d is smaller than batch = %d", name, ld, batch);
+    if (ld >= (1 << 30)) return fail(NERVA_ERR_SHAPE, "%s = %d: rows of 4 GiB or more are not supported", name, ld);
+    return NERVA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *nerva_last_error(void) { return g_last_error.c_str(); }
+
+const char *nerva_build_info(void) { return "nerva_sparse 0.1 gfx950 fp32/int32"; }
+
+int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz, const int32_t *indptr,
+                            const int32_t *indices)
+{
+    if (rows < 0 || cols < 0 || nnz < 0) return fail(NERVA_ERR_ARGUMENT, "negative size");
+    if (!indptr || (nnz > 0 && !indices)) return fail(NERVA_ERR_ARGUMENT, "null pattern array");
+    if (nnz > INT32_MAX) return fail(NERVA_ERR_ARGUMENT, "nnz does not fit int32 indices");
+    if (indptr[0] != 0) return fail(NERVA_ERR_CSR, "indptr[0] = %d, expected 0", indptr[0]);
+    for (int32_t i = 0; i < rows; ++i) {
+        const int64_t b = indptr[i], e = indptr[i + 1];
+        if (e < b) return fail(NERVA_ERR_CSR, "indptr decreases at row %d", i);
+        if (e > nnz) return fail(NERVA_ERR_CSR, "indptr[%d] = %lld exceeds nnz = %lld", i + 1, (long long)e, (long long)nnz);
+        for (int64_t p = b; p < e; ++p) {
+            const int32_t j = indices[p];
+            if (j < 0 || j >= cols) return fail(NERVA_ERR_CSR, "column index %d out of range at position %lld", j, (long long)p);
+            if (p > b && indices[p - 1] >= j)
+                return fail(NERVA_ERR_CSR, "column indices not strictly ascending in row %d", i);
+        }
+    }
+    if (indptr[rows] != nnz) return fail(NERVA_ERR_CSR, "indptr[rows] = %d, expected nnz = %lld", indptr[rows], (long long)nnz);
+    return NERVA_OK;
+}
+
+int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
+                         int32_t *block_first_host, int32_t *block_info_host, int32_t *n_blocks_host)
+{
+    if (rows <= 0 || !indptr_host || !n_blocks_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    std::vector<int32_t> order, first, info;
+    const int nb = plan_rows(rows, indptr_host, order, first, info);
+    *n_blocks_host = nb;
+    if (row_order_host) memcpy(row_order_host, order.data(), order.size() * 4);
+    if (block_first_host) memcpy(block_first_host, first.data(), first.size() * 4);
+    if (block_info_host) memcpy(block_info_host, info.data(), info.size() * 4);
+    return NERVA_OK;
+}
+
+int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
+                         const int32_t *indices, float *values, float *bias, int32_t activation, void *stream)
+{
+    if (!out) return fail(NERVA_ERR_ARGUMENT, "out is null");
+    *out = nullptr;
+    if (rows <= 0 || cols <= 0 || nnz < 0) return fail(NERVA_ERR_ARGUMENT, "bad layer size %d x %d, nnz %d", rows, cols, nnz);
+    if (!indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
+    if (activation != NERVA_ACT_NONE && activation != NERVA_ACT_RELU) return fail(NERVA_ERR_ARGUMENT, "unknown activation %d", activation);
+    hipStream_t s = as_stream(stream);
+
+    std::vector<int32_t> h_indptr(static_cast<size_t>(rows) + 1), h_indices(static_cast<size_t>(nnz));
+    HIP_TRY(hipMemcpyAsync(h_indptr.data(), indptr, h_indptr.size() * 4, hipMemcpyDeviceToHost, s));
+    if (nnz) HIP_TRY(hipMemcpyAsync(h_indices.data(), indices, h_indices.size() * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    int rc = nerva_validate_csr_host(rows, cols, nnz, h_indptr.data(), h_indices.data());
+    if (rc != NERVA_OK) return rc;
+
+    // Counting sort of the stored entries by column; ties keep row order, so the mirror is
+    // the canonical CSR of W^T.  Integer work, done once because the pattern never changes.
+    std::vector<int32_t> h_indptr_t(static_cast<size_t>(cols) + 1, 0), h_indices_t(nnz), h_perm(nnz), h_pos_t(nnz);
+    for (int32_t p = 0; p < nnz; ++p) ++h_indptr_t[h_indices[p] + 1];
+    for (int32_t j = 0; j < cols; ++j) h_indptr_t[j + 1] += h_indptr_t[j];
+    {
+        std::vector<int32_t> cursor(h_indptr_t.begin(), h_indptr_t.end() - 1);
+        for (int32_t i = 0; i < rows; ++i)
+            for (int32_t p = h_indptr[i]; p < h_indptr[i + 1]; ++p) {
+                const int32_t q = cursor[h_indices[p]]++;
+                h_indices_t[q] = i;
+                h_perm[q] = p;
+                h_pos_t[p] = q;
+            }
+    }
+
+    nerva_layer *l = new (std::nothrow) nerva_layer;
+    if (!l) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
+    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation;
+    l->indptr = indptr; l->indices = indices; l->values = values; l->bias = bias;
+    const size_t nb = static_cast<size_t>(nnz > 0 ? nnz : 1) * 4;
+    hipError_t e = hipMalloc(&l->indptr_t, (static_cast<size_t>(cols) + 1) * 4);
+    if (e == hipSuccess) e = hipMalloc(&l->indices_t, nb);
+    if (e == hipSuccess) e = hipMalloc(&l->values_t, nb);
+    if (e == hipSuccess) e = hipMalloc(&l->perm, nb);
+    if (e == hipSuccess) e = hipMalloc(&l->pos_t, nb);
+    if (e == hipSuccess) e = hipMemcpyAsync(l->indptr_t, h_indptr_t.data(), h_indptr_t.size() * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->indices_t, h_indices_t.data(), nb, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->perm, h_perm.data(), nb, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->pos_t, h_pos_t.data(), nb, hipMemcpyHostToDevice, s);
+    std::vector<int32_t> stage_a, stage_b;
+    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), &l->plan_mem, &l->plan, s, stage_a);
+    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
+    if (e == hipSuccess) e = launch_gather(l->values_t, values, l->perm, nnz, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
+    if (e != hipSuccess) {
+        free_layer_buffers(l);
+        delete l;
+        return hip_fail(e, "sparse_linear_create");
+    }
+    *out = l;
+    return NERVA_OK;
+}
+
+void sparse_linear_destroy(nerva_layer *layer)
+{
+    if (!layer) return;
+    free_layer_buffers(layer);
+    delete layer;
+}
+
+int sparse_linear_mirror(const nerva_layer *layer, const int32_t **indptr_t, const int32_t **indices_t,
+                         const float **values_t, const int32_t **perm)
+{
+    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
+    if (indptr_t) *indptr_t = layer->indptr_t;
+    if (indices_t) *indices_t = layer->indices_t;
+    if (values_t) *values_t = layer->values_t;
+    if (perm) *perm = layer->perm;
+    return NERVA_OK;
+}
+
+int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx, float *Y, int32_t ldy,
+                          int32_t batch, void *stream)
+{
+    if (!layer || !X || !Y) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    int rc = check_batch(batch, ldx, "ldx");
+    if (rc == NERVA_OK) rc = check_batch(batch, ldy, "ldy");
+    if (rc != NERVA_OK) return rc;
+    SpmmArgs a{};
+    a.blocks = layer->plan;
+    a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
+    a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
+    a.rows = layer->rows; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
+    HIP_TRY(launch_spmm(a, as_stream(stream)));
+    return NERVA_OK;
+}
+
+int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, const float *Y, int32_t ldy,
+                           const float *dY, int32_t lddy, float *dX, int32_t lddx, float *dvalues, float *dbias,
+                           int32_t batch, void *stream)
+{
+    if (!layer || !dY) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    const bool relu = layer->activation == NERVA_ACT_RELU;
+    if (relu && !Y) return fail(NERVA_ERR_ARGUMENT, "a ReLU layer needs its output Y for the backward pass");
+    if (dvalues && !X) return fail(NERVA_ERR_ARGUMENT, "dvalues needs the layer input X");
+    int rc = check_batch(batch, lddy, "lddy");
+    if (rc == NERVA_OK && relu) rc = check_batch(batch, ldy, "ldy");
+    if (rc == NERVA_OK && dvalues) rc = check_batch(batch, ldx, "ldx");
+    if (rc == NERVA_OK && dX) rc = check_batch(batch, lddx, "lddx");
+    if (rc != NERVA_OK) return rc;
+    hipStream_t s = as_stream(stream);
+    if (dX) {
+        HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
+        SpmmArgs a{};
+        a.blocks = layer->plan_t;
+        a.indptr = layer->indptr_t; a.indices = layer->indices_t; a.values = layer->values_t;
+        a.X = dY; a.ldx = lddy;
+        if (relu) { a.XM = Y; a.ldxm = ldy; }
+        a.Y = dX; a.ldy = lddx; a.rows = layer->cols; a.batch = batch;
+        HIP_TRY(launch_spmm(a, s));
+    }
+    if (dvalues || dbias) {
+        SddmmArgs a{};
+        a.blocks = layer->plan;
+        a.indptr = layer->indptr; a.indices = layer->indices;
+        a.dZ = dY; a.lddz = lddy;
+        if (relu) { a.ZM = Y; a.ldzm = ldy; }
+        a.X = X; a.ldx = ldx; a.g = dvalues; a.db = dbias;
+        a.rows = layer->rows; a.batch = batch;
+        a.skip_products = dvalues ? 0 : 1;  // only the bias gradient is wanted
+        HIP_TRY(launch_sddmm(a, s));
+    }
+    return NERVA_OK;
+}
+
+int sgd_update_values(float *values, float *velocity, const float *grad, int64_t n, float lr, float momentum,
+                      void *stream)
+{
+    if (n < 0) return fail(NERVA_ERR_ARGUMENT, "n is negative");
+    if (n > 0 && (!values || !velocity || !grad)) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    HIP_TRY(launch_momentum(values, velocity, grad, n, lr, momentum, as_stream(stream)));
+    return NERVA_OK;
+}
+
+int softmax_cross_entropy(const float *Z, int32_t ldz, const int32_t *labels, int32_t classes, int32_t batch,
+                          float *dZ, int32_t lddz, float *loss_out, void *stream)
+{
+    if (!Z || !labels || !dZ) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    if (classes <= 0) return fail(NERVA_ERR_ARGUMENT, "classes must be positive");
+    int rc = check_batch(batch, ldz, "ldz");
+    if (rc == NERVA_OK) rc = check_batch(batch, lddz, "lddz");
+    if (rc != NERVA_OK) return rc;
+    HIP_TRY(launch_softmax_ce(Z, ldz, labels, classes, batch, dZ, lddz, loss_out, as_stream(stream)));
+    return NERVA_OK;
+}
+
+int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, float *const *velocities,
+               float *const *bias_velocities, int32_t max_batch, int32_t flags)
+{
+    if (!out) return fail(NERVA_ERR_ARGUMENT, "out is null");
+    *out = nullptr;
+    if (n_layers <= 0 || !layers || !velocities || !bias_velocities) return fail(NERVA_ERR_ARGUMENT, "null or empty layer list");
+    if (max_batch <= 0) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive");
+    if (flags & ~NERVA_MLP_UNFUSED) return fail(NERVA_ERR_ARGUMENT, "unknown flags 0x%x", flags);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (!layers[l]) return fail(NERVA_ERR_ARGUMENT, "layer %d is null", l);
+        if (layers[l]->nnz > 0 && !velocities[l]) return fail(NERVA_ERR_ARGUMENT, "velocity of layer %d is null", l);
+        if (layers[l]->bias && !bias_velocities[l]) return fail(NERVA_ERR_ARGUMENT, "bias velocity of layer %d is null", l);
+        if (l > 0 && layers[l]->cols != layers[l - 1]->rows)
+            return fail(NERVA_ERR_SHAPE, "layer %d has %d inputs but layer %d has %d outputs", l, layers[l]->cols, l - 1, layers[l - 1]->rows);
+        const int32_t want = l + 1 < n_layers ? NERVA_ACT_RELU : NERVA_ACT_NONE;
+        if (layers[l]->activation != want)
+            return fail(NERVA_ERR_ARGUMENT, "layer %d: hidden layers must be ReLU and the last layer linear", l);
+    }
+    nerva_mlp *m = new (std::nothrow) nerva_mlp;
+    if (!m) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
+    m->layers.assign(layers, layers + n_layers);
+    m->vel.assign(velocities, velocities + n_layers);
+    m->bias_vel.assign(bias_velocities, bias_velocities + n_layers);
+    m->max_batch = max_batch;
+    m->flags = flags;
+    *out = m;
+    return NERVA_OK;
+}
+
+void mlp_destroy(nerva_mlp *mlp) { delete mlp; }
+
+size_t mlp_workspace_bytes(const nerva_mlp *mlp, int32_t batch)
+{
+    if (!mlp || batch <= 0) return 0;
+    return static_cast<size_t>(make_layout(mlp, batch).bytes);
+}
+
+int mlp_workspace_layout(const nerva_mlp *mlp, int32_t batch, int64_t *layout_host)
+{
+    if (!mlp || !layout_host) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    if (batch <= 0) return fail(NERVA_ERR_ARGUMENT, "batch must be positive");
+    const Layout L = make_layout(mlp, batch);
+    layout_host[0] = L.ld;
+    for (size_t l = 0; l < mlp->layers.size(); ++l) {
+        layout_host[1 + 4 * l + 0] = L.A[l];
+        layout_host[1 + 4 * l + 1] = L.dZ[l];
+        layout_host[1 + 4 * l + 2] = L.g[l];
+        layout_host[1 + 4 * l + 3] = L.db[l];
+    }
+    return NERVA_OK;
+}
+
+static int check_step_args(const nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, void *workspace,
+                           size_t workspace_bytes, Layout &L)
+{
+    if (!mlp || !X || !workspace) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    int rc = check_batch(batch, ldx, "ldx");
+    if (rc != NERVA_OK) return rc;
+    if (batch > mlp->max_batch) return fail(NERVA_ERR_SHAPE, "batch %d exceeds max_batch %d", batch, mlp->max_batch);
+    L = make_layout(mlp, batch);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(NERVA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < static_cast<size_t>(L.bytes))
+        return fail(NERVA_ERR_WORKSPACE, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)L.bytes);
+    return NERVA_OK;
+}
+
+static int forward_chain(const nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, char *ws, const Layout &L,
+                         hipStream_t s)
+{
+    const float *in = X;
+    int64_t ldin = ldx;
+    for (size_t l = 0; l < mlp->layers.size(); ++l) {
+        const nerva_layer *ly = mlp->layers[l];
+        float *A = reinterpret_cast<float *>(ws + L.A[l]);
+        SpmmArgs a{};
+        a.blocks = ly->plan;
+        a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
+        a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
+        a.rows = ly->rows; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
+        HIP_TRY(launch_spmm(a, s));
+        in = A;
+        ldin = L.ld;
+    }
+    return NERVA_OK;
+}
+
+int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, void *workspace, size_t workspace_bytes,
+                void *stream)
+{
+    Layout L;
+    int rc = check_step_args(mlp, X, ldx, batch, workspace, workspace_bytes, L);
+    if (rc != NERVA_OK) return rc;
+    return forward_chain(mlp, X, ldx, batch, static_cast<char *>(workspace), L, as_stream(stream));
+}
+
+int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
+                   float momentum, void *workspace, size_t workspace_bytes, float *loss_out, void *stream)
+{
+    Layout L;
+    int rc = check_step_args(mlp, X, ldx, batch, workspace, workspace_bytes, L);
+    if (rc != NERVA_OK) return rc;
+    if (!labels) return fail(NERVA_ERR_ARGUMENT, "labels is null");
+    hipStream_t s = as_stream(stream);
+    char *ws = static_cast<char *>(workspace);
+    const int n = static_cast<int>(mlp->layers.size());
+    const bool fused = !(mlp->flags & NERVA_MLP_UNFUSED);
+    auto A = [&](int l) { return reinterpret_cast<float *>(ws + L.A[l]); };
+    auto dZ = [&](int l) { return reinterpret_cast<float *>(ws + L.dZ[l]); };
+
+    // feedforward
+    rc = forward_chain(mlp, X, ldx, batch, ws, L, s);
+    if (rc != NERVA_OK) return rc;
+
+    // loss gradient / batch size
+    const nerva_layer *last = mlp->layers[n - 1];
+    HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
+
+    // backpropagate and optimize, last layer first.  Layer l's transposed product runs before
+    // anything updates layer l's weights, so every gradient sees the weights of the step's start.
+    for (int l = n - 1; l >= 0; --l) {
+        nerva_layer *ly = mlp->layers[l];
+        if (l > 0) {
+            // dZ_{l-1} = (W_l^T dZ_l) * [A_{l-1} > 0]: the ReLU derivative of the layer below is
+            // applied as the transposed product is stored
+            SpmmArgs t{};
+            t.blocks = ly->plan_t;
+            t.indptr = ly->indptr_t; t.indices = ly->indices_t; t.values = ly->values_t;
+            t.X = dZ(l); t.ldx = L.ld; t.Y = dZ(l - 1); t.ldy = L.ld;
+            t.YM = A(l - 1); t.ldym = L.ld;
+            t.rows = ly->cols; t.batch = batch;
+            HIP_TRY(launch_spmm(t, s));
+        }
+        SddmmArgs g{};
+        g.blocks = ly->plan;
+        g.indptr = ly->indptr; g.indices = ly->indices;
+        g.dZ = dZ(l); g.lddz = L.ld;
+        g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
+        g.rows = ly->rows; g.batch = batch;
+        float *gl = reinterpret_cast<float *>(ws + L.g[l]);
+        float *dbl = reinterpret_cast<float *>(ws + L.db[l]);
+        if (fused) {
+            g.fused = 1; g.lr = lr; g.momentum = momentum;
+            g.values = ly->values; g.velocity = mlp->vel[l];
+            if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
+            g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
+            HIP_TRY(launch_sddmm(g, s));
+        } else {
+            g.g = gl; g.db = dbl;
+            HIP_TRY(launch_sddmm(g, s));
+            HIP_TRY(launch_momentum(ly->values, mlp->vel[l], gl, ly->nnz, lr, momentum, s));
+            if (ly->bias) HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], dbl, ly->rows, lr, momentum, s));
+            if (l > 0) HIP_TRY(launch_gather(ly->values_t, ly->values, ly->perm, ly->nnz, s));
+        }
+    }
+    return NERVA_OK;
+}
+
+int nerva_copy_f32(float *dst, const float *src, int64_t n, void *stream)
+{
+    if (n < 0 || (n > 0 && (!dst || !src))) return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    HIP_TRY(launch_copy(dst, src, n, as_stream(stream)));
+    return NERVA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal launch interface between the C ABI (api.hip) and the gfx950 kernels (kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nerva {
+
+constexpr int kWavesPerBlock = 16;   // 1024 threads
+
+// Static partition of the rows of a CSR matrix over work-groups, built once per pattern.
+// A work-group of kWavesPerBlock waves serves (kWavesPerBlock >> lg) rows, 2^lg waves per
+// row, each wave taking a contiguous share of the row's stored entries.
+struct RowBlocks {
+    const int32_t *row_order;    // [rows] row ids, grouped by lg (descending)
+    const int32_t *block_first;  // [n_blocks] first slot of row_order served by the block
+    const int32_t *block_info;   // [n_blocks] lg | (rows served << 8)
+    int32_t n_blocks;
+};
+
+// Y = epilogue( W * gather(X) ) for a CSR matrix W (rows x cols); also used on the CSC
+// mirror, where "rows" are W's columns.
+struct SpmmArgs {
+    RowBlocks blocks;
+    const int32_t *indptr;   // [rows+1]
+    const int32_t *indices;  // [nnz]
+    const float *values;     // [nnz]
+    const float *bias;       // [rows] or nullptr
+    const float *X;          // gathered operand, (cols, ldx)
+    int64_t ldx;
+    const float *XM;         // optional (cols, ldxm): operand row j is X[j,c] * [XM[j,c] > 0]
+    int64_t ldxm;
+    float *Y;                // (rows, ldy)
+    int64_t ldy;
+    const float *YM;         // optional (rows, ldym): result is multiplied by [YM[i,c] > 0]
+    int64_t ldym;
+    int32_t rows;
+    int32_t batch;
+    int32_t relu;            // clamp the result at zero
+};
+hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s);
+
+// g[p] = <dZ[row(p),:], X[indices[p],:]>, db[i] = sum_c dZ[i,c]; optionally followed, inside
+// the same kernel, by the momentum step on values/velocity (and bias/bias_velocity).
+struct SddmmArgs {
+    RowBlocks blocks;
+    const int32_t *indptr;
+    const int32_t *indices;
+    const float *dZ;         // (rows, lddz)
+    int64_t lddz;
+    const float *ZM;         // optional (rows, ldzm): dZ is multiplied by [ZM > 0]
+    int64_t ldzm;
+    const float *X;          // (cols, ldx)
+    int64_t ldx;
+    float *g;                // [nnz] or nullptr
+    float *db;               // [rows] or nullptr
+    int32_t rows;
+    int32_t batch;
+    int32_t skip_products;   // only db is wanted: do not touch indptr/indices/X
+    // fused momentum step (fused != 0): g/db are not stored unless non-null
+    int32_t fused;
+    float lr, momentum;
+    float *values;           // [nnz]
+    float *velocity;         // [nnz]
+    float *values_t;         // mirror values or nullptr
+    const int32_t *pos_t;    // CSR position -> mirror position (needed iff values_t)
+    float *bias;             // [rows] or nullptr
+    float *bias_velocity;    // [rows] or nullptr
+};
+hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
+
+hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu,
+                           hipStream_t s);
+// values_t[q] = values[perm[q]]
+hipError_t launch_gather(float *values_t, const float *values, const int32_t *perm, int64_t n,
+                         hipStream_t s);
+hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels, int32_t classes,
+                             int32_t batch, float *dZ, int64_t lddz, float *loss, hipStream_t s);
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
+
+}  // namespace nerva

@@ -1,0 +1,643 @@
+// gfx950 kernels of the truly sparse MLP training step.
+//
+// Mapping shared by the sparse kernels: lanes of a 64-wide wavefront run along the batch
+// dimension, so every gather of a dense row is one contiguous, coalesced read (one example
+// per column, batch contiguous).  Row pointers, column indices and weights are wave-uniform
+// and travel through the scalar path.  Rows are handed to work-groups by a static partition
+// (RowBlocks) that gives long rows several waves, each with a contiguous share of the row's
+// stored entries; partial sums of one row meet in LDS and are added in a fixed order.  There
+// are no float atomics: every output element is produced by one lane in one order, so results
+// are bit-reproducible from run to run.
+#include "kernels.h"
+
+namespace nerva {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = kWave * kWavesPerBlock;
+
+__device__ __forceinline__ int wave_in_block()
+{
+    return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6));
+}
+
+__device__ __forceinline__ float4 keep_where_positive(float4 x, float4 m)
+{
+    x.x = m.x > 0.f ? x.x : 0.f;
+    x.y = m.y > 0.f ? x.y : 0.f;
+    x.z = m.z > 0.f ? x.z : 0.f;
+    x.w = m.w > 0.f ? x.w : 0.f;
+    return x;
+}
+__device__ __forceinline__ float keep_where_positive(float x, float m) { return m > 0.f ? x : 0.f; }
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+
+// Data-parallel-primitive move: lane l receives x from the lane that CTRL names; lanes in rows
+// not selected by ROW_MASK receive 0.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false));
+}
+
+// Sum over each row of 16 lanes, all 64 lanes active; every lane of a row gets the same bits.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp<0xB1>(x);   // quad_perm [1,0,3,2]
+    x += dpp<0x4E>(x);   // quad_perm [2,3,0,1]
+    x += dpp<0x141>(x);  // row_half_mirror
+    x += dpp<0x140>(x);  // row_mirror
+    return x;
+}
+
+// Sum over groups of G lanes (16: per row; 64: whole wave, returned wave-uniform).
+template <int G>
+__device__ __forceinline__ float group_sum(float x)
+{
+    x = row16_sum(x);
+    if constexpr (G == 64) {
+        x += dpp<0x142, 0xA>(x);  // row_bcast15 into rows 1 and 3
+        x += dpp<0x143, 0xC>(x);  // row_bcast31 into rows 2 and 3
+        x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+    }
+    return x;
+}
+
+// The momentum step of one element; the same expression in the fused and the stand-alone path.
+__device__ __forceinline__ void momentum_step(float &w, float &v, float g, float lr, float mu)
+{
+    v = fmaf(mu, v, -(lr * g));
+    w = w + v;
+}
+
+// Which row, and which share of it, the calling wave serves.
+struct WaveTask {
+    int row;    // -1: nothing to do
+    int part;   // share index inside the row
+    int lg;     // log2(waves per row), uniform over the work-group
+};
+__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b)
+{
+    const int info = b.block_info[blockIdx.x];
+    const int first = b.block_first[blockIdx.x];
+    const int w = wave_in_block();
+    WaveTask t;
+    t.lg = info & 0xff;
+    const int slot = w >> t.lg;
+    t.part = w & ((1 << t.lg) - 1);
+    t.row = slot < (info >> 8) ? b.row_order[first + slot] : -1;
+    return t;
+}
+
+// Address of row j of a dense matrix whose rows are ld_bytes apart, kept in scalar registers:
+// the readfirstlane fences stop the compiler from folding the per-lane column offset into a
+// 64-bit vector multiply-add, so the gather uses the scalar-base + 32-bit lane offset form.
+typedef const __attribute__((address_space(1))) char *gmem_ptr;  // global (device) memory
+__device__ __forceinline__ gmem_ptr row_base(const void *base, int j, uint32_t ld_bytes)
+{
+    const uint64_t addr = reinterpret_cast<uint64_t>(base) + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ld_bytes;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(addr));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(addr >> 32));
+    return reinterpret_cast<gmem_ptr>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+template <typename V>
+__device__ __forceinline__ V gload(gmem_ptr row, uint32_t byte_offset)
+{
+    return *reinterpret_cast<const __attribute__((address_space(1))) V *>(row + byte_offset);
+}
+
+template <int VEC> struct Pack;
+template <> struct Pack<4> { using type = float4; };
+template <> struct Pack<1> { using type = float; };
+
+__device__ __forceinline__ void fma_into(float (&acc)[4], float w, float4 x)
+{
+    acc[0] = fmaf(w, x.x, acc[0]);
+    acc[1] = fmaf(w, x.y, acc[1]);
+    acc[2] = fmaf(w, x.z, acc[2]);
+    acc[3] = fmaf(w, x.w, acc[3]);
+}
+__device__ __forceinline__ void fma_into(float (&acc)[1], float w, float x) { acc[0] = fmaf(w, x, acc[0]); }
+
+// U consecutive stored entries: all index/weight fetches, then all gathers, then the FMAs, so
+// that U*NV reads are in flight per wave.
+template <int VEC, int NV, bool XMASK, int U>
+__device__ __forceinline__ void spmm_step(const SpmmArgs &a, int p, uint32_t ldxb, uint32_t ldmb,
+                                          const uint32_t (&off)[NV], float (&acc)[NV][VEC])
+{
+    using V = typename Pack<VEC>::type;
+    int j[U];
+    float w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        j[u] = a.indices[p + u];
+        w[u] = a.values[p + u];
+    }
+    V x[U][NV];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const gmem_ptr xr = row_base(a.X, j[u], ldxb);
+#pragma unroll
+        for (int t = 0; t < NV; ++t) x[u][t] = gload<V>(xr, off[t]);
+        if constexpr (XMASK) {
+            const gmem_ptr mr = row_base(a.XM, j[u], ldmb);
+#pragma unroll
+            for (int t = 0; t < NV; ++t) x[u][t] = keep_where_positive(x[u][t], gload<V>(mr, off[t]));
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int t = 0; t < NV; ++t) fma_into(acc[t], w[u], x[u][t]);
+}
+
+// ---------------------------------------------------------------------------------------
+// SpMM.  VEC = floats per lane access (4: 16-byte accesses, needs leading dimensions that are
+// multiples of 4 and 16-byte aligned bases; 1: anything).  A wave covers 64*VEC*NV columns;
+// blockIdx.y walks over column tiles.
+// ---------------------------------------------------------------------------------------
+template <int VEC, int NV, bool XMASK>
+__global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
+{
+    constexpr int U = NV >= 4 ? 2 : (NV == 2 ? 4 : 8);
+    __shared__ float red[kWavesPerBlock][NV][VEC][kWave];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const WaveTask task = wave_task(a.blocks);
+    const int col_base = blockIdx.y * (kWave * VEC * NV);
+
+    // Lanes whose columns lie beyond the batch re-read the tile's first columns and are never stored.
+    // A 4-wide access that starts below `batch` stays inside the row: ld is a multiple of 4 and >= batch.
+    int col[NV];
+    bool on[NV];
+    uint32_t off[NV];
+    float acc[NV][VEC];
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+        col[t] = col_base + (t * kWave + lane) * VEC;
+        on[t] = col[t] < a.batch;
+        off[t] = static_cast<uint32_t>(on[t] ? col[t] : col_base) * 4u;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[t][k] = 0.f;
+    }
+
+    if (task.row >= 0) {
+        const int p0 = a.indptr[task.row];
+        const int p1 = a.indptr[task.row + 1];
+        const int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
+        int p = p0 + task.part * per;
+        const int pe = min(p + per, p1);
+        const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
+        const uint32_t ldmb = XMASK ? static_cast<uint32_t>(a.ldxm) * 4u : 0u;
+        for (; p + U <= pe; p += U) spmm_step<VEC, NV, XMASK, U>(a, p, ldxb, ldmb, off, acc);
+        if constexpr (U >= 8)
+            if (p + 4 <= pe) { spmm_step<VEC, NV, XMASK, 4>(a, p, ldxb, ldmb, off, acc); p += 4; }
+        if constexpr (U >= 4)
+            if (p + 2 <= pe) { spmm_step<VEC, NV, XMASK, 2>(a, p, ldxb, ldmb, off, acc); p += 2; }
+        if (p < pe) spmm_step<VEC, NV, XMASK, 1>(a, p, ldxb, ldmb, off, acc);
+    }
+
+    if (task.lg > 0) {  // uniform over the work-group
+        if (task.part != 0) {
+#pragma unroll
+            for (int t = 0; t < NV; ++t)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) red[wv][t][k][lane] = acc[t][k];
+        }
+        __syncthreads();
+        if (task.part == 0) {
+            for (int s = 1; s < (1 << task.lg); ++s)
+#pragma unroll
+                for (int t = 0; t < NV; ++t)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[t][k] += red[wv + s][t][k][lane];
+        }
+    }
+    if (task.row < 0 || task.part != 0) return;
+
+    const float b = a.bias ? a.bias[task.row] : 0.f;
+    float *yr = a.Y + static_cast<int64_t>(task.row) * a.ldy;
+    const float *ym = a.YM ? a.YM + static_cast<int64_t>(task.row) * a.ldym : nullptr;
+#pragma unroll
+    for (int t = 0; t < NV; ++t) {
+        if (!on[t]) continue;
+        float y[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            y[k] = acc[t][k] + b;
+            if (a.relu) y[k] = y[k] > 0.f ? y[k] : 0.f;
+        }
+        if constexpr (VEC == 4) {
+            if (col[t] + 4 <= a.batch) {
+                float4 o = make_float4(y[0], y[1], y[2], y[3]);
+                if (ym) o = keep_where_positive(o, ld4(ym + col[t]));
+                st4(yr + col[t], o);
+            } else {
+                for (int k = 0; k < 4; ++k)
+                    if (col[t] + k < a.batch) {
+                        float o = y[k];
+                        if (ym) o = keep_where_positive(o, ym[col[t] + k]);
+                        yr[col[t] + k] = o;
+                    }
+            }
+        } else {
+            float o = y[0];
+            if (ym) o = keep_where_positive(o, ym[col[t]]);
+            yr[col[t]] = o;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// SDDMM.  The row of dZ stays in registers; the wave is cut into 64/G groups of G lanes, each
+// group computing the dot product of one stored entry at a time (lanes along the batch, 4
+// columns per lane and tile, NV tiles: G*4*NV >= batch), reduced inside the group with DPP
+// moves.  Results of up to 64 consecutive entries are collected one per lane, so the store of
+// g -- or the fused momentum step on values/velocity -- is a coalesced access.
+// EXACT4: batch is a multiple of 4 (no column tail inside a 4-wide access).
+// Lanes whose columns lie beyond the batch hold dZ = 0 and re-read columns 0..3 of the row.
+// ---------------------------------------------------------------------------------------
+template <int G, int NV, bool EXACT4>
+__global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
+{
+    constexpr int NG = kWave / G;
+    constexpr int UI = NV >= 4 ? 2 : 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const WaveTask task = wave_task(a.blocks);
+    if (task.row < 0) return;
+    const int row = task.row;
+    const int grp = lane / G;
+    const int lig = lane % G;
+
+    float4 dz[NV];
+    uint32_t off[NV];
+    {
+        const float *zr = a.dZ + static_cast<int64_t>(row) * a.lddz;
+        const float *zm = a.ZM ? a.ZM + static_cast<int64_t>(row) * a.ldzm : nullptr;
+#pragma unroll
+        for (int t = 0; t < NV; ++t) {
+            const int c = (t * G + lig) * 4;
+            dz[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+            off[t] = 0u;
+            if (c < a.batch) {
+                off[t] = static_cast<uint32_t>(c) * 4u;
+                dz[t] = ld4(zr + c);
+                if (zm) dz[t] = keep_where_positive(dz[t], ld4(zm + c));
+                if constexpr (!EXACT4) {
+                    if (c + 1 >= a.batch) dz[t].y = 0.f;
+                    if (c + 2 >= a.batch) dz[t].z = 0.f;
+                    if (c + 3 >= a.batch) dz[t].w = 0.f;
+                }
+            }
+        }
+    }
+
+    if (task.part == 0 && (a.db || (a.fused && a.bias))) {
+        float s = 0.f;
+#pragma unroll
+        for (int t = 0; t < NV; ++t) s += (dz[t].x + dz[t].y) + (dz[t].z + dz[t].w);
+        s = group_sum<G>(s);
+        if (lane == 0) {
+            if (a.db) a.db[row] = s;
+            if (a.fused && a.bias) {
+                float w = a.bias[row], v = a.bias_velocity[row];
+                momentum_step(w, v, s, a.lr, a.momentum);
+                a.bias[row] = w;
+                a.bias_velocity[row] = v;
+            }
+        }
+    }
+    if (a.skip_products) return;
+
+    const int p0 = a.indptr[row];
+    const int p1 = a.indptr[row + 1];
+    int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
+    per = (per + NG - 1) / NG * NG;
+    const int s0 = p0 + task.part * per;
+    const int s1 = min(s0 + per, p1);
+    const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
+    const char *Xb = reinterpret_cast<const char *>(a.X);
+    const int q_mine = lig * NG + grp;  // slot of this lane inside a chunk of 64 entries
+    const int bperm_base = grp * G * 4;
+
+    for (int pc = s0; pc < s1; pc += kWave) {
+        const int n = min(kWave, s1 - pc);
+        const int my_j = q_mine < n ? a.indices[pc + q_mine] : 0;
+        const int iters = (n + NG - 1) / NG;
+        float res = 0.f;
+        // UI entries per group and pass: all index moves, then all gathers, then the dot products.
+        // Passes may run past `iters` (UI divides G): such slots read a valid row and land in lanes
+        // that are not stored.
+        for (int it0 = 0; it0 < iters; it0 += UI) {
+            float4 x[UI][NV];
+#pragma unroll
+            for (int u = 0; u < UI; ++u) {
+                // group `grp` works on slot it*NG+grp, whose column index sits in lane grp*G+it
+                const int it = it0 + u;
+                if constexpr (G == kWave) {
+                    const gmem_ptr xr = row_base(a.X, __builtin_amdgcn_readlane(my_j, it), ldxb);
+#pragma unroll
+                    for (int t = 0; t < NV; ++t) x[u][t] = gload<float4>(xr, off[t]);
+                } else {
+                    const int j = __builtin_amdgcn_ds_bpermute(bperm_base + it * 4, my_j);
+                    const char *xr = Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb;
+#pragma unroll
+                    for (int t = 0; t < NV; ++t) x[u][t] = *reinterpret_cast<const float4 *>(xr + off[t]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UI; ++u) {
+                float part = 0.f;
+#pragma unroll
+                for (int t = 0; t < NV; ++t) {
+                    if constexpr (!EXACT4) {
+                        // padding columns inside the access may hold anything, also NaN: drop them
+                        const int c = (t * G + lig) * 4;
+                        if (c + 1 >= a.batch) x[u][t].y = 0.f;
+                        if (c + 2 >= a.batch) x[u][t].z = 0.f;
+                        if (c + 3 >= a.batch) x[u][t].w = 0.f;
+                        if (c >= a.batch) x[u][t].x = 0.f;
+                    }
+                    part = fmaf(dz[t].x, x[u][t].x, part);
+                    part = fmaf(dz[t].y, x[u][t].y, part);
+                    part = fmaf(dz[t].z, x[u][t].z, part);
+                    part = fmaf(dz[t].w, x[u][t].w, part);
+                }
+                part = group_sum<G>(part);
+                if (lig == it0 + u) res = part;
+            }
+        }
+        if (q_mine < n) {
+            const int p = pc + q_mine;
+            if (a.g) a.g[p] = res;
+            if (a.fused) {
+                float w = a.values[p], v = a.velocity[p];
+                momentum_step(w, v, res, a.lr, a.momentum);
+                a.values[p] = w;
+                a.velocity[p] = v;
+                if (a.values_t) a.values_t[a.pos_t[p]] = w;
+            }
+        }
+    }
+}
+
+// Any batch size, any leading dimension, any alignment: one column per lane and pass, both
+// operands re-read per stored entry.  The slow path behind sddmm_kernel.
+__global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const WaveTask task = wave_task(a.blocks);
+    if (task.row < 0) return;
+    const int row = task.row;
+    const float *zr = a.dZ + static_cast<int64_t>(row) * a.lddz;
+    const float *zm = a.ZM ? a.ZM + static_cast<int64_t>(row) * a.ldzm : nullptr;
+
+    if (task.part == 0 && (a.db || (a.fused && a.bias))) {
+        float s = 0.f;
+        for (int c = lane; c < a.batch; c += kWave) {
+            float z = zr[c];
+            if (zm) z = keep_where_positive(z, zm[c]);
+            s += z;
+        }
+        s = group_sum<kWave>(s);
+        if (lane == 0) {
+            if (a.db) a.db[row] = s;
+            if (a.fused && a.bias) {
+                float w = a.bias[row], v = a.bias_velocity[row];
+                momentum_step(w, v, s, a.lr, a.momentum);
+                a.bias[row] = w;
+                a.bias_velocity[row] = v;
+            }
+        }
+    }
+    if (a.skip_products) return;
+
+    const int p0 = a.indptr[row];
+    const int p1 = a.indptr[row + 1];
+    const int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
+    const int s0 = p0 + task.part * per;
+    const int s1 = min(s0 + per, p1);
+    for (int p = s0; p < s1; ++p) {
+        const float *xr = a.X + static_cast<int64_t>(a.indices[p]) * a.ldx;
+        float part = 0.f;
+        for (int c = lane; c < a.batch; c += kWave) {
+            float z = zr[c];
+            if (zm) z = keep_where_positive(z, zm[c]);
+            part = fmaf(z, xr[c], part);
+        }
+        part = group_sum<kWave>(part);
+        if (lane == 0) {
+            if (a.g) a.g[p] = part;
+            if (a.fused) {
+                float w = a.values[p], v = a.velocity[p];
+                momentum_step(w, v, part, a.lr, a.momentum);
+                a.values[p] = w;
+                a.velocity[p] = v;
+                if (a.values_t) a.values_t[a.pos_t[p]] = w;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Element-wise kernels
+// ---------------------------------------------------------------------------------------
+constexpr int kEwBlock = 256;
+
+__global__ __launch_bounds__(kEwBlock) void momentum_kernel(float *__restrict__ w, float *__restrict__ v,
+                                                            const float *__restrict__ g, int64_t n,
+                                                            float lr, float mu, int vec4)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vec4) {
+        const int64_t n4 = n >> 2;
+        for (int64_t k = i; k < n4; k += stride) {
+            float4 ww = ld4(w + 4 * k), vv = ld4(v + 4 * k);
+            const float4 gg = ld4(g + 4 * k);
+            momentum_step(ww.x, vv.x, gg.x, lr, mu);
+            momentum_step(ww.y, vv.y, gg.y, lr, mu);
+            momentum_step(ww.z, vv.z, gg.z, lr, mu);
+            momentum_step(ww.w, vv.w, gg.w, lr, mu);
+            st4(v + 4 * k, vv);
+            st4(w + 4 * k, ww);
+        }
+        i += n4 << 2;  // tail: elements 4*n4 .. n-1, one per thread of the first work-group
+        if (i < n) {
+            float ww = w[i], vv = v[i];
+            momentum_step(ww, vv, g[i], lr, mu);
+            v[i] = vv;
+            w[i] = ww;
+        }
+    } else {
+        for (; i < n; i += stride) {
+            float ww = w[i], vv = v[i];
+            momentum_step(ww, vv, g[i], lr, mu);
+            v[i] = vv;
+            w[i] = ww;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kEwBlock) void gather_kernel(float *__restrict__ dst, const float *__restrict__ src,
+                                                          const int32_t *__restrict__ perm, int64_t n)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride)
+        dst[i] = src[perm[i]];
+}
+
+__global__ __launch_bounds__(kEwBlock) void copy_kernel(float *__restrict__ dst, const float *__restrict__ src,
+                                                        int64_t n, int vec4)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vec4) {
+        const int64_t n4 = n >> 2;
+        for (int64_t k = i; k < n4; k += stride) st4(dst + 4 * k, ld4(src + 4 * k));
+        i += n4 << 2;
+        if (i < n) dst[i] = src[i];
+    } else {
+        for (; i < n; i += stride) dst[i] = src[i];
+    }
+}
+
+// Softmax cross-entropy, one column (example) per thread, a single work-group so that the
+// mean over the batch is summed in one fixed order.  The logits matrix is classes x batch:
+// small next to the layers that feed it.
+constexpr int kSoftmaxBlock = 1024;
+__global__ __launch_bounds__(kSoftmaxBlock) void softmax_ce_kernel(const float *Z, int64_t ldz,
+                                                                   const int32_t *__restrict__ labels,
+                                                                   int classes, int batch, float *dZ,
+                                                                   int64_t lddz, float *loss_out)
+{
+    __shared__ float partial[kSoftmaxBlock];
+    const float inv_b = 1.0f / static_cast<float>(batch);
+    float loss = 0.f;
+    for (int c = threadIdx.x; c < batch; c += kSoftmaxBlock) {
+        float m = -INFINITY;
+        for (int i = 0; i < classes; ++i) m = fmaxf(m, Z[static_cast<int64_t>(i) * ldz + c]);
+        float s = 0.f;
+        for (int i = 0; i < classes; ++i) s += expf(Z[static_cast<int64_t>(i) * ldz + c] - m);
+        const float lse = m + logf(s);
+        const int t = labels[c];
+        loss += lse - Z[static_cast<int64_t>(t) * ldz + c];
+        for (int i = 0; i < classes; ++i) {
+            const float p = expf(Z[static_cast<int64_t>(i) * ldz + c] - lse);
+            dZ[static_cast<int64_t>(i) * lddz + c] = (p - (i == t ? 1.f : 0.f)) * inv_b;
+        }
+    }
+    partial[threadIdx.x] = loss;
+    __syncthreads();
+    for (int w = kSoftmaxBlock / 2; w >= 1; w >>= 1) {
+        if (static_cast<int>(threadIdx.x) < w) partial[threadIdx.x] += partial[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && loss_out) *loss_out = partial[0] * inv_b;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int elementwise_blocks(int64_t work_items)
+{
+    int64_t b = (work_items + kEwBlock - 1) / kEwBlock;
+    if (b < 1) b = 1;
+    if (b > 256 * 32) b = 256 * 32;  // 256 compute units; grid-stride beyond that
+    return static_cast<int>(b);
+}
+
+template <int VEC, int NV>
+hipError_t spmm_go(const SpmmArgs &a, hipStream_t s)
+{
+    const int tile = kWave * VEC * NV;
+    dim3 grid(a.blocks.n_blocks, (a.batch + tile - 1) / tile);
+    if (a.XM)
+        hipLaunchKernelGGL((spmm_kernel<VEC, NV, true>), grid, dim3(kBlock), 0, s, a);
+    else
+        hipLaunchKernelGGL((spmm_kernel<VEC, NV, false>), grid, dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int G, int NV>
+hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
+{
+    dim3 grid(a.blocks.n_blocks);
+    if (a.batch % 4 == 0)
+        hipLaunchKernelGGL((sddmm_kernel<G, NV, true>), grid, dim3(kBlock), 0, s, a);
+    else
+        hipLaunchKernelGGL((sddmm_kernel<G, NV, false>), grid, dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
+{
+    if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    bool vec = a.ldx % 4 == 0 && a.ldy % 4 == 0 && aligned16(a.X) && aligned16(a.Y);
+    if (a.XM) vec = vec && a.ldxm % 4 == 0 && aligned16(a.XM);
+    if (a.YM) vec = vec && a.ldym % 4 == 0 && aligned16(a.YM);
+    if (vec) {
+        if (a.batch <= 256) return spmm_go<4, 1>(a, s);
+        if (a.batch <= 512) return spmm_go<4, 2>(a, s);
+        return spmm_go<4, 4>(a, s);
+    }
+    if (a.batch <= 64) return spmm_go<1, 1>(a, s);
+    if (a.batch <= 128) return spmm_go<1, 2>(a, s);
+    return spmm_go<1, 4>(a, s);
+}
+
+hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
+{
+    if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    bool vec = a.lddz % 4 == 0 && aligned16(a.dZ);
+    if (!a.skip_products) vec = vec && a.ldx % 4 == 0 && aligned16(a.X);
+    if (a.ZM) vec = vec && a.ldzm % 4 == 0 && aligned16(a.ZM);
+    if (vec && a.batch <= 1024) {
+        if (a.batch <= 64) return sddmm_go<16, 1>(a, s);
+        if (a.batch <= 128) return sddmm_go<16, 2>(a, s);
+        if (a.batch <= 256) return sddmm_go<16, 4>(a, s);
+        if (a.batch <= 512) return sddmm_go<64, 2>(a, s);
+        return sddmm_go<64, 4>(a, s);
+    }
+    hipLaunchKernelGGL(sddmm_generic, dim3(a.blocks.n_blocks), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int vec4 = aligned16(w) && aligned16(v) && aligned16(g);
+    hipLaunchKernelGGL(momentum_kernel, dim3(elementwise_blocks(vec4 ? (n + 3) / 4 : n)), dim3(kEwBlock), 0, s,
+                       w, v, g, n, lr, mu, vec4);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(float *values_t, const float *values, const int32_t *perm, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(gather_kernel, dim3(elementwise_blocks(n)), dim3(kEwBlock), 0, s, values_t, values, perm, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels, int32_t classes, int32_t batch,
+                             float *dZ, int64_t lddz, float *loss, hipStream_t s)
+{
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(kSoftmaxBlock), 0, s, Z, ldz, labels, classes, batch, dZ,
+                       lddz, loss);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int vec4 = aligned16(dst) && aligned16(src);
+    hipLaunchKernelGGL(copy_kernel, dim3(elementwise_blocks(vec4 ? (n + 3) / 4 : n)), dim3(kEwBlock), 0, s, dst, src,
+                       n, vec4);
+    return hipGetLastError();
+}
+
+}  // namespace nerva

@@ -1,0 +1,259 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bar: index structure bit-exact; fp32 values within 1e-5 of the oracle, normalised by the sum
+of the absolute values of the terms of each result (S, returned by the oracle).  Elements
+whose S is zero (empty rows) must match exactly.
+"""
+import numpy as np
+import pytest
+
+from paper_2407_17437_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def nb():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2407_17437_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    return torch
+
+
+def close(got, ref, S, tol=TOL, what=""):
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values in the GPU result"
+    err = np.abs(got - ref)
+    bound = tol * np.asarray(S, dtype=np.float64)
+    bad = err > bound
+    if bad.any():
+        k = np.unravel_index(np.argmax(err - bound), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} of {err.size} elements off; worst at {k}: "
+                             f"gpu={got[k]!r} oracle={ref[k]!r} err={err[k]:.3e} allowed={bound[k]:.3e}")
+    return float((err / np.maximum(bound / tol, 1e-300)).max()) if err.size else 0.0
+
+
+def raw_i32(nb, torch, addr, n):
+    """Copy n int32 from a raw device address (bit copy through the library's copy kernel)."""
+    out = torch.empty(max(n, 1), dtype=torch.float32, device="cuda")
+    if n:
+        nb._check(nb.lib.nerva_copy_f32(out.data_ptr(), addr, n, None))
+    torch.cuda.synchronize()
+    return out[:n].view(torch.int32).cpu().numpy()
+
+
+def raw_f32(nb, torch, addr, n):
+    out = torch.empty(max(n, 1), dtype=torch.float32, device="cuda")
+    if n:
+        nb._check(nb.lib.nerva_copy_f32(out.data_ptr(), addr, n, None))
+    torch.cuda.synchronize()
+    return out[:n].cpu().numpy()
+
+
+def layer_case(rows, cols, density, seed, relu=False, bias=True):
+    nnz = wl.round_half_up(density * rows * cols)
+    indptr, indices = wl.uniform_pattern(rows, cols, nnz, seed)
+    rng = np.random.default_rng(seed + 1)
+    values = wl.init_values(indptr, seed + 2)
+    b = (rng.standard_normal(rows) * 0.5).astype(np.float32) if bias else np.zeros(rows, dtype=np.float32)
+    return wl.SparseLayerData(rows, cols, indptr, indices, values, b, relu)
+
+
+# (rows, cols, density, batch, ld or None): several tiles, ragged tails, empty rows, every kernel variant
+SHAPES = [
+    (7, 5, 0.3, 3, None),            # tiny, batch not a multiple of 4
+    (33, 65, 0.2, 100, None),        # the paper's batch size
+    (130, 257, 0.05, 64, None),
+    (64, 96, 1.0, 37, None),         # fully dense pattern
+    (50, 40, 0.0, 8, None),          # empty matrix
+    (300, 200, 0.5, 100, 101),       # odd leading dimension -> scalar kernels
+    (200, 300, 0.1, 256, None),
+    (96, 128, 0.3, 300, None),       # two tiles per lane
+    (128, 512, 0.2, 1024, None),     # four tiles per lane
+    (40, 64, 0.3, 1100, None),       # beyond one column tile
+    (1024, 3072, 0.01, 100, None),   # first layer of the paper's MLP at 99 % sparsity
+    (10, 512, 0.1, 100, None),       # its last layer
+]
+
+
+@pytest.mark.parametrize("rows,cols,density,batch,ld", SHAPES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_forward_parity(nb, torch_mod, oracle, rows, cols, density, batch, ld, relu):
+    torch = torch_mod
+    lay = layer_case(rows, cols, density, seed=rows + cols, relu=relu)
+    X = np.random.default_rng(batch).standard_normal((cols, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay)
+    Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld)
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(rows, cols, lay.indptr, lay.indices, lay.values, lay.bias, X, relu)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    # padding columns of the output were not written
+    full = Yd._base if Yd._base is not None else Yd
+    assert torch.isnan(full.view(rows, -1)[:, batch:]).all()
+    L.close()
+
+
+@pytest.mark.parametrize("rows,cols,density,batch,ld", SHAPES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_backward_parity(nb, torch_mod, oracle, rows, cols, density, batch, ld, relu):
+    torch = torch_mod
+    lay = layer_case(rows, cols, density, seed=rows * 3 + cols, relu=relu)
+    rng = np.random.default_rng(batch + 1)
+    X = rng.standard_normal((cols, batch)).astype(np.float32)
+    dY = rng.standard_normal((rows, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay)
+    Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld); dYd = nb.to_dense(dY, ld=ld)
+    dXd = nb.dense(cols, batch, ld=ld)
+    g = torch.full((max(lay.nnz, 1),), float("nan"), device="cuda")[:lay.nnz]
+    db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    dZ = oracle.relu_backward(dY, Y) if relu else dY            # mask from the GPU's own output
+    dX, SdX = oracle.spmm_t(rows, cols, lay.indptr, lay.indices, lay.values, dZ)
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, lay.indptr, lay.indices, dZ, X)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    close(g.cpu().numpy(), gr, Sg, what="dvalues")
+    close(db.cpu().numpy(), dbr, Sdb, what="dbias")
+    # pieces can be asked for separately
+    db2 = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_backward(L.handle, None, Yd, dYd, None, None, db2, batch)
+    torch.cuda.synchronize()
+    assert torch.equal(db2, db)
+    L.close()
+
+
+def test_backward_sees_changed_values(nb, torch_mod, oracle):
+    """values[] changed behind the library's back: dX must use the new values."""
+    torch = torch_mod
+    lay = layer_case(64, 48, 0.3, seed=9)
+    rng = np.random.default_rng(2)
+    dY = rng.standard_normal((64, 20)).astype(np.float32)
+    L = nb.SparseLinear(lay)
+    dYd = nb.to_dense(dY); dXd = nb.dense(48, 20)
+    new_vals = rng.standard_normal(lay.nnz).astype(np.float32)
+    L.values.copy_(torch.as_tensor(new_vals))
+    nb.sparse_linear_backward(L.handle, None, None, dYd, dXd, None, None, 20)
+    torch.cuda.synchronize()
+    dX, S = oracle.spmm_t(64, 48, lay.indptr, lay.indices, new_vals, dY)
+    close(dXd.cpu().numpy(), dX, S, what="dX after external update")
+    L.close()
+
+
+@pytest.mark.parametrize("rows,cols,density", [(7, 5, 0.3), (130, 257, 0.05), (64, 96, 1.0), (50, 40, 0.0),
+                                               (1024, 3072, 0.01)])
+def test_mirror_is_the_transposed_pattern_bit_exact(nb, torch_mod, rows, cols, density):
+    torch = torch_mod
+    lay = layer_case(rows, cols, density, seed=5)
+    L = nb.SparseLinear(lay)
+    ip_t, ix_t, v_t, perm = nb.sparse_linear_mirror(L.handle)
+    indptr_t = raw_i32(nb, torch, ip_t, cols + 1)
+    indices_t = raw_i32(nb, torch, ix_t, lay.nnz)
+    perm_h = raw_i32(nb, torch, perm, lay.nnz)
+    values_t = raw_f32(nb, torch, v_t, lay.nnz)
+    # expected: stable sort of the stored entries by column (rows ascending inside a column)
+    row_of = np.repeat(np.arange(rows, dtype=np.int32), np.diff(lay.indptr))
+    order = np.argsort(lay.indices, kind="stable")
+    exp_indptr = np.zeros(cols + 1, dtype=np.int32)
+    np.cumsum(np.bincount(lay.indices, minlength=cols), out=exp_indptr[1:])
+    assert np.array_equal(indptr_t, exp_indptr)
+    assert np.array_equal(indices_t, row_of[order])
+    assert np.array_equal(perm_h, order.astype(np.int32))
+    assert np.array_equal(values_t, lay.values[order])
+    # the caller's pattern arrays are untouched
+    assert np.array_equal(L.indptr.cpu().numpy(), lay.indptr) and np.array_equal(L.indices.cpu().numpy(), lay.indices)
+    L.close()
+
+
+def test_invalid_pattern_is_rejected_on_create(nb, torch_mod):
+    torch = torch_mod
+    lay = layer_case(16, 16, 0.3, seed=3)
+    bad = lay.indices.copy(); bad[1] = bad[0]
+    lay_bad = wl.SparseLayerData(16, 16, lay.indptr, bad, lay.values, lay.bias, False)
+    with pytest.raises(nb.NervaError) as e:
+        nb.SparseLinear(lay_bad)
+    assert e.value.code == nb.NERVA_ERR_CSR
+
+
+def test_shape_errors(nb, torch_mod):
+    lay = layer_case(16, 12, 0.3, seed=4)
+    L = nb.SparseLinear(lay)
+    X = nb.dense(12, 8); Y = nb.dense(16, 8)
+    with pytest.raises(nb.NervaError) as e:
+        nb.sparse_linear_forward(L.handle, X, Y, 64)       # batch larger than the leading dimension
+    assert e.value.code == nb.NERVA_ERR_SHAPE
+    with pytest.raises(nb.NervaError) as e:
+        nb.sparse_linear_forward(L.handle, X, Y, 0)
+    assert e.value.code == nb.NERVA_ERR_ARGUMENT
+    L.close()
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 1000, 1027, 314573])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_sgd_update_parity(nb, torch_mod, oracle, n, offset):
+    torch = torch_mod
+    rng = np.random.default_rng(n + offset)
+    w, v, g = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    pad = lambda a: torch.as_tensor(np.concatenate([np.zeros(offset, np.float32), a])).cuda()[offset:]
+    wd, vd, gd = pad(w), pad(v), pad(g)     # offset 1: not 16-byte aligned -> scalar kernel
+    nb.sgd_update_values(wd, vd, gd, n, 0.01, 0.9)
+    torch.cuda.synchronize()
+    wr, vr, Sw, Sv = oracle.momentum(w, v, g, 0.01, 0.9)
+    close(vd.cpu().numpy(), vr, Sv, what="velocity")
+    close(wd.cpu().numpy(), wr, Sw, what="values")
+    assert np.array_equal(gd.cpu().numpy(), g)
+
+
+@pytest.mark.parametrize("classes,batch", [(10, 100), (10, 1), (3, 7), (10, 1024), (100, 2500)])
+def test_softmax_ce_parity(nb, torch_mod, oracle, classes, batch):
+    torch = torch_mod
+    rng = np.random.default_rng(classes + batch)
+    Z = (rng.standard_normal((classes, batch)) * 3).astype(np.float32)
+    labels = rng.integers(0, classes, size=batch).astype(np.int32)
+    Zd = nb.to_dense(Z); dZd = nb.dense(classes, batch)
+    loss = torch.zeros(1, device="cuda"); lab = torch.as_tensor(labels).cuda()
+    nb.softmax_cross_entropy(Zd, lab, classes, batch, dZd, loss)
+    torch.cuda.synchronize()
+    lr, Sl, dZr, SdZ = oracle.softmax_ce(Z, labels)
+    close(dZd.cpu().numpy(), dZr, SdZ, what="dZ")
+    assert abs(float(loss.item()) - lr) <= TOL * Sl
+    # uniform logits: ln(classes)
+    Zd.zero_()
+    nb.softmax_cross_entropy(Zd, lab, classes, batch, dZd, loss)
+    assert abs(float(loss.item()) - np.log(classes)) < 1e-6 * np.log(max(classes, 2)) + 1e-7
+
+
+def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
+    """Power-law rows (one full row, many empty ones): every share count of the row partition."""
+    torch = torch_mod
+    z = wl.make_zipf_matrix(1024, 0.02, seed=5)
+    _, _, info = nb.nerva_plan_rows_host(1024, z.indptr)
+    assert len(set((info & 0xFF).tolist())) >= 3
+    for batch in (128, 100):
+        rng = np.random.default_rng(batch)
+        X = rng.standard_normal((1024, batch)).astype(np.float32)
+        dY = rng.standard_normal((1024, batch)).astype(np.float32)
+        L = nb.SparseLinear(z)
+        Xd = nb.to_dense(X); Yd = nb.dense(1024, batch); dYd = nb.to_dense(dY); dXd = nb.dense(1024, batch)
+        g = torch.empty(z.nnz, device="cuda"); db = torch.empty(1024, device="cuda")
+        nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+        nb.sparse_linear_backward(L.handle, Xd, None, dYd, dXd, g, db, batch)
+        torch.cuda.synchronize()
+        Y, S = oracle.spmm(1024, 1024, z.indptr, z.indices, z.values, z.bias, X, False)
+        close(Yd.cpu().numpy(), Y, S, what="Y")
+        dX, SdX = oracle.spmm_t(1024, 1024, z.indptr, z.indices, z.values, dY)
+        close(dXd.cpu().numpy(), dX, SdX, what="dX")
+        gr, Sg, dbr, Sdb = oracle.sddmm(1024, 1024, z.indptr, z.indices, dY, X)
+        close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+        L.close()

@@ -1,0 +1,128 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates CSR patterns, plans the row partition, and rejects bad arguments
+before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2407_17437_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nb():
+    from paper_2407_17437_amd import binding
+    return binding
+
+
+def test_header_symbols_are_exported(nb):
+    header = open(os.path.join(ROOT, "include", "nerva_sparse.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined"}
+    assert declared == set(nb.EXPORTS), declared ^ set(nb.EXPORTS)
+    for name in declared:
+        assert hasattr(nb.lib, name), name
+    assert "gfx950" in nb.build_info()
+
+
+def test_validate_csr_accepts_generated_patterns(nb):
+    for rows, cols, nnz in [(5, 7, 0), (5, 7, 35), (64, 33, 500)]:
+        indptr, indices = wl.uniform_pattern(rows, cols, nnz, seed=1)
+        assert nb.nerva_validate_csr_host(rows, cols, nnz, indptr, indices) == nb.NERVA_OK
+
+
+def test_validate_csr_rejects_broken_patterns(nb):
+    indptr, indices = wl.uniform_pattern(6, 9, 20, seed=2)
+    ok = lambda ip, ix, nnz=20, cols=9: nb.nerva_validate_csr_host(6, cols, nnz, ip, ix)
+    assert ok(indptr, indices) == 0
+    bad = indptr.copy(); bad[0] = 1
+    assert ok(bad, indices) == nb.NERVA_ERR_CSR and "indptr[0]" in nb.last_error()
+    bad = indptr.copy(); bad[3], bad[4] = bad[4] + 1, bad[3]
+    assert ok(bad, indices) == nb.NERVA_ERR_CSR
+    bad = indptr.copy(); bad[-1] = 19
+    assert ok(bad, indices) == nb.NERVA_ERR_CSR
+    bad = indices.copy(); bad[5] = 9
+    assert ok(indptr, bad) == nb.NERVA_ERR_CSR and "out of range" in nb.last_error()
+    bad = indices.copy(); bad[5] = -1
+    assert ok(indptr, bad) == nb.NERVA_ERR_CSR
+    # duplicate / unsorted inside a row
+    row = int(np.argmax(np.diff(indptr) >= 2)); p = indptr[row]
+    bad = indices.copy(); bad[p + 1] = bad[p]
+    assert ok(indptr, bad) == nb.NERVA_ERR_CSR and "ascending" in nb.last_error()
+    bad = indices.copy(); bad[p], bad[p + 1] = bad[p + 1], bad[p]
+    assert ok(indptr, bad) == nb.NERVA_ERR_CSR
+    assert ok(indptr, indices, nnz=21) == nb.NERVA_ERR_CSR
+    assert nb.lib.nerva_validate_csr_host(6, 9, 20, None, None) == nb.NERVA_ERR_ARGUMENT
+    assert nb.lib.nerva_validate_csr_host(-1, 9, 0, indptr.ctypes.data, None) == nb.NERVA_ERR_ARGUMENT
+
+
+def _check_plan(nb, indptr, rows):
+    order, first, info = nb.nerva_plan_rows_host(rows, indptr)
+    assert sorted(order.tolist()) == list(range(rows))            # every row exactly once
+    W = nb.NERVA_WAVES_PER_BLOCK
+    nnz = int(indptr[-1])
+    target = min(64, max(8, nnz // 16384))
+    covered = 0
+    prev_lg = 99
+    for f, inf in zip(first.tolist(), info.tolist()):
+        lg, n = inf & 0xFF, inf >> 8
+        assert 1 <= n <= (W >> lg) and f == covered
+        assert lg <= prev_lg                                       # heavy rows are served first
+        prev_lg = lg
+        for r in order[f:f + n]:
+            k = int(indptr[r + 1] - indptr[r])
+            per_wave = -(-k // (1 << lg))
+            assert per_wave <= target or (1 << lg) == W            # no wave above the target unless capped
+            if lg > 0:
+                assert -(-k // (1 << (lg - 1))) > target           # and no more waves than needed
+        covered += n
+    assert covered == rows
+    return order, first, info
+
+
+def test_row_plan_uniform_and_skewed(nb):
+    mlp = wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9)
+    for lay in mlp.layers:
+        _check_plan(nb, lay.indptr, lay.rows)
+    # layer 1 at 90 %: 307 entries per row on average -> a whole work-group per row
+    _, first, info = nb.nerva_plan_rows_host(1024, mlp.layers[0].indptr)
+    assert len(first) == 1024 and set((info & 0xFF).tolist()) == {4}
+    z = wl.make_zipf_matrix(1024, 0.02, seed=5)
+    order, first, info = _check_plan(nb, z.indptr, 1024)
+    assert len(set((info & 0xFF).tolist())) >= 3                   # several row classes in one matrix
+    empty = np.zeros(11, dtype=np.int32)
+    order, first, info = _check_plan(nb, empty, 10)
+    assert len(first) == 1 and info[0] == (10 << 8)
+
+
+def test_argument_errors_come_before_any_device_work(nb):
+    lib = nb.lib
+    h = ctypes.c_void_p()
+    assert lib.sparse_linear_create(None, 4, 4, 0, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_create(ctypes.addressof(h), 0, 4, 0, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_create(ctypes.addressof(h), 4, 4, 3, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_forward(None, None, 4, None, 4, 4, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_backward(None, None, 0, None, 0, None, 0, None, 0, None, None, 4, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sgd_update_values(None, None, None, 5, 0.1, 0.9, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sgd_update_values(None, None, None, -1, 0.1, 0.9, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sgd_update_values(None, None, None, 0, 0.1, 0.9, None) == nb.NERVA_OK       # empty update is a no-op
+    assert lib.softmax_cross_entropy(None, 4, None, 10, 4, None, 4, None, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.mlp_create(ctypes.addressof(h), 0, None, None, None, 4, 0) == nb.NERVA_ERR_ARGUMENT
+    assert lib.mlp_train_step(None, None, 4, None, 4, 0.1, 0.9, None, 0, None, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.mlp_workspace_bytes(None, 4) == 0
+    assert lib.nerva_copy_f32(None, None, 3, None) == nb.NERVA_ERR_ARGUMENT
+    assert nb.last_error() != ""
+    lib.sparse_linear_destroy(None)
+    lib.mlp_destroy(None)
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    import importlib
+    from paper_2407_17437_amd import binding
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        binding._load()
