@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-MLP training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A "step" is one call of mlp_train_step (feedforward, loss gradient, backpropagation, momentum
+update) on one mini-batch that is already resident in HBM.  The default workload is the
+paper's MLP 3072-1024-512-10 at 90 % sparsity, batch 100, one synthetic epoch of 50,000
+N(0,1) samples (500 steps).  Prints one JSON line with the throughput, the roofline position
+of the dominant kernel (HIP-event timing of every kernel of the step, taken in a second pass
+over the same steps) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+WORKLOADS = {
+    # name: (sizes, sparsity | None, er_density | None, batch, pool batches, description)
+    "cfg1": ((3072, 1024, 512, 10), 0.99, None, 100, 64, "MLP 3072-1024-512-10, 99% sparsity, batch 100"),
+    "cfg2": ((3072, 1024, 512, 10), 0.90, None, 100, 500,
+             "MLP 3072-1024-512-10, 90% sparsity, batch 100, one epoch of 50,000 synthetic samples"),
+    "cfg4": ((3072, 8192, 8192, 10), None, 0.01, 1024, 32,
+             "MLP 3072-8192-8192-10, global density 1% split by Erdos-Renyi, batch 1024"),
+}
+for _s in (0.5, 0.8, 0.9, 0.95, 0.99, 0.999):
+    WORKLOADS[f"sweep{_s}"] = ((3072, 1024, 512, 10), _s, None, 100, 64,
+                               f"MLP 3072-1024-512-10, {_s * 100:g}% sparsity, batch 100")
+
+
+def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
+    """Algorithmic HBM bytes of one launch: what the operation itself must read and write once
+    (fp32 values, int32 indices); gathers that hit in cache are not counted."""
+    m, k, nnz, n = layer.rows, layer.cols, layer.nnz, batch
+    kind = name.split("[")[0]
+    if kind == "spmm_forward":        # pattern + values, X in, Y out, bias
+        return 8 * nnz + 4 * (m + 1) + 4 * n * (k + m) + 4 * m
+    if kind == "spmm_transposed":     # mirror pattern + values, dZ in, dX out, ReLU mask of the layer below in
+        return 8 * nnz + 4 * (k + 1) + 4 * n * (m + k) + 4 * n * k
+    if kind == "sddmm_update":        # indices, dZ and X in; values and velocity read and written; biases
+        b = 4 * nnz + 4 * (m + 1) + 4 * n * (m + k) + 16 * nnz + 16 * m
+        return b + (8 * nnz if has_mirror_scatter else 0)
+    if kind == "sddmm":
+        return 4 * nnz + 4 * (m + 1) + 4 * n * (m + k) + 4 * nnz + 4 * m
+    if kind == "momentum_values":
+        return 20 * nnz
+    if kind == "momentum_bias":
+        return 20 * m
+    if kind == "mirror_refresh":
+        return 12 * nnz
+    if kind == "softmax_ce":
+        return 8 * n * m + 4 * n
+    return 0.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
+    ap.add_argument("--profile-steps", type=int, default=100, help="steps of the per-kernel event pass (0: skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0: skip)")
+    ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
+    ap.add_argument("--unfused", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2407_17437_amd import binding as nb
+    from paper_2407_17437_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    sizes, sparsity, er, batch, pool, desc = WORKLOADS[args.workload]
+    mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, pool, seed=3000)
+    ld = nb.padded_ld(batch)
+    Xd = torch.zeros((pool, sizes[0], ld), dtype=torch.float32, device="cuda")
+    Xd[:, :, :batch] = torch.as_tensor(Xs).cuda()
+    Td = torch.as_tensor(Ts).cuda()
+    M = nb.MLP(mlp, batch, nb.NERVA_MLP_UNFUSED if args.unfused else nb.NERVA_MLP_DEFAULT)
+    x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4
+    t_ptr, t_stride = Td.data_ptr(), batch * 4
+    lr, mu = 0.01, 0.9
+
+    def step(k: int) -> None:
+        b = k % pool
+        nb.mlp_train_step(M.handle, x_ptr + b * x_stride, ld, t_ptr + b * t_stride, batch, lr, mu, M.workspace, M.loss)
+
+    graphs = []
+    if args.graph > 0:
+        # graphs of `--graph` consecutive steps each, covering one cycle through the batch pool
+        assert pool % args.graph == 0, "--graph must divide the number of pooled batches"
+        for k in range(3):
+            step(k)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        for g0 in range(0, pool, args.graph):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for k in range(g0, g0 + args.graph):
+                    step(k)
+            graphs.append(g)
+
+    def run(first: int, count: int) -> None:
+        if not graphs:
+            for k in range(first, first + count):
+                step(k)
+        else:
+            assert first % args.graph == 0 and count % args.graph == 0
+            for i in range(first // args.graph, (first + count) // args.graph):
+                graphs[i % len(graphs)].replay()
+
+    K, W = args.steps, args.warmup
+    if graphs:
+        K = max(args.graph, K // args.graph * args.graph)
+        W = (W + args.graph - 1) // args.graph * args.graph
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, K)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    loss_end = float(M.loss.item())
+    assert np.isfinite(loss_end), "training diverged"
+    value = K * batch / sec
+
+    # ---- per-kernel HIP-event pass over the same steps (plain launches) -------------------
+    roofline = None
+    kernels = []
+    if args.profile_steps > 0:
+        P = min(args.profile_steps, K)
+        nb.mlp_profile_enable(M.handle, P)
+        for k in range(W + K, W + K + P):
+            step(k)
+        torch.cuda.synchronize()
+        steps_done, slots = nb.mlp_profile_read(M.handle)
+        nb.mlp_profile_enable(M.handle, 0)
+        for name, ms in slots:
+            l = int(name.split("[")[1].rstrip("]"))
+            byt = slot_bytes(name, M.layers[l], batch, has_mirror_scatter=(l > 0))
+            us = ms * 1e3 / max(steps_done, 1)
+            kernels.append({"kernel": name, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
+                            "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})
+        dom = max(kernels, key=lambda r: r["avg_us"])
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],
+                    "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": None,
+                    "timing": f"HIP events around each launch, {steps_done} steps"}
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        st = oracle.new_state(mlp.layers, np.float32)
+        t = time.perf_counter()
+        oracle.mlp_step(st, Xs[0], Ts[0], lr, mu, np.float32)
+        one = time.perf_counter() - t
+        n = int(max(2, min(pool - 1, args.cpu_seconds / max(one, 1e-6))))
+        t = time.perf_counter()
+        for k in range(1, 1 + n):
+            oracle.mlp_step(st, Xs[k % pool], Ts[k % pool], lr, mu, np.float32)
+        dt = time.perf_counter() - t
+        cpu = {"value": round(n * batch / dt, 1), "unit": "samples/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{n} training steps of batch {batch} on the same network and batches ({dt:.1f} s)",
+               "ms_per_step": round(dt / n * 1e3, 3)}
+
+    out = {
+        "metric": "sparse-MLP train samples/s", "value": round(value, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(sec / K * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "layer_nnz": [l.nnz for l in mlp.layers],
+                   "batch": batch, "lr": lr, "momentum": mu, "launch": f"hip graph of {args.graph} steps" if graphs else "stream",
+                   "fused_update": not args.unfused, "final_loss": round(loss_end, 5)},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "context": "paper: ~4x faster than masked PyTorch at 99% sparsity, CIFAR-10 MLP, Intel i7-6700 4 cores, MKL "
+                   "(abstract, Section 5.5, Appendix A); another machine, not a target",
+    }
+    print(json.dumps(out))
+    M.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

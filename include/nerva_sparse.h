@@ -196,6 +196,20 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
 int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch,
                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Per-kernel timing of mlp_train_step with HIP events, for benchmarks.  After
+ * mlp_profile_enable(mlp, max_steps > 0) the next max_steps training steps record a pair of
+ * events around every kernel launch on the step's stream (events are created on the fly: a
+ * profiled step allocates, must not be captured in a graph, and runs slower than a plain one).
+ * mlp_profile_read waits for the recorded events and returns, per launch slot of a step (in
+ * launch order), the summed elapsed milliseconds over the recorded steps; the slots keep their
+ * meaning until the next mlp_profile_enable.  mlp_profile_enable(mlp, 0) switches timing off
+ * and frees the events.  Slot names look like "spmm_forward[0]", "sddmm_update[2]".
+ *   n_slots_host, steps_host: HOST int32; ms_sum_host: HOST double[max_slots]. */
+int mlp_profile_enable(nerva_mlp *mlp, int32_t max_steps);
+int mlp_profile_read(nerva_mlp *mlp, int32_t max_slots, int32_t *n_slots_host,
+                     double *ms_sum_host, int32_t *steps_host);
+const char *mlp_profile_slot_name(const nerva_mlp *mlp, int32_t slot);
+
 /* Plain device copy dst[k] = src[k], k in [0, n): the known-size kernel that memory
  * traffic counters are calibrated against.  Not part of the training path. */
 int nerva_copy_f32(float *dst, const float *src, int64_t n, void *stream);

@@ -29,6 +29,7 @@ EXPORTS = [
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_workspace_bytes",
     "mlp_workspace_layout", "mlp_train_step", "mlp_forward", "nerva_copy_f32",
+    "mlp_profile_enable", "mlp_profile_read", "mlp_profile_slot_name",
 ]
 
 
@@ -64,6 +65,9 @@ def _load() -> ctypes.CDLL:
         "mlp_train_step": (ctypes.c_int, [vp, vp, i32, vp, i32, f32, f32, vp, sz, vp, vp]),
         "mlp_forward": (ctypes.c_int, [vp, vp, i32, i32, vp, sz, vp]),
         "nerva_copy_f32": (ctypes.c_int, [vp, vp, i64, vp]),
+        "mlp_profile_enable": (ctypes.c_int, [vp, i32]),
+        "mlp_profile_read": (ctypes.c_int, [vp, i32, vp, vp, vp]),
+        "mlp_profile_slot_name": (ctypes.c_char_p, [vp, i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -205,6 +209,18 @@ def mlp_forward(mlp: int, X, ldx: int, batch: int, workspace, stream=None) -> No
                            _stream(stream)))
 
 
+def mlp_profile_enable(mlp: int, max_steps: int) -> None:
+    _check(lib.mlp_profile_enable(mlp, max_steps))
+
+
+def mlp_profile_read(mlp: int, max_slots: int = 256):
+    """Returns (steps, [(slot name, summed milliseconds), ...])."""
+    n = ctypes.c_int32(0); steps = ctypes.c_int32(0)
+    ms = (ctypes.c_double * max_slots)()
+    _check(lib.mlp_profile_read(mlp, max_slots, ctypes.addressof(n), ms, ctypes.addressof(steps)))
+    return steps.value, [(lib.mlp_profile_slot_name(mlp, k).decode(), ms[k]) for k in range(n.value)]
+
+
 def nerva_copy_f32(dst, src, n: int, stream=None) -> None:
     _check(lib.nerva_copy_f32(_ptr(dst), _ptr(src), n, _stream(stream)))
 
@@ -235,6 +251,7 @@ class SparseLinear:
     """Device copies of one layer's arrays plus the library handle."""
 
     def __init__(self, layer_data, device="cuda"):
+        self.handle = None
         d = layer_data
         self.rows, self.cols, self.nnz = d.rows, d.cols, d.nnz
         self.relu = bool(d.relu)
@@ -260,6 +277,8 @@ class MLP:
     """A chain of SparseLinear layers, the library's MLP handle and its workspace."""
 
     def __init__(self, mlp_data, max_batch: int, flags: int = NERVA_MLP_DEFAULT, device="cuda"):
+        self.handle = None
+        self.layers = []
         self.layers = [SparseLinear(l, device) for l in mlp_data.layers]
         self.max_batch = max_batch
         self.handle = mlp_create([l.handle for l in self.layers], [l.velocity for l in self.layers],

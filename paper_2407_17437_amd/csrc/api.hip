@@ -63,12 +63,30 @@ struct nerva_layer {
     RowBlocks plan{}, plan_t{};
 };
 
+// Optional per-kernel timing of mlp_train_step: one pair of HIP events around every launch of
+// the first `max_steps` steps after mlp_profile_enable.
+struct StepProfiler {
+    bool on = false;
+    int32_t max_steps = 0, step = 0, slot = 0;
+    std::vector<std::string> names;    // one per launch of a step, in launch order
+    std::vector<hipEvent_t> events;    // [step][slot][begin, end], grown while recording
+    void release()
+    {
+        for (hipEvent_t e : events) (void)hipEventDestroy(e);
+        events.clear();
+        names.clear();
+        on = false;
+        step = slot = 0;
+    }
+};
+
 struct nerva_mlp {
     std::vector<nerva_layer *> layers;
     std::vector<float *> vel;
     std::vector<float *> bias_vel;
     int32_t max_batch = 0;
     int32_t flags = 0;
+    StepProfiler prof;
 };
 
 namespace {
@@ -167,6 +185,31 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->perm);
     (void)hipFree(l->pos_t);
 }
+
+// Brackets one launch with events while profiling is on; costs one branch otherwise.
+struct Timed {
+    StepProfiler &P;
+    hipStream_t s;
+    bool live;
+    Timed(StepProfiler &p, hipStream_t st, const char *kind, int layer) : P(p), s(st), live(p.on && p.step < p.max_steps)
+    {
+        if (!live) return;
+        if (P.step == 0) {
+            char buf[64];
+            snprintf(buf, sizeof buf, "%s[%d]", kind, layer);
+            P.names.push_back(buf);
+        }
+        hipEvent_t b = nullptr, e = nullptr;
+        if (hipEventCreate(&b) != hipSuccess || hipEventCreate(&e) != hipSuccess) { live = false; return; }
+        P.events.push_back(b);
+        P.events.push_back(e);
+        (void)hipEventRecord(b, s);
+    }
+    ~Timed()
+    {
+        if (live) (void)hipEventRecord(P.events.back(), s);
+    }
+};
 
 int check_batch(int32_t batch, int32_t ld, const char *name)
 {
@@ -402,7 +445,48 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     return NERVA_OK;
 }
 
-void mlp_destroy(nerva_mlp *mlp) { delete mlp; }
+void mlp_destroy(nerva_mlp *mlp)
+{
+    if (!mlp) return;
+    mlp->prof.release();
+    delete mlp;
+}
+
+int mlp_profile_enable(nerva_mlp *mlp, int32_t max_steps)
+{
+    if (!mlp || max_steps < 0) return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    mlp->prof.release();
+    mlp->prof.on = max_steps > 0;
+    mlp->prof.max_steps = max_steps;
+    return NERVA_OK;
+}
+
+int mlp_profile_read(nerva_mlp *mlp, int32_t max_slots, int32_t *n_slots_host, double *ms_sum_host,
+                     int32_t *steps_host)
+{
+    if (!mlp || !n_slots_host || !ms_sum_host || !steps_host) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    StepProfiler &P = mlp->prof;
+    const int32_t n = static_cast<int32_t>(P.names.size());
+    if (n > max_slots) return fail(NERVA_ERR_ARGUMENT, "%d slots, room for %d", n, max_slots);
+    *n_slots_host = n;
+    *steps_host = P.step;
+    for (int32_t k = 0; k < n; ++k) ms_sum_host[k] = 0.0;
+    for (int32_t t = 0; t < P.step; ++t)
+        for (int32_t k = 0; k < n; ++k) {
+            const size_t i = (static_cast<size_t>(t) * n + k) * 2;
+            HIP_TRY(hipEventSynchronize(P.events[i + 1]));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, P.events[i], P.events[i + 1]));
+            ms_sum_host[k] += ms;
+        }
+    return NERVA_OK;
+}
+
+const char *mlp_profile_slot_name(const nerva_mlp *mlp, int32_t slot)
+{
+    if (!mlp || slot < 0 || slot >= static_cast<int32_t>(mlp->prof.names.size())) return "";
+    return mlp->prof.names[slot].c_str();
+}
 
 size_t mlp_workspace_bytes(const nerva_mlp *mlp, int32_t batch)
 {
@@ -439,7 +523,7 @@ static int check_step_args(const nerva_mlp *mlp, const float *X, int32_t ldx, in
     return NERVA_OK;
 }
 
-static int forward_chain(const nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, char *ws, const Layout &L,
+static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, char *ws, const Layout &L,
                          hipStream_t s)
 {
     const float *in = X;
@@ -452,7 +536,10 @@ static int forward_chain(const nerva_mlp *mlp, const float *X, int32_t ldx, int3
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
         a.rows = ly->rows; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
-        HIP_TRY(launch_spmm(a, s));
+        {
+            Timed tm(mlp->prof, s, "spmm_forward", static_cast<int>(l));
+            HIP_TRY(launch_spmm(a, s));
+        }
         in = A;
         ldin = L.ld;
     }
@@ -488,7 +575,10 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
 
     // loss gradient / batch size
     const nerva_layer *last = mlp->layers[n - 1];
-    HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
+    {
+        Timed tm(mlp->prof, s, "softmax_ce", n - 1);
+        HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
+    }
 
     // backpropagate and optimize, last layer first.  Layer l's transposed product runs before
     // anything updates layer l's weights, so every gradient sees the weights of the step's start.
@@ -503,6 +593,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             t.X = dZ(l); t.ldx = L.ld; t.Y = dZ(l - 1); t.ldy = L.ld;
             t.YM = A(l - 1); t.ldym = L.ld;
             t.rows = ly->cols; t.batch = batch;
+            Timed tm(mlp->prof, s, "spmm_transposed", l);
             HIP_TRY(launch_spmm(t, s));
         }
         SddmmArgs g{};
@@ -518,15 +609,29 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
+            Timed tm(mlp->prof, s, "sddmm_update", l);
             HIP_TRY(launch_sddmm(g, s));
         } else {
             g.g = gl; g.db = dbl;
-            HIP_TRY(launch_sddmm(g, s));
-            HIP_TRY(launch_momentum(ly->values, mlp->vel[l], gl, ly->nnz, lr, momentum, s));
-            if (ly->bias) HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], dbl, ly->rows, lr, momentum, s));
-            if (l > 0) HIP_TRY(launch_gather(ly->values_t, ly->values, ly->perm, ly->nnz, s));
+            {
+                Timed tm(mlp->prof, s, "sddmm", l);
+                HIP_TRY(launch_sddmm(g, s));
+            }
+            {
+                Timed tm(mlp->prof, s, "momentum_values", l);
+                HIP_TRY(launch_momentum(ly->values, mlp->vel[l], gl, ly->nnz, lr, momentum, s));
+            }
+            if (ly->bias) {
+                Timed tm(mlp->prof, s, "momentum_bias", l);
+                HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], dbl, ly->rows, lr, momentum, s));
+            }
+            if (l > 0) {
+                Timed tm(mlp->prof, s, "mirror_refresh", l);
+                HIP_TRY(launch_gather(ly->values_t, ly->values, ly->perm, ly->nnz, s));
+            }
         }
     }
+    if (mlp->prof.on && mlp->prof.step < mlp->prof.max_steps) ++mlp->prof.step;
     return NERVA_OK;
 }
 

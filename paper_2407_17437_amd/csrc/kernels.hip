@@ -102,10 +102,19 @@ __device__ __forceinline__ gmem_ptr row_base(const void *base, int j, uint32_t l
     const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(addr >> 32));
     return reinterpret_cast<gmem_ptr>((static_cast<uint64_t>(hi) << 32) | lo);
 }
+typedef float v4f __attribute__((ext_vector_type(4)));
 template <typename V>
-__device__ __forceinline__ V gload(gmem_ptr row, uint32_t byte_offset)
+__device__ __forceinline__ V gload(gmem_ptr row, uint32_t byte_offset);
+template <>
+__device__ __forceinline__ float4 gload<float4>(gmem_ptr row, uint32_t byte_offset)
 {
-    return *reinterpret_cast<const __attribute__((address_space(1))) V *>(row + byte_offset);
+    const v4f r = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(row + byte_offset);
+    return make_float4(r.x, r.y, r.z, r.w);
+}
+template <>
+__device__ __forceinline__ float gload<float>(gmem_ptr row, uint32_t byte_offset)
+{
+    return *reinterpret_cast<const __attribute__((address_space(1))) float *>(row + byte_offset);
 }
 
 template <int VEC> struct Pack;

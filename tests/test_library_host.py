@@ -29,6 +29,13 @@ def test_header_symbols_are_exported(nb):
     assert "gfx950" in nb.build_info()
 
 
+def test_library_is_newer_than_its_sources(nb):
+    csrc = os.path.join(ROOT, "paper_2407_17437_amd", "csrc")
+    srcs = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(ROOT, "include", "nerva_sparse.h")]
+    stale = [s for s in srcs if os.path.getmtime(s) > os.path.getmtime(nb.LIB_PATH)]
+    assert not stale, f"rebuild the library: {stale} changed after it was built"
+
+
 def test_validate_csr_accepts_generated_patterns(nb):
     for rows, cols, nnz in [(5, 7, 0), (5, 7, 35), (64, 33, 500)]:
         indptr, indices = wl.uniform_pattern(rows, cols, nnz, seed=1)
