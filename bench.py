@@ -125,6 +125,14 @@ def main() -> int:
             for i in range(first // args.graph, (first + count) // args.graph):
                 graphs[i % len(graphs)].replay()
 
+    # one plain copy of known size (256 MiB read + 256 MiB written): the reference that HBM traffic
+    # counters of a profiled run are scaled by; outside the timed region
+    cal_src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    nb.nerva_copy_f32(cal_dst, cal_src, cal_src.numel())
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     K, W = args.steps, args.warmup
     if graphs:
         K = max(args.graph, K // args.graph * args.graph)
