@@ -160,8 +160,13 @@ def main() -> int:
         steps_done, slots = nb.mlp_profile_read(M.handle)
         nb.mlp_profile_enable(M.handle, 0)
         for name, ms in slots:
+            # "a+b[l]" is one grid that runs kernel a of layer l and kernel b of layer l+1
             l = int(name.split("[")[1].rstrip("]"))
-            byt = slot_bytes(name, M.layers[l], batch, has_mirror_scatter=(l > 0))
+            kinds = name.split("[")[0].split("+")
+            byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
+            if len(kinds) == 2:
+                l2 = l + 1
+                byt += slot_bytes(kinds[1], M.layers[l2], batch, has_mirror_scatter=(l2 > 0))
             us = ms * 1e3 / max(steps_done, 1)
             kernels.append({"kernel": name, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
                             "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})

@@ -73,17 +73,21 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz,
                             const int32_t *indptr_host, const int32_t *indices_host);
 
 /* The static work partition the kernels use, computed on HOST arrays (needs no GPU; exposed so
- * that it can be checked).  Rows are grouped by lg = log2(waves that share one row); a
- * work-group of NERVA_WAVES_PER_BLOCK waves serves NERVA_WAVES_PER_BLOCK >> lg rows.
- *   row_order_host[rows]      row ids in serving order (every row exactly once)
- *   block_first_host[nb]      first position of row_order served by work-group b
- *   block_info_host[nb]       lg | (number of rows served << 8)
- *   *n_blocks_host            nb, at most `rows`
- * Output arrays may be NULL (only the count is returned); otherwise they need `rows` entries. */
-enum { NERVA_WAVES_PER_BLOCK = 16 };
+ * that it can be checked).  A work-group has NERVA_WAVES_PER_BLOCK waves.  Ordinary rows are
+ * grouped by lg = log2(waves that share one row); a work-group serves
+ * NERVA_WAVES_PER_BLOCK >> lg of them.  A row with more stored entries than one work-group should
+ * take is "huge": it is cut into several work-groups whose partial results a second kernel adds
+ * in order.  Outputs (any array may be NULL to get only the counts):
+ *   counts_host[4]            {ordinary rows, work-groups, huge rows, huge work-groups}
+ *   row_order_host[rows]      ordinary row ids in serving order
+ *   blocks_host[4*nb]         per work-group, huge ones first:
+ *                               ordinary {lg | rows served << 8, first position of row_order, 0, 0}
+ *                               huge     {NERVA_HUGE_FLAG | share index, row, first entry, end entry}
+ *   huge_rows_host[4*nh]      per huge row {row, first work-group, number of work-groups, 0}
+ * nb <= rows + nnz / 128 and nh <= rows bound the sizes. */
+enum { NERVA_WAVES_PER_BLOCK = 16, NERVA_HUGE_FLAG = 0x40000000 };
 int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
-                         int32_t *block_first_host, int32_t *block_info_host,
-                         int32_t *n_blocks_host);
+                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *counts_host);
 
 /* ---- layer -------------------------------------------------------------------------
  * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays
@@ -94,10 +98,13 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
  * exists because the topology is static (Section 6).  The call copies the pattern to the
  * host to validate it (NERVA_ERR_CSR if not canonical), allocates device memory and
  * synchronises `stream`.  activation: NERVA_ACT_RELU for hidden layers, NERVA_ACT_NONE
- * for the output layer (Section 5.1). `bias` may be NULL (no bias).  */
+ * for the output layer (Section 5.1). `bias` may be NULL (no bias).  max_batch bounds the
+ * batch of later calls on this layer (it sizes the scratch rows of huge-row work-groups; a
+ * later call with a larger batch returns NERVA_ERR_SHAPE).  */
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz,
                          const int32_t *indptr, const int32_t *indices,
-                         float *values, float *bias, int32_t activation, void *stream);
+                         float *values, float *bias, int32_t activation, int32_t max_batch,
+                         void *stream);
 void sparse_linear_destroy(nerva_layer *layer);
 
 /* Device pointers of the mirror, for inspection: indptr_t[cols+1], indices_t[nnz],
@@ -153,7 +160,7 @@ int softmax_cross_entropy(const float *Z, int32_t ldz, const int32_t *labels,
  * float[nnz_l], bias_velocities[l] is float[rows_l] (device, caller-owned, normally zero
  * at the start; bias_velocities[l] may be NULL iff the layer has no bias).  The handle
  * keeps the layer pointers: destroy the MLP before its layers.  max_batch bounds `batch`
- * of later calls.  flags: bitwise OR of the NERVA_MLP_* values below. */
+ * of later calls and must not exceed any layer's max_batch.  flags: bitwise OR of the NERVA_MLP_* values below. */
 enum {
     NERVA_MLP_DEFAULT = 0,
     /* Run S = A B^T, the momentum update and the mirror refresh as separate kernels that

@@ -22,6 +22,7 @@ NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_E
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
 NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED = 0, 1
 NERVA_WAVES_PER_BLOCK = 16
+NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
     "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host",
@@ -51,7 +52,7 @@ def _load() -> ctypes.CDLL:
         "nerva_build_info": (ctypes.c_char_p, []),
         "nerva_validate_csr_host": (ctypes.c_int, [i32, i32, i64, vp, vp]),
         "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp]),
-        "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp]),
+        "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
         "sparse_linear_mirror": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sparse_linear_forward": (ctypes.c_int, [vp, vp, i32, vp, i32, i32, vp]),
@@ -120,22 +121,25 @@ def nerva_validate_csr_host(rows: int, cols: int, nnz: int, indptr, indices) -> 
 
 
 def nerva_plan_rows_host(rows: int, indptr):
-    """Returns (row_order, block_first, block_info) numpy int32 arrays."""
+    """Returns (row_order, blocks[nb,4], huge_rows[nh,4], n_huge_blocks) as numpy int32 arrays."""
     import numpy as np
     indptr = np.ascontiguousarray(indptr, dtype=np.int32)
-    order = np.empty(rows, dtype=np.int32); first = np.empty(rows, dtype=np.int32); info = np.empty(rows, dtype=np.int32)
-    nb = ctypes.c_int32(0)
-    _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, order.ctypes.data, first.ctypes.data, info.ctypes.data,
-                                    ctypes.addressof(nb)))
-    return order, first[:nb.value].copy(), info[:nb.value].copy()
+    counts = np.zeros(4, dtype=np.int32)
+    _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, None, None, None, counts.ctypes.data))
+    order = np.empty(max(1, counts[0]), dtype=np.int32)
+    blocks = np.empty((max(1, counts[1]), 4), dtype=np.int32)
+    huge = np.empty((max(1, counts[2]), 4), dtype=np.int32)
+    _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, order.ctypes.data, blocks.ctypes.data, huge.ctypes.data,
+                                    counts.ctypes.data))
+    return order[:counts[0]], blocks[:counts[1]], huge[:counts[2]], int(counts[3])
 
 
 # ---- entry points, same names as the C ABI ------------------------------------------------
 
-def sparse_linear_create(rows, cols, nnz, indptr, indices, values, bias, activation, stream=None) -> int:
+def sparse_linear_create(rows, cols, nnz, indptr, indices, values, bias, activation, max_batch, stream=None) -> int:
     h = ctypes.c_void_p()
     _check(lib.sparse_linear_create(ctypes.addressof(h), rows, cols, nnz, _ptr(indptr), _ptr(indices), _ptr(values),
-                                    _ptr(bias), activation, _stream(stream)))
+                                    _ptr(bias), activation, max_batch, _stream(stream)))
     return h.value
 
 
@@ -250,7 +254,7 @@ def to_dense(array, device="cuda", ld: Optional[int] = None) -> torch.Tensor:
 class SparseLinear:
     """Device copies of one layer's arrays plus the library handle."""
 
-    def __init__(self, layer_data, device="cuda"):
+    def __init__(self, layer_data, max_batch: int = 1024, device="cuda"):
         self.handle = None
         d = layer_data
         self.rows, self.cols, self.nnz = d.rows, d.cols, d.nnz
@@ -262,7 +266,7 @@ class SparseLinear:
         self.velocity = torch.zeros(max(1, d.nnz), dtype=torch.float32, device=device)[:d.nnz]
         self.bias_velocity = torch.zeros(d.rows, dtype=torch.float32, device=device)
         self.handle = sparse_linear_create(d.rows, d.cols, d.nnz, self.indptr, self.indices, self.values, self.bias,
-                                           NERVA_ACT_RELU if d.relu else NERVA_ACT_NONE)
+                                           NERVA_ACT_RELU if d.relu else NERVA_ACT_NONE, max_batch)
 
     def close(self):
         if self.handle:
@@ -279,7 +283,7 @@ class MLP:
     def __init__(self, mlp_data, max_batch: int, flags: int = NERVA_MLP_DEFAULT, device="cuda"):
         self.handle = None
         self.layers = []
-        self.layers = [SparseLinear(l, device) for l in mlp_data.layers]
+        self.layers = [SparseLinear(l, max_batch, device) for l in mlp_data.layers]
         self.max_batch = max_batch
         self.handle = mlp_create([l.handle for l in self.layers], [l.velocity for l in self.layers],
                                  [l.bias_velocity for l in self.layers], max_batch, flags)

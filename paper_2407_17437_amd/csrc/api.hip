@@ -45,7 +45,7 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 }  // namespace
 
 struct nerva_layer {
-    int32_t rows = 0, cols = 0, nnz = 0, activation = 0;
+    int32_t rows = 0, cols = 0, nnz = 0, activation = 0, max_batch = 0;
     // caller-owned
     const int32_t *indptr = nullptr;
     const int32_t *indices = nullptr;
@@ -61,6 +61,9 @@ struct nerva_layer {
     int32_t *plan_mem = nullptr;
     int32_t *plan_t_mem = nullptr;
     RowBlocks plan{}, plan_t{};
+    // owned: partial rows of huge-row work-groups, shared by the forward and the transposed product
+    float *scratch = nullptr;
+    int64_t scratch_ld = 0;
 };
 
 // Optional per-kernel timing of mlp_train_step: one pair of HIP events around every launch of
@@ -118,60 +121,85 @@ Layout make_layout(const nerva_mlp *m, int32_t batch)
 }
 
 // Rows are grouped by the number of waves that share one row: 2^lg, the smallest power of two
-// that leaves each wave at most `target` stored entries, capped at a whole work-group.  `target`
-// aims at >= 16384 waves per launch (64 per compute unit) but never fewer than 8 entries per wave.
-int plan_rows(int32_t rows, const int32_t *indptr, std::vector<int32_t> &row_order,
-              std::vector<int32_t> &block_first, std::vector<int32_t> &block_info)
+// that leaves each wave at most `target` stored entries.  `target` aims at >= 16384 waves per
+// launch (64 per compute unit) but never fewer than 8 entries per wave.  A whole work-group on
+// one row may run up to 4x over the target; a row beyond that is huge: it is cut into work-groups
+// of at most 2 * kWavesPerBlock * target entries each.
+struct RowPlan {
+    std::vector<int32_t> row_order;  // ordinary rows
+    std::vector<int32_t> blocks;     // 4 ints per work-group, huge ones first
+    std::vector<int32_t> huge_rows;  // 4 ints per huge row
+    int32_t n_huge_blocks = 0;
+    int32_t n_blocks() const { return static_cast<int32_t>(blocks.size() / 4); }
+    int32_t n_huge_rows() const { return static_cast<int32_t>(huge_rows.size() / 4); }
+};
+
+RowPlan plan_rows(int32_t rows, const int32_t *indptr)
 {
+    RowPlan P;
     const int64_t nnz = indptr[rows];
     int64_t target = nnz / 16384;
     if (target < 8) target = 8;
     if (target > 64) target = 64;
+    const int64_t block_cap = target * kWavesPerBlock;
     int max_lg = 0;
     while ((1 << max_lg) < kWavesPerBlock) ++max_lg;
     std::vector<int8_t> lg_of(rows);
     std::vector<int32_t> count(max_lg + 1, 0);
     for (int32_t i = 0; i < rows; ++i) {
         const int64_t n = indptr[i + 1] - indptr[i];
+        if (n > 4 * block_cap) {
+            lg_of[i] = -1;
+            const int32_t parts = static_cast<int32_t>((n + 2 * block_cap - 1) / (2 * block_cap));
+            const int64_t share = (n + parts - 1) / parts;
+            const int32_t first = P.n_blocks();
+            for (int32_t q = 0; q < parts; ++q) {
+                const int64_t b = indptr[i] + q * share;
+                const int64_t e = b + share < indptr[i + 1] ? b + share : indptr[i + 1];
+                P.blocks.insert(P.blocks.end(), {kHugeFlag | q, i, static_cast<int32_t>(b), static_cast<int32_t>(e)});
+            }
+            P.huge_rows.insert(P.huge_rows.end(), {i, first, parts, 0});
+            continue;
+        }
         int lg = 0;
         while (lg < max_lg && (n + (1 << lg) - 1) / (1 << lg) > target) ++lg;
         lg_of[i] = static_cast<int8_t>(lg);
         ++count[lg];
     }
-    row_order.resize(rows);
-    block_first.clear();
-    block_info.clear();
-    int32_t slot = 0;
+    P.n_huge_blocks = P.n_blocks();
     for (int lg = max_lg; lg >= 0; --lg) {
         if (!count[lg]) continue;
-        const int32_t begin = slot;
+        const int32_t begin = static_cast<int32_t>(P.row_order.size());
         for (int32_t i = 0; i < rows; ++i)
-            if (lg_of[i] == lg) row_order[slot++] = i;
+            if (lg_of[i] == lg) P.row_order.push_back(i);
+        const int32_t end = static_cast<int32_t>(P.row_order.size());
         const int32_t per_block = kWavesPerBlock >> lg;
-        for (int32_t f = begin; f < slot; f += per_block) {
-            const int32_t n_rows = slot - f < per_block ? slot - f : per_block;
-            block_first.push_back(f);
-            block_info.push_back(lg | (n_rows << 8));
+        for (int32_t f = begin; f < end; f += per_block) {
+            const int32_t n_rows = end - f < per_block ? end - f : per_block;
+            P.blocks.insert(P.blocks.end(), {lg | (n_rows << 8), f, 0, 0});
         }
     }
-    return static_cast<int>(block_first.size());
+    return P;
 }
 
 hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, RowBlocks *plan, hipStream_t s,
                        std::vector<int32_t> &staging)
 {
-    std::vector<int32_t> order, first, info;
-    const int nb = plan_rows(rows, indptr_host, order, first, info);
-    staging = order;
-    staging.insert(staging.end(), first.begin(), first.end());
-    staging.insert(staging.end(), info.begin(), info.end());
+    const RowPlan P = plan_rows(rows, indptr_host);
+    // 16-byte records first so that they stay 16-byte aligned
+    staging = P.blocks;
+    staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
+    staging.insert(staging.end(), P.row_order.begin(), P.row_order.end());
+    if (staging.empty()) staging.push_back(0);
     hipError_t e = hipMalloc(mem, staging.size() * 4);
     if (e != hipSuccess) return e;
     e = hipMemcpyAsync(*mem, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, s);
-    plan->row_order = *mem;
-    plan->block_first = *mem + rows;
-    plan->block_info = *mem + rows + nb;
-    plan->n_blocks = nb;
+    plan->blocks = reinterpret_cast<const int4 *>(*mem);
+    plan->huge_rows = reinterpret_cast<const int4 *>(*mem + P.blocks.size());
+    plan->row_order = *mem + P.blocks.size() + P.huge_rows.size();
+    plan->n_blocks = P.n_blocks();
+    plan->n_huge_rows = P.n_huge_rows();
+    plan->n_huge_blocks = P.n_huge_blocks;
     return e;
 }
 
@@ -179,6 +207,7 @@ void free_layer_buffers(nerva_layer *l)
 {
     (void)hipFree(l->plan_mem);
     (void)hipFree(l->plan_t_mem);
+    (void)hipFree(l->scratch);
     (void)hipFree(l->indptr_t);
     (void)hipFree(l->indices_t);
     (void)hipFree(l->values_t);
@@ -250,26 +279,30 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz, const int32
 }
 
 int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
-                         int32_t *block_first_host, int32_t *block_info_host, int32_t *n_blocks_host)
+                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *counts_host)
 {
-    if (rows <= 0 || !indptr_host || !n_blocks_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
-    std::vector<int32_t> order, first, info;
-    const int nb = plan_rows(rows, indptr_host, order, first, info);
-    *n_blocks_host = nb;
-    if (row_order_host) memcpy(row_order_host, order.data(), order.size() * 4);
-    if (block_first_host) memcpy(block_first_host, first.data(), first.size() * 4);
-    if (block_info_host) memcpy(block_info_host, info.data(), info.size() * 4);
+    if (rows <= 0 || !indptr_host || !counts_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    const RowPlan P = plan_rows(rows, indptr_host);
+    counts_host[0] = static_cast<int32_t>(P.row_order.size());
+    counts_host[1] = P.n_blocks();
+    counts_host[2] = P.n_huge_rows();
+    counts_host[3] = P.n_huge_blocks;
+    if (row_order_host && !P.row_order.empty()) memcpy(row_order_host, P.row_order.data(), P.row_order.size() * 4);
+    if (blocks_host && !P.blocks.empty()) memcpy(blocks_host, P.blocks.data(), P.blocks.size() * 4);
+    if (huge_rows_host && !P.huge_rows.empty()) memcpy(huge_rows_host, P.huge_rows.data(), P.huge_rows.size() * 4);
     return NERVA_OK;
 }
 
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
-                         const int32_t *indices, float *values, float *bias, int32_t activation, void *stream)
+                         const int32_t *indices, float *values, float *bias, int32_t activation, int32_t max_batch,
+                         void *stream)
 {
     if (!out) return fail(NERVA_ERR_ARGUMENT, "out is null");
     *out = nullptr;
     if (rows <= 0 || cols <= 0 || nnz < 0) return fail(NERVA_ERR_ARGUMENT, "bad layer size %d x %d, nnz %d", rows, cols, nnz);
     if (!indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
     if (activation != NERVA_ACT_NONE && activation != NERVA_ACT_RELU) return fail(NERVA_ERR_ARGUMENT, "unknown activation %d", activation);
+    if (max_batch <= 0 || max_batch >= (1 << 30)) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive (got %d)", max_batch);
     hipStream_t s = as_stream(stream);
 
     std::vector<int32_t> h_indptr(static_cast<size_t>(rows) + 1), h_indices(static_cast<size_t>(nnz));
@@ -297,7 +330,7 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
 
     nerva_layer *l = new (std::nothrow) nerva_layer;
     if (!l) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
-    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation;
+    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation; l->max_batch = max_batch;
     l->indptr = indptr; l->indices = indices; l->values = values; l->bias = bias;
     const size_t nb = static_cast<size_t>(nnz > 0 ? nnz : 1) * 4;
     hipError_t e = hipMalloc(&l->indptr_t, (static_cast<size_t>(cols) + 1) * 4);
@@ -312,6 +345,11 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
     std::vector<int32_t> stage_a, stage_b;
     if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), &l->plan_mem, &l->plan, s, stage_a);
     if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
+    if (e == hipSuccess) {
+        const int64_t slots = l->plan.n_huge_blocks > l->plan_t.n_huge_blocks ? l->plan.n_huge_blocks : l->plan_t.n_huge_blocks;
+        l->scratch_ld = round_up(max_batch, 64);
+        if (slots > 0) e = hipMalloc(&l->scratch, static_cast<size_t>(slots) * l->scratch_ld * 4);
+    }
     if (e == hipSuccess) e = launch_gather(l->values_t, values, l->perm, nnz, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
     if (e != hipSuccess) {
@@ -347,9 +385,10 @@ int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
     if (!layer || !X || !Y) return fail(NERVA_ERR_ARGUMENT, "null argument");
     int rc = check_batch(batch, ldx, "ldx");
     if (rc == NERVA_OK) rc = check_batch(batch, ldy, "ldy");
+    if (rc == NERVA_OK && batch > layer->max_batch) rc = fail(NERVA_ERR_SHAPE, "batch %d exceeds the layer's max_batch %d", batch, layer->max_batch);
     if (rc != NERVA_OK) return rc;
     SpmmArgs a{};
-    a.blocks = layer->plan;
+    a.blocks = layer->plan; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
     a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
     a.rows = layer->rows; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
@@ -369,12 +408,13 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
     if (rc == NERVA_OK && relu) rc = check_batch(batch, ldy, "ldy");
     if (rc == NERVA_OK && dvalues) rc = check_batch(batch, ldx, "ldx");
     if (rc == NERVA_OK && dX) rc = check_batch(batch, lddx, "lddx");
+    if (rc == NERVA_OK && batch > layer->max_batch) rc = fail(NERVA_ERR_SHAPE, "batch %d exceeds the layer's max_batch %d", batch, layer->max_batch);
     if (rc != NERVA_OK) return rc;
     hipStream_t s = as_stream(stream);
     if (dX) {
         HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
         SpmmArgs a{};
-        a.blocks = layer->plan_t;
+        a.blocks = layer->plan_t; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
         a.indptr = layer->indptr_t; a.indices = layer->indices_t; a.values = layer->values_t;
         a.X = dY; a.ldx = lddy;
         if (relu) { a.XM = Y; a.ldxm = ldy; }
@@ -428,6 +468,8 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
         if (!layers[l]) return fail(NERVA_ERR_ARGUMENT, "layer %d is null", l);
         if (layers[l]->nnz > 0 && !velocities[l]) return fail(NERVA_ERR_ARGUMENT, "velocity of layer %d is null", l);
         if (layers[l]->bias && !bias_velocities[l]) return fail(NERVA_ERR_ARGUMENT, "bias velocity of layer %d is null", l);
+        if (layers[l]->max_batch < max_batch)
+            return fail(NERVA_ERR_SHAPE, "layer %d was created for batches up to %d, the MLP asks for %d", l, layers[l]->max_batch, max_batch);
         if (l > 0 && layers[l]->cols != layers[l - 1]->rows)
             return fail(NERVA_ERR_SHAPE, "layer %d has %d inputs but layer %d has %d outputs", l, layers[l]->cols, l - 1, layers[l - 1]->rows);
         const int32_t want = l + 1 < n_layers ? NERVA_ACT_RELU : NERVA_ACT_NONE;
@@ -532,7 +574,7 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
         const nerva_layer *ly = mlp->layers[l];
         float *A = reinterpret_cast<float *>(ws + L.A[l]);
         SpmmArgs a{};
-        a.blocks = ly->plan;
+        a.blocks = ly->plan; a.nnz = ly->nnz; a.scratch = ly->scratch; a.scratch_ld = ly->scratch_ld;
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
         a.rows = ly->rows; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
@@ -580,50 +622,91 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
     }
 
-    // backpropagate and optimize, last layer first.  Layer l's transposed product runs before
+    // backpropagate and optimize, last layer first.  Layer l's transposed product T_l runs before
     // anything updates layer l's weights, so every gradient sees the weights of the step's start.
-    for (int l = n - 1; l >= 0; --l) {
+    auto make_T = [&](int l) {
+        // dZ_{l-1} = (W_l^T dZ_l) * [A_{l-1} > 0]: the ReLU derivative of the layer below is
+        // applied as the transposed product is stored
         nerva_layer *ly = mlp->layers[l];
-        if (l > 0) {
-            // dZ_{l-1} = (W_l^T dZ_l) * [A_{l-1} > 0]: the ReLU derivative of the layer below is
-            // applied as the transposed product is stored
-            SpmmArgs t{};
-            t.blocks = ly->plan_t;
-            t.indptr = ly->indptr_t; t.indices = ly->indices_t; t.values = ly->values_t;
-            t.X = dZ(l); t.ldx = L.ld; t.Y = dZ(l - 1); t.ldy = L.ld;
-            t.YM = A(l - 1); t.ldym = L.ld;
-            t.rows = ly->cols; t.batch = batch;
-            Timed tm(mlp->prof, s, "spmm_transposed", l);
-            HIP_TRY(launch_spmm(t, s));
-        }
+        SpmmArgs t{};
+        t.blocks = ly->plan_t; t.nnz = ly->nnz; t.scratch = ly->scratch; t.scratch_ld = ly->scratch_ld;
+        t.indptr = ly->indptr_t; t.indices = ly->indices_t; t.values = ly->values_t;
+        t.X = dZ(l); t.ldx = L.ld; t.Y = dZ(l - 1); t.ldy = L.ld;
+        t.YM = A(l - 1); t.ldym = L.ld;
+        t.rows = ly->cols; t.batch = batch;
+        return t;
+    };
+    auto make_S = [&](int l) {
+        nerva_layer *ly = mlp->layers[l];
         SddmmArgs g{};
         g.blocks = ly->plan;
         g.indptr = ly->indptr; g.indices = ly->indices;
         g.dZ = dZ(l); g.lddz = L.ld;
         g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
         g.rows = ly->rows; g.batch = batch;
-        float *gl = reinterpret_cast<float *>(ws + L.g[l]);
-        float *dbl = reinterpret_cast<float *>(ws + L.db[l]);
         if (fused) {
             g.fused = 1; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
-            Timed tm(mlp->prof, s, "sddmm_update", l);
-            HIP_TRY(launch_sddmm(g, s));
         } else {
-            g.g = gl; g.db = dbl;
+            g.g = reinterpret_cast<float *>(ws + L.g[l]);
+            g.db = reinterpret_cast<float *>(ws + L.db[l]);
+        }
+        return g;
+    };
+
+    if (fused) {
+        // Launch order T_{n-1} | T_{n-2} + S_{n-1} | ... | T_1 + S_2 | S_1 + S_0: the fused
+        // SDDMM+update S_l of a layer shares a grid with the transposed product of the layer
+        // below, which no longer depends on it (S_l only needs dZ_l and must follow T_l).
+        if (n > 1) {
+            Timed tm(mlp->prof, s, "spmm_transposed", n - 1);
+            HIP_TRY(launch_spmm(make_T(n - 1), s));
+        }
+        for (int l = n - 1; l >= 2; --l) {
+            const SpmmArgs t = make_T(l - 1);
+            const SddmmArgs g = make_S(l);
+            if (can_pair(t, g)) {
+                Timed tm(mlp->prof, s, "spmm_transposed+sddmm_update", l - 1);
+                HIP_TRY(launch_pair(t, g, s));
+            } else {
+                { Timed tm(mlp->prof, s, "spmm_transposed", l - 1); HIP_TRY(launch_spmm(t, s)); }
+                { Timed tm(mlp->prof, s, "sddmm_update", l); HIP_TRY(launch_sddmm(g, s)); }
+            }
+        }
+        if (n > 1) {
+            const SddmmArgs g1 = make_S(1), g0 = make_S(0);
+            if (can_pair(g1, g0)) {
+                Timed tm(mlp->prof, s, "sddmm_update+sddmm_update", 0);
+                HIP_TRY(launch_pair(g1, g0, s));
+            } else {
+                { Timed tm(mlp->prof, s, "sddmm_update", 1); HIP_TRY(launch_sddmm(g1, s)); }
+                { Timed tm(mlp->prof, s, "sddmm_update", 0); HIP_TRY(launch_sddmm(g0, s)); }
+            }
+        } else {
+            Timed tm(mlp->prof, s, "sddmm_update", 0);
+            HIP_TRY(launch_sddmm(make_S(0), s));
+        }
+    } else {
+        for (int l = n - 1; l >= 0; --l) {
+            nerva_layer *ly = mlp->layers[l];
+            if (l > 0) {
+                Timed tm(mlp->prof, s, "spmm_transposed", l);
+                HIP_TRY(launch_spmm(make_T(l), s));
+            }
+            const SddmmArgs g = make_S(l);
             {
                 Timed tm(mlp->prof, s, "sddmm", l);
                 HIP_TRY(launch_sddmm(g, s));
             }
             {
                 Timed tm(mlp->prof, s, "momentum_values", l);
-                HIP_TRY(launch_momentum(ly->values, mlp->vel[l], gl, ly->nnz, lr, momentum, s));
+                HIP_TRY(launch_momentum(ly->values, mlp->vel[l], g.g, ly->nnz, lr, momentum, s));
             }
             if (ly->bias) {
                 Timed tm(mlp->prof, s, "momentum_bias", l);
-                HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], dbl, ly->rows, lr, momentum, s));
+                HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], g.db, ly->rows, lr, momentum, s));
             }
             if (l > 0) {
                 Timed tm(mlp->prof, s, "mirror_refresh", l);

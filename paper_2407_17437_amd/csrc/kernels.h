@@ -8,14 +8,21 @@ namespace nerva {
 constexpr int kWavesPerBlock = 16;   // 1024 threads
 
 // Static partition of the rows of a CSR matrix over work-groups, built once per pattern.
-// A work-group of kWavesPerBlock waves serves (kWavesPerBlock >> lg) rows, 2^lg waves per
-// row, each wave taking a contiguous share of the row's stored entries.
+// A work-group has kWavesPerBlock waves.  Ordinary rows: the work-group serves
+// (kWavesPerBlock >> lg) rows, 2^lg waves per row, each wave taking a contiguous share of the
+// row's stored entries.  Huge rows (more entries than a whole work-group should take) are cut
+// into several work-groups; each produces a partial result that a second, small kernel adds
+// up in share order.  Huge work-groups come first, so blockIdx.x is also their scratch slot.
 struct RowBlocks {
-    const int32_t *row_order;    // [rows] row ids, grouped by lg (descending)
-    const int32_t *block_first;  // [n_blocks] first slot of row_order served by the block
-    const int32_t *block_info;   // [n_blocks] lg | (rows served << 8)
+    const int32_t *row_order;  // [rows - n_huge_rows] ordinary row ids, grouped by lg (descending)
+    const int4 *blocks;        // [n_blocks] ordinary: {lg | rows served << 8, first slot of row_order, 0, 0}
+                               //            huge:     {kHugeFlag | share index, row, first entry, end entry}
+    const int4 *huge_rows;     // [n_huge_rows] {row, first work-group, number of work-groups, 0}
     int32_t n_blocks;
+    int32_t n_huge_rows;
+    int32_t n_huge_blocks;
 };
+constexpr int32_t kHugeFlag = 0x40000000;
 
 // Y = epilogue( W * gather(X) ) for a CSR matrix W (rows x cols); also used on the CSC
 // mirror, where "rows" are W's columns.
@@ -36,6 +43,9 @@ struct SpmmArgs {
     int32_t rows;
     int32_t batch;
     int32_t relu;            // clamp the result at zero
+    int32_t nnz;             // length of indices/values
+    float *scratch;          // partial rows of huge-row work-groups, (n_huge_blocks, scratch_ld)
+    int64_t scratch_ld;
 };
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s);
 
@@ -67,6 +77,12 @@ struct SddmmArgs {
     float *bias_velocity;    // [rows] or nullptr
 };
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
+
+// Two independent launches in one grid (both on the 16-byte path, batch <= 1024, one column tile).
+bool can_pair(const SpmmArgs &a, const SddmmArgs &b);
+bool can_pair(const SddmmArgs &a, const SddmmArgs &b);
+hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s);
+hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s);
 
 hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu,
                            hipStream_t s);

@@ -72,22 +72,49 @@ __device__ __forceinline__ void momentum_step(float &w, float &v, float g, float
     w = w + v;
 }
 
-// Which row, and which share of it, the calling wave serves.
+// Which row, and which contiguous run [s0, s1) of its stored entries, the calling wave serves.
 struct WaveTask {
-    int row;    // -1: nothing to do
-    int part;   // share index inside the row
-    int lg;     // log2(waves per row), uniform over the work-group
+    int row;     // -1: nothing to do
+    int part;    // index of this wave among the waves that share the row inside this work-group
+    int lg;      // log2(waves that share the row in this work-group); uniform over the work-group
+    int s0, s1;  // the wave's stored entries
+    bool huge;   // the work-group holds one share of a huge row: its result is a partial sum
+    bool lead;   // first wave of the row's first share (owner of per-row by-products)
 };
-__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b)
+// GRAIN: shares are multiples of GRAIN entries (the SDDMM works on GRAIN entries at a time).
+template <int GRAIN>
+__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, const int32_t *indptr, int block)
 {
-    const int info = b.block_info[blockIdx.x];
-    const int first = b.block_first[blockIdx.x];
+    const int4 d = b.blocks[block];
     const int w = wave_in_block();
     WaveTask t;
-    t.lg = info & 0xff;
-    const int slot = w >> t.lg;
-    t.part = w & ((1 << t.lg) - 1);
-    t.row = slot < (info >> 8) ? b.row_order[first + slot] : -1;
+    int p0, p1;
+    if (d.x & kHugeFlag) {
+        t.huge = true;
+        t.lg = 4;
+        static_assert(kWavesPerBlock == 16, "a huge-row work-group spreads one share over all 16 waves");
+        t.part = w;
+        t.row = d.y;
+        p0 = d.z;
+        p1 = d.w;
+        t.lead = w == 0 && (d.x & ~kHugeFlag) == 0;
+    } else {
+        t.huge = false;
+        t.lg = d.x & 0xff;
+        const int slot = w >> t.lg;
+        t.part = w & ((1 << t.lg) - 1);
+        t.row = slot < (d.x >> 8) ? b.row_order[d.y + slot] : -1;
+        p0 = p1 = 0;
+        if (t.row >= 0) {
+            p0 = indptr[t.row];
+            p1 = indptr[t.row + 1];
+        }
+        t.lead = t.part == 0;
+    }
+    int per = ((p1 - p0) + (1 << t.lg) - 1) >> t.lg;
+    per = (per + GRAIN - 1) / GRAIN * GRAIN;
+    t.s0 = min(p0 + t.part * per, p1);
+    t.s1 = min(t.s0 + per, p1);
     return t;
 }
 
@@ -130,8 +157,8 @@ __device__ __forceinline__ void fma_into(float (&acc)[4], float w, float4 x)
 }
 __device__ __forceinline__ void fma_into(float (&acc)[1], float w, float x) { acc[0] = fmaf(w, x, acc[0]); }
 
-// U consecutive stored entries: all index/weight fetches, then all gathers, then the FMAs, so
-// that U*NV reads are in flight per wave.
+// U consecutive stored entries starting at p: all index/weight fetches, then all gathers, then
+// the FMAs, so that U*NV reads are in flight per wave.
 template <int VEC, int NV, bool XMASK, int U>
 __device__ __forceinline__ void spmm_step(const SpmmArgs &a, int p, uint32_t ldxb, uint32_t ldmb,
                                           const uint32_t (&off)[NV], float (&acc)[NV][VEC])
@@ -168,15 +195,15 @@ __device__ __forceinline__ void spmm_step(const SpmmArgs &a, int p, uint32_t ldx
 // blockIdx.y walks over column tiles.
 // ---------------------------------------------------------------------------------------
 template <int VEC, int NV, bool XMASK>
-__global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
+__device__ __forceinline__ void spmm_body(const SpmmArgs &a, const int block, const int col_tile)
 {
     constexpr int U = NV >= 4 ? 2 : (NV == 2 ? 4 : 8);
     __shared__ float red[kWavesPerBlock][NV][VEC][kWave];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = wave_in_block();
-    const WaveTask task = wave_task(a.blocks);
-    const int col_base = blockIdx.y * (kWave * VEC * NV);
+    const WaveTask task = wave_task<1>(a.blocks, a.indptr, block);
+    const int col_base = col_tile * (kWave * VEC * NV);
 
     // Lanes whose columns lie beyond the batch re-read the tile's first columns and are never stored.
     // A 4-wide access that starts below `batch` stays inside the row: ld is a multiple of 4 and >= batch.
@@ -194,13 +221,11 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
     }
 
     if (task.row >= 0) {
-        const int p0 = a.indptr[task.row];
-        const int p1 = a.indptr[task.row + 1];
-        const int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
-        int p = p0 + task.part * per;
-        const int pe = min(p + per, p1);
         const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
         const uint32_t ldmb = XMASK ? static_cast<uint32_t>(a.ldxm) * 4u : 0u;
+        int p = task.s0;
+        const int pe = task.s1;
+        // only entries of this wave's share are gathered: the gather stream is what the kernel pays for
         for (; p + U <= pe; p += U) spmm_step<VEC, NV, XMASK, U>(a, p, ldxb, ldmb, off, acc);
         if constexpr (U >= 8)
             if (p + 4 <= pe) { spmm_step<VEC, NV, XMASK, 4>(a, p, ldxb, ldmb, off, acc); p += 4; }
@@ -226,6 +251,17 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
         }
     }
     if (task.row < 0 || task.part != 0) return;
+
+    if (task.huge) {
+        // one share of a huge row: the raw partial sum goes to this work-group's scratch row
+        float *sr = a.scratch + static_cast<int64_t>(block) * a.scratch_ld;
+#pragma unroll
+        for (int t = 0; t < NV; ++t)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                if (col[t] + k < a.batch) sr[col[t] + k] = acc[t][k];
+        return;
+    }
 
     const float b = a.bias ? a.bias[task.row] : 0.f;
     float *yr = a.Y + static_cast<int64_t>(task.row) * a.ldy;
@@ -260,6 +296,28 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
     }
 }
 
+template <int VEC, int NV, bool XMASK>
+__global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
+{
+    spmm_body<VEC, NV, XMASK>(a, blockIdx.x, blockIdx.y);
+}
+
+// Second pass for huge rows: adds the partial rows of a row's work-groups in share order, then
+// bias, ReLU and the optional output mask.  One thread per column.
+__global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
+{
+    const int4 h = a.blocks.huge_rows[blockIdx.x];
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= a.batch) return;
+    const float *sr = a.scratch + static_cast<int64_t>(h.y) * a.scratch_ld + c;
+    float y = 0.f;
+    for (int q = 0; q < h.z; ++q) y += sr[static_cast<int64_t>(q) * a.scratch_ld];
+    y += a.bias ? a.bias[h.x] : 0.f;
+    if (a.relu) y = y > 0.f ? y : 0.f;
+    if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(h.x) * a.ldym + c]);
+    a.Y[static_cast<int64_t>(h.x) * a.ldy + c] = y;
+}
+
 // ---------------------------------------------------------------------------------------
 // SDDMM.  The row of dZ stays in registers; the wave is cut into 64/G groups of G lanes, each
 // group computing the dot product of one stored entry at a time (lanes along the batch, 4
@@ -270,12 +328,12 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
 // Lanes whose columns lie beyond the batch hold dZ = 0 and re-read columns 0..3 of the row.
 // ---------------------------------------------------------------------------------------
 template <int G, int NV, bool EXACT4>
-__global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
+__device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
 {
     constexpr int NG = kWave / G;
     constexpr int UI = NV >= 4 ? 2 : 4;
     const int lane = threadIdx.x & (kWave - 1);
-    const WaveTask task = wave_task(a.blocks);
+    const WaveTask task = wave_task<NG>(a.blocks, a.indptr, block);
     if (task.row < 0) return;
     const int row = task.row;
     const int grp = lane / G;
@@ -304,7 +362,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
         }
     }
 
-    if (task.part == 0 && (a.db || (a.fused && a.bias))) {
+    if (task.lead && (a.db || (a.fused && a.bias))) {
         float s = 0.f;
 #pragma unroll
         for (int t = 0; t < NV; ++t) s += (dz[t].x + dz[t].y) + (dz[t].z + dz[t].w);
@@ -321,12 +379,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
     }
     if (a.skip_products) return;
 
-    const int p0 = a.indptr[row];
-    const int p1 = a.indptr[row + 1];
-    int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
-    per = (per + NG - 1) / NG * NG;
-    const int s0 = p0 + task.part * per;
-    const int s1 = min(s0 + per, p1);
+    const int s0 = task.s0;
+    const int s1 = task.s1;
     const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
     const char *Xb = reinterpret_cast<const char *>(a.X);
     const int q_mine = lig * NG + grp;  // slot of this lane inside a chunk of 64 entries
@@ -393,18 +447,43 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
     }
 }
 
+template <int G, int NV, bool EXACT4>
+__global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
+{
+    sddmm_body<G, NV, EXACT4>(a, blockIdx.x);
+}
+
+// Two independent launches of a training step in one grid: work-groups [0, na) run the first,
+// the rest the second.  Saves a launch (and its drain) on the step's critical path.
+template <int NV_S, int G, int NV_D, bool EXACT4>
+__global__ __launch_bounds__(kBlock) void spmm_sddmm_pair_kernel(const SpmmArgs a, const SddmmArgs b, const int na)
+{
+    if (static_cast<int>(blockIdx.x) < na)
+        spmm_body<4, NV_S, false>(a, blockIdx.x, 0);
+    else
+        sddmm_body<G, NV_D, EXACT4>(b, blockIdx.x - na);
+}
+template <int G, int NV_D, bool EXACT4>
+__global__ __launch_bounds__(kBlock) void sddmm_pair_kernel(const SddmmArgs a, const SddmmArgs b, const int na)
+{
+    if (static_cast<int>(blockIdx.x) < na)
+        sddmm_body<G, NV_D, EXACT4>(a, blockIdx.x);
+    else
+        sddmm_body<G, NV_D, EXACT4>(b, blockIdx.x - na);
+}
+
 // Any batch size, any leading dimension, any alignment: one column per lane and pass, both
 // operands re-read per stored entry.  The slow path behind sddmm_kernel.
 __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const WaveTask task = wave_task(a.blocks);
+    const WaveTask task = wave_task<1>(a.blocks, a.indptr, blockIdx.x);
     if (task.row < 0) return;
     const int row = task.row;
     const float *zr = a.dZ + static_cast<int64_t>(row) * a.lddz;
     const float *zm = a.ZM ? a.ZM + static_cast<int64_t>(row) * a.ldzm : nullptr;
 
-    if (task.part == 0 && (a.db || (a.fused && a.bias))) {
+    if (task.lead && (a.db || (a.fused && a.bias))) {
         float s = 0.f;
         for (int c = lane; c < a.batch; c += kWave) {
             float z = zr[c];
@@ -424,11 +503,8 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
     }
     if (a.skip_products) return;
 
-    const int p0 = a.indptr[row];
-    const int p1 = a.indptr[row + 1];
-    const int per = ((p1 - p0) + (1 << task.lg) - 1) >> task.lg;
-    const int s0 = p0 + task.part * per;
-    const int s1 = min(s0 + per, p1);
+    const int s0 = task.s0;
+    const int s1 = task.s1;
     for (int p = s0; p < s1; ++p) {
         const float *xr = a.X + static_cast<int64_t>(a.indices[p]) * a.ldx;
         float part = 0.f;
@@ -515,37 +591,60 @@ __global__ __launch_bounds__(kEwBlock) void copy_kernel(float *__restrict__ dst,
 }
 
 // Softmax cross-entropy, one column (example) per thread, a single work-group so that the
-// mean over the batch is summed in one fixed order.  The logits matrix is classes x batch:
-// small next to the layers that feed it.
+// mean over the batch is summed in one fixed order (wave sums by DPP, then the wave leaders'
+// values in wave order).  The logits matrix is classes x batch: small next to the layers that
+// feed it.  CMAX > 0: classes <= CMAX and a column's logits are read once into registers.
 constexpr int kSoftmaxBlock = 1024;
+template <int CMAX>
 __global__ __launch_bounds__(kSoftmaxBlock) void softmax_ce_kernel(const float *Z, int64_t ldz,
                                                                    const int32_t *__restrict__ labels,
                                                                    int classes, int batch, float *dZ,
                                                                    int64_t lddz, float *loss_out)
 {
-    __shared__ float partial[kSoftmaxBlock];
+    __shared__ float wave_loss[kSoftmaxBlock / kWave];
     const float inv_b = 1.0f / static_cast<float>(batch);
     float loss = 0.f;
-    for (int c = threadIdx.x; c < batch; c += kSoftmaxBlock) {
-        float m = -INFINITY;
-        for (int i = 0; i < classes; ++i) m = fmaxf(m, Z[static_cast<int64_t>(i) * ldz + c]);
-        float s = 0.f;
-        for (int i = 0; i < classes; ++i) s += expf(Z[static_cast<int64_t>(i) * ldz + c] - m);
-        const float lse = m + logf(s);
+    for (int c = threadIdx.x; c < batch; c += blockDim.x) {
         const int t = labels[c];
-        loss += lse - Z[static_cast<int64_t>(t) * ldz + c];
-        for (int i = 0; i < classes; ++i) {
-            const float p = expf(Z[static_cast<int64_t>(i) * ldz + c] - lse);
-            dZ[static_cast<int64_t>(i) * lddz + c] = (p - (i == t ? 1.f : 0.f)) * inv_b;
+        if constexpr (CMAX > 0) {
+            float z[CMAX];
+#pragma unroll
+            for (int i = 0; i < CMAX; ++i) z[i] = i < classes ? Z[static_cast<int64_t>(i) * ldz + c] : -INFINITY;
+            float m = z[0];
+#pragma unroll
+            for (int i = 1; i < CMAX; ++i) m = fmaxf(m, z[i]);
+            float s = 0.f, zt = 0.f;
+#pragma unroll
+            for (int i = 0; i < CMAX; ++i) {
+                if (i < classes) s += expf(z[i] - m);
+                zt = i == t ? z[i] : zt;
+            }
+            const float lse = m + logf(s);
+            loss += lse - zt;
+#pragma unroll
+            for (int i = 0; i < CMAX; ++i)
+                if (i < classes) dZ[static_cast<int64_t>(i) * lddz + c] = (expf(z[i] - lse) - (i == t ? 1.f : 0.f)) * inv_b;
+        } else {
+            float m = -INFINITY;
+            for (int i = 0; i < classes; ++i) m = fmaxf(m, Z[static_cast<int64_t>(i) * ldz + c]);
+            float s = 0.f;
+            for (int i = 0; i < classes; ++i) s += expf(Z[static_cast<int64_t>(i) * ldz + c] - m);
+            const float lse = m + logf(s);
+            loss += lse - Z[static_cast<int64_t>(t) * ldz + c];
+            for (int i = 0; i < classes; ++i) {
+                const float p = expf(Z[static_cast<int64_t>(i) * ldz + c] - lse);
+                dZ[static_cast<int64_t>(i) * lddz + c] = (p - (i == t ? 1.f : 0.f)) * inv_b;
+            }
         }
     }
-    partial[threadIdx.x] = loss;
+    loss = group_sum<kWave>(loss);  // every lane of every wave arrives here
+    if ((threadIdx.x & (kWave - 1)) == 0) wave_loss[threadIdx.x >> 6] = loss;
     __syncthreads();
-    for (int w = kSoftmaxBlock / 2; w >= 1; w >>= 1) {
-        if (static_cast<int>(threadIdx.x) < w) partial[threadIdx.x] += partial[threadIdx.x + w];
-        __syncthreads();
+    if (threadIdx.x == 0 && loss_out) {
+        float total = 0.f;
+        for (int w = 0; w < static_cast<int>(blockDim.x >> 6); ++w) total += wave_loss[w];
+        *loss_out = total * inv_b;
     }
-    if (threadIdx.x == 0 && loss_out) *loss_out = partial[0] * inv_b;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -567,6 +666,8 @@ hipError_t spmm_go(const SpmmArgs &a, hipStream_t s)
         hipLaunchKernelGGL((spmm_kernel<VEC, NV, true>), grid, dim3(kBlock), 0, s, a);
     else
         hipLaunchKernelGGL((spmm_kernel<VEC, NV, false>), grid, dim3(kBlock), 0, s, a);
+    if (a.blocks.n_huge_rows > 0)
+        hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -581,15 +682,84 @@ hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+bool spmm_vec_ok(const SpmmArgs &a)
+{
+    bool vec = a.ldx % 4 == 0 && a.ldy % 4 == 0 && aligned16(a.X) && aligned16(a.Y);
+    if (a.XM) vec = vec && a.ldxm % 4 == 0 && aligned16(a.XM);
+    if (a.YM) vec = vec && a.ldym % 4 == 0 && aligned16(a.YM);
+    return vec;
+}
+
+bool sddmm_vec_ok(const SddmmArgs &a)
+{
+    bool vec = a.lddz % 4 == 0 && aligned16(a.dZ);
+    if (!a.skip_products) vec = vec && a.ldx % 4 == 0 && aligned16(a.X);
+    if (a.ZM) vec = vec && a.ldzm % 4 == 0 && aligned16(a.ZM);
+    return vec;
+}
+
+template <int NV_S, int G, int NV_D>
+hipError_t pair_go(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
+{
+    const int na = a.blocks.n_blocks;
+    dim3 grid(na + b.blocks.n_blocks);
+    if (a.batch % 4 == 0)
+        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<NV_S, G, NV_D, true>), grid, dim3(kBlock), 0, s, a, b, na);
+    else
+        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<NV_S, G, NV_D, false>), grid, dim3(kBlock), 0, s, a, b, na);
+    if (a.blocks.n_huge_rows > 0)
+        hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int G, int NV_D>
+hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
+{
+    const int na = a.blocks.n_blocks;
+    dim3 grid(na + b.blocks.n_blocks);
+    if (a.batch % 4 == 0)
+        hipLaunchKernelGGL((sddmm_pair_kernel<G, NV_D, true>), grid, dim3(kBlock), 0, s, a, b, na);
+    else
+        hipLaunchKernelGGL((sddmm_pair_kernel<G, NV_D, false>), grid, dim3(kBlock), 0, s, a, b, na);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
+{
+    return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
+           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && sddmm_vec_ok(b);
+}
+
+bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
+{
+    return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && a.rows > 0 && b.rows > 0 &&
+           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && sddmm_vec_ok(a) && sddmm_vec_ok(b);
+}
+
+hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
+{
+    if (a.batch <= 64) return pair_go<1, 16, 1>(a, b, s);
+    if (a.batch <= 128) return pair_go<1, 16, 2>(a, b, s);
+    if (a.batch <= 256) return pair_go<1, 16, 4>(a, b, s);
+    if (a.batch <= 512) return pair_go<2, 64, 2>(a, b, s);
+    return pair_go<4, 64, 4>(a, b, s);
+}
+
+hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
+{
+    if (a.batch <= 64) return sddmm_pair_go<16, 1>(a, b, s);
+    if (a.batch <= 128) return sddmm_pair_go<16, 2>(a, b, s);
+    if (a.batch <= 256) return sddmm_pair_go<16, 4>(a, b, s);
+    if (a.batch <= 512) return sddmm_pair_go<64, 2>(a, b, s);
+    return sddmm_pair_go<64, 4>(a, b, s);
+}
 
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
-    bool vec = a.ldx % 4 == 0 && a.ldy % 4 == 0 && aligned16(a.X) && aligned16(a.Y);
-    if (a.XM) vec = vec && a.ldxm % 4 == 0 && aligned16(a.XM);
-    if (a.YM) vec = vec && a.ldym % 4 == 0 && aligned16(a.YM);
-    if (vec) {
+    if (spmm_vec_ok(a)) {
         if (a.batch <= 256) return spmm_go<4, 1>(a, s);
         if (a.batch <= 512) return spmm_go<4, 2>(a, s);
         return spmm_go<4, 4>(a, s);
@@ -602,10 +772,7 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
-    bool vec = a.lddz % 4 == 0 && aligned16(a.dZ);
-    if (!a.skip_products) vec = vec && a.ldx % 4 == 0 && aligned16(a.X);
-    if (a.ZM) vec = vec && a.ldzm % 4 == 0 && aligned16(a.ZM);
-    if (vec && a.batch <= 1024) {
+    if (sddmm_vec_ok(a) && a.batch <= 1024) {
         if (a.batch <= 64) return sddmm_go<16, 1>(a, s);
         if (a.batch <= 128) return sddmm_go<16, 2>(a, s);
         if (a.batch <= 256) return sddmm_go<16, 4>(a, s);
@@ -635,8 +802,14 @@ hipError_t launch_gather(float *values_t, const float *values, const int32_t *pe
 hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels, int32_t classes, int32_t batch,
                              float *dZ, int64_t lddz, float *loss, hipStream_t s)
 {
-    hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(kSoftmaxBlock), 0, s, Z, ldz, labels, classes, batch, dZ,
-                       lddz, loss);
+    int threads = (batch + kWave - 1) / kWave * kWave;
+    if (threads > kSoftmaxBlock) threads = kSoftmaxBlock;
+    if (classes <= 16)
+        hipLaunchKernelGGL(softmax_ce_kernel<16>, dim3(1), dim3(threads), 0, s, Z, ldz, labels, classes, batch, dZ,
+                           lddz, loss);
+    else
+        hipLaunchKernelGGL(softmax_ce_kernel<0>, dim3(1), dim3(threads), 0, s, Z, ldz, labels, classes, batch, dZ,
+                           lddz, loss);
     return hipGetLastError();
 }
 

@@ -82,6 +82,9 @@ SHAPES = [
     (40, 64, 0.3, 1100, None),       # beyond one column tile
     (1024, 3072, 0.01, 100, None),   # first layer of the paper's MLP at 99 % sparsity
     (10, 512, 0.1, 100, None),       # its last layer
+    (10, 2048, 1.0, 1024, None),     # dense rows cut over several work-groups (huge rows), wide batch
+    (12, 4096, 0.9, 100, None),      # huge rows at the paper's batch size
+    (6, 3000, 1.0, 37, 41),          # huge rows through the scalar kernels
 ]
 
 
@@ -91,7 +94,7 @@ def test_forward_parity(nb, torch_mod, oracle, rows, cols, density, batch, ld, r
     torch = torch_mod
     lay = layer_case(rows, cols, density, seed=rows + cols, relu=relu)
     X = np.random.default_rng(batch).standard_normal((cols, batch)).astype(np.float32)
-    L = nb.SparseLinear(lay)
+    L = nb.SparseLinear(lay, max_batch=batch)
     Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld)
     nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
     torch.cuda.synchronize()
@@ -111,7 +114,7 @@ def test_backward_parity(nb, torch_mod, oracle, rows, cols, density, batch, ld, 
     rng = np.random.default_rng(batch + 1)
     X = rng.standard_normal((cols, batch)).astype(np.float32)
     dY = rng.standard_normal((rows, batch)).astype(np.float32)
-    L = nb.SparseLinear(lay)
+    L = nb.SparseLinear(lay, max_batch=batch)
     Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld); dYd = nb.to_dense(dY, ld=ld)
     dXd = nb.dense(cols, batch, ld=ld)
     g = torch.full((max(lay.nnz, 1),), float("nan"), device="cuda")[:lay.nnz]
@@ -197,6 +200,11 @@ def test_shape_errors(nb, torch_mod):
         nb.sparse_linear_forward(L.handle, X, Y, 0)
     assert e.value.code == nb.NERVA_ERR_ARGUMENT
     L.close()
+    L = nb.SparseLinear(lay, max_batch=4)
+    with pytest.raises(nb.NervaError) as e:
+        nb.sparse_linear_forward(L.handle, X, Y, 8)         # beyond the batch the layer was created for
+    assert e.value.code == nb.NERVA_ERR_SHAPE
+    L.close()
 
 
 @pytest.mark.parametrize("n", [0, 1, 3, 4, 1000, 1027, 314573])
@@ -238,8 +246,8 @@ def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
     """Power-law rows (one full row, many empty ones): every share count of the row partition."""
     torch = torch_mod
     z = wl.make_zipf_matrix(1024, 0.02, seed=5)
-    _, _, info = nb.nerva_plan_rows_host(1024, z.indptr)
-    assert len(set((info & 0xFF).tolist())) >= 3
+    _, blocks, huge, nh = nb.nerva_plan_rows_host(1024, z.indptr)
+    assert len(set((blocks[nh:, 0] & 0xFF).tolist())) >= 3 and len(huge) >= 1
     for batch in (128, 100):
         rng = np.random.default_rng(batch)
         X = rng.standard_normal((1024, batch)).astype(np.float32)

@@ -68,50 +68,69 @@ def test_validate_csr_rejects_broken_patterns(nb):
 
 
 def _check_plan(nb, indptr, rows):
-    order, first, info = nb.nerva_plan_rows_host(rows, indptr)
-    assert sorted(order.tolist()) == list(range(rows))            # every row exactly once
+    order, blocks, huge, n_huge_blocks = nb.nerva_plan_rows_host(rows, indptr)
     W = nb.NERVA_WAVES_PER_BLOCK
     nnz = int(indptr[-1])
     target = min(64, max(8, nnz // 16384))
+    cap = target * W
+    row_nnz = np.diff(indptr)
+    huge_ids = huge[:, 0].tolist()
+    assert sorted(order.tolist() + huge_ids) == list(range(rows))           # every row exactly once
+    assert set(huge_ids) == set(np.nonzero(row_nnz > 4 * cap)[0].tolist())    # huge = far beyond one work-group
+    # huge work-groups come first and tile each huge row's entries exactly, in order
+    assert all(b[0] & nb.NERVA_HUGE_FLAG for b in blocks[:n_huge_blocks])
+    assert not any(b[0] & nb.NERVA_HUGE_FLAG for b in blocks[n_huge_blocks:])
+    for r, first, parts, _ in huge.tolist():
+        pos = int(indptr[r])
+        for q in range(parts):
+            info, row, b, e = blocks[first + q].tolist()
+            assert row == r and (info & ~nb.NERVA_HUGE_FLAG) == q and b == pos and b < e <= b + 2 * cap
+            pos = e
+        assert pos == int(indptr[r + 1])
+        assert parts == -(-int(row_nnz[r]) // (2 * cap))
     covered = 0
     prev_lg = 99
-    for f, inf in zip(first.tolist(), info.tolist()):
-        lg, n = inf & 0xFF, inf >> 8
+    for info, f, _, _ in blocks[n_huge_blocks:].tolist():
+        lg, n = info & 0xFF, info >> 8
         assert 1 <= n <= (W >> lg) and f == covered
         assert lg <= prev_lg                                       # heavy rows are served first
         prev_lg = lg
         for r in order[f:f + n]:
-            k = int(indptr[r + 1] - indptr[r])
-            per_wave = -(-k // (1 << lg))
-            assert per_wave <= target or (1 << lg) == W            # no wave above the target unless capped
+            k = int(row_nnz[r])
+            assert -(-k // (1 << lg)) <= (target if (1 << lg) < W else 4 * target)   # a full work-group may run 4x over
             if lg > 0:
                 assert -(-k // (1 << (lg - 1))) > target           # and no more waves than needed
         covered += n
-    assert covered == rows
-    return order, first, info
+    assert covered == len(order)
+    return order, blocks, huge, n_huge_blocks
 
 
 def test_row_plan_uniform_and_skewed(nb):
     mlp = wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9)
     for lay in mlp.layers:
         _check_plan(nb, lay.indptr, lay.rows)
-    # layer 1 at 90 %: 307 entries per row on average -> a whole work-group per row
-    _, first, info = nb.nerva_plan_rows_host(1024, mlp.layers[0].indptr)
-    assert len(first) == 1024 and set((info & 0xFF).tolist()) == {4}
+    # layer 1 at 90 %: 307 entries per row on average -> a whole work-group per row, none huge
+    _, blocks, huge, nh = nb.nerva_plan_rows_host(1024, mlp.layers[0].indptr)
+    assert len(blocks) == 1024 and set((blocks[:, 0] & 0xFF).tolist()) == {4} and nh == 0 and len(huge) == 0
     z = wl.make_zipf_matrix(1024, 0.02, seed=5)
-    order, first, info = _check_plan(nb, z.indptr, 1024)
-    assert len(set((info & 0xFF).tolist())) >= 3                   # several row classes in one matrix
+    order, blocks, huge, nh = _check_plan(nb, z.indptr, 1024)
+    assert len(set((blocks[nh:, 0] & 0xFF).tolist())) >= 3         # several row classes in one matrix
+    assert len(huge) >= 1 and nh >= 2                              # and rows cut over several work-groups
+    # the dense last layer of the wide MLP: every row is huge
+    dense = np.arange(0, 11 * 8192, 8192, dtype=np.int32)
+    order, blocks, huge, nh = _check_plan(nb, dense, 10)
+    assert len(order) == 0 and len(huge) == 10 and nh == len(blocks) == 320
     empty = np.zeros(11, dtype=np.int32)
-    order, first, info = _check_plan(nb, empty, 10)
-    assert len(first) == 1 and info[0] == (10 << 8)
+    order, blocks, huge, nh = _check_plan(nb, empty, 10)
+    assert len(blocks) == 1 and blocks[0, 0] == (10 << 8) and nh == 0
 
 
 def test_argument_errors_come_before_any_device_work(nb):
     lib = nb.lib
     h = ctypes.c_void_p()
-    assert lib.sparse_linear_create(None, 4, 4, 0, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
-    assert lib.sparse_linear_create(ctypes.addressof(h), 0, 4, 0, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
-    assert lib.sparse_linear_create(ctypes.addressof(h), 4, 4, 3, None, None, None, None, 0, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_create(None, 4, 4, 0, None, None, None, None, 0, 8, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_create(ctypes.addressof(h), 0, 4, 0, None, None, None, None, 0, 8, None) == nb.NERVA_ERR_ARGUMENT
+    assert lib.sparse_linear_create(ctypes.addressof(h), 4, 4, 3, None, None, None, None, 0, 8, None) == nb.NERVA_ERR_ARGUMENT
     assert lib.sparse_linear_forward(None, None, 4, None, 4, 4, None) == nb.NERVA_ERR_ARGUMENT
     assert lib.sparse_linear_backward(None, None, 0, None, 0, None, 0, None, 0, None, None, 4, None) == nb.NERVA_ERR_ARGUMENT
     assert lib.sgd_update_values(None, None, None, 5, 0.1, 0.9, None) == nb.NERVA_ERR_ARGUMENT
