@@ -84,10 +84,15 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz,
  *                               ordinary {lg | rows served << 8, first position of row_order, 0, 0}
  *                               huge     {NERVA_HUGE_FLAG | share index, row, first entry, end entry}
  *   huge_rows_host[4*nh]      per huge row {row, first work-group, number of work-groups, 0}
+ *   waves_host[4*16*nb]       the same partition per wave, 16 waves per work-group:
+ *                               {row or -1 (idle), first entry, end entry,
+ *                                share index in the work-group | lg << 4 | owner-of-row flag << 8 | huge << 9}
+ *                             shares of one row are contiguous, in order, multiples of 4 entries
  * nb <= rows + nnz / 128 and nh <= rows bound the sizes. */
 enum { NERVA_WAVES_PER_BLOCK = 16, NERVA_HUGE_FLAG = 0x40000000 };
 int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
-                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *counts_host);
+                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host,
+                         int32_t *counts_host);
 
 /* ---- layer -------------------------------------------------------------------------
  * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays

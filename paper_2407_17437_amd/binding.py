@@ -51,7 +51,7 @@ def _load() -> ctypes.CDLL:
         "nerva_last_error": (ctypes.c_char_p, []),
         "nerva_build_info": (ctypes.c_char_p, []),
         "nerva_validate_csr_host": (ctypes.c_int, [i32, i32, i64, vp, vp]),
-        "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp]),
+        "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp, vp]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
         "sparse_linear_mirror": (ctypes.c_int, [vp, vp, vp, vp, vp]),
@@ -121,17 +121,18 @@ def nerva_validate_csr_host(rows: int, cols: int, nnz: int, indptr, indices) -> 
 
 
 def nerva_plan_rows_host(rows: int, indptr):
-    """Returns (row_order, blocks[nb,4], huge_rows[nh,4], n_huge_blocks) as numpy int32 arrays."""
+    """Returns (row_order, blocks[nb,4], huge_rows[nh,4], n_huge_blocks, waves[nb,16,4]) as numpy int32 arrays."""
     import numpy as np
     indptr = np.ascontiguousarray(indptr, dtype=np.int32)
     counts = np.zeros(4, dtype=np.int32)
-    _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, None, None, None, counts.ctypes.data))
+    _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, None, None, None, None, counts.ctypes.data))
     order = np.empty(max(1, counts[0]), dtype=np.int32)
     blocks = np.empty((max(1, counts[1]), 4), dtype=np.int32)
     huge = np.empty((max(1, counts[2]), 4), dtype=np.int32)
+    waves = np.empty((max(1, counts[1]), NERVA_WAVES_PER_BLOCK, 4), dtype=np.int32)
     _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, order.ctypes.data, blocks.ctypes.data, huge.ctypes.data,
-                                    counts.ctypes.data))
-    return order[:counts[0]], blocks[:counts[1]], huge[:counts[2]], int(counts[3])
+                                    waves.ctypes.data, counts.ctypes.data))
+    return order[:counts[0]], blocks[:counts[1]], huge[:counts[2]], int(counts[3]), waves[:counts[1]]
 
 
 # ---- entry points, same names as the C ABI ------------------------------------------------

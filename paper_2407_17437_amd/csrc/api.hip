@@ -129,6 +129,7 @@ struct RowPlan {
     std::vector<int32_t> row_order;  // ordinary rows
     std::vector<int32_t> blocks;     // 4 ints per work-group, huge ones first
     std::vector<int32_t> huge_rows;  // 4 ints per huge row
+    std::vector<int32_t> waves;      // 4 ints per wave, kWavesPerBlock waves per work-group
     int32_t n_huge_blocks = 0;
     int32_t n_blocks() const { return static_cast<int32_t>(blocks.size() / 4); }
     int32_t n_huge_rows() const { return static_cast<int32_t>(huge_rows.size() / 4); }
@@ -179,6 +180,34 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr)
             P.blocks.insert(P.blocks.end(), {lg | (n_rows << 8), f, 0, 0});
         }
     }
+    // The same partition per wave: each of the 2^lg waves of a row takes a contiguous share of
+    // its entries, a multiple of 4 entries long (the kernels work on 1, 2 or 4 entries at a time).
+    P.waves.reserve(P.blocks.size() * kWavesPerBlock);
+    for (int32_t b = 0; b < P.n_blocks(); ++b) {
+        const int32_t info = P.blocks[4 * b], y = P.blocks[4 * b + 1];
+        const bool huge = (info & kHugeFlag) != 0;
+        const int lg = huge ? max_lg : (info & 0xff);
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const int part = w & ((1 << lg) - 1);
+            int32_t row = -1;
+            int64_t p0 = 0, p1 = 0;
+            bool lead = false;
+            if (huge) {
+                row = y; p0 = P.blocks[4 * b + 2]; p1 = P.blocks[4 * b + 3];
+                lead = w == 0 && (info & ~kHugeFlag) == 0;
+            } else if ((w >> lg) < (info >> 8)) {
+                row = P.row_order[y + (w >> lg)];
+                p0 = indptr[row]; p1 = indptr[row + 1];
+                lead = part == 0;
+            }
+            int64_t per = ((p1 - p0) + (1 << lg) - 1) >> lg;
+            per = (per + 3) / 4 * 4;
+            const int64_t s0 = p0 + part * per < p1 ? p0 + part * per : p1;
+            const int64_t s1 = s0 + per < p1 ? s0 + per : p1;
+            P.waves.insert(P.waves.end(), {row, static_cast<int32_t>(s0), static_cast<int32_t>(s1),
+                                           part | (lg << 4) | (lead ? 256 : 0) | (huge ? 512 : 0)});
+        }
+    }
     return P;
 }
 
@@ -189,6 +218,7 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, 
     // 16-byte records first so that they stay 16-byte aligned
     staging = P.blocks;
     staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
+    staging.insert(staging.end(), P.waves.begin(), P.waves.end());
     staging.insert(staging.end(), P.row_order.begin(), P.row_order.end());
     if (staging.empty()) staging.push_back(0);
     hipError_t e = hipMalloc(mem, staging.size() * 4);
@@ -196,7 +226,8 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, 
     e = hipMemcpyAsync(*mem, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, s);
     plan->blocks = reinterpret_cast<const int4 *>(*mem);
     plan->huge_rows = reinterpret_cast<const int4 *>(*mem + P.blocks.size());
-    plan->row_order = *mem + P.blocks.size() + P.huge_rows.size();
+    plan->waves = reinterpret_cast<const int4 *>(*mem + P.blocks.size() + P.huge_rows.size());
+    plan->row_order = *mem + P.blocks.size() + P.huge_rows.size() + P.waves.size();
     plan->n_blocks = P.n_blocks();
     plan->n_huge_rows = P.n_huge_rows();
     plan->n_huge_blocks = P.n_huge_blocks;
@@ -279,7 +310,7 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz, const int32
 }
 
 int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_order_host,
-                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *counts_host)
+                         int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host, int32_t *counts_host)
 {
     if (rows <= 0 || !indptr_host || !counts_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
     const RowPlan P = plan_rows(rows, indptr_host);
@@ -290,6 +321,7 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
     if (row_order_host && !P.row_order.empty()) memcpy(row_order_host, P.row_order.data(), P.row_order.size() * 4);
     if (blocks_host && !P.blocks.empty()) memcpy(blocks_host, P.blocks.data(), P.blocks.size() * 4);
     if (huge_rows_host && !P.huge_rows.empty()) memcpy(huge_rows_host, P.huge_rows.data(), P.huge_rows.size() * 4);
+    if (waves_host && !P.waves.empty()) memcpy(waves_host, P.waves.data(), P.waves.size() * 4);
     return NERVA_OK;
 }
 

@@ -18,6 +18,8 @@ struct RowBlocks {
     const int4 *blocks;        // [n_blocks] ordinary: {lg | rows served << 8, first slot of row_order, 0, 0}
                                //            huge:     {kHugeFlag | share index, row, first entry, end entry}
     const int4 *huge_rows;     // [n_huge_rows] {row, first work-group, number of work-groups, 0}
+    const int4 *waves;         // [n_blocks * kWavesPerBlock] the same partition spelled out per wave:
+                               // {row or -1, first entry, end entry, part | lg << 4 | lead << 8 | huge << 9}
     int32_t n_blocks;
     int32_t n_huge_rows;
     int32_t n_huge_blocks;

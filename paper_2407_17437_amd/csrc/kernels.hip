@@ -81,40 +81,21 @@ struct WaveTask {
     bool huge;   // the work-group holds one share of a huge row: its result is a partial sum
     bool lead;   // first wave of the row's first share (owner of per-row by-products)
 };
-// GRAIN: shares are multiples of GRAIN entries (the SDDMM works on GRAIN entries at a time).
+// One 16-byte scalar load per wave: the partition table is spelled out per wave when the
+// pattern is bound, so nothing about the row has to be looked up before its entries are fetched.
 template <int GRAIN>
-__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, const int32_t *indptr, int block)
+__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, const int32_t *, int block)
 {
-    const int4 d = b.blocks[block];
-    const int w = wave_in_block();
+    static_assert(GRAIN == 1 || GRAIN == 2 || GRAIN == 4, "shares are cut in multiples of 4 entries");
+    const int4 d = b.waves[block * kWavesPerBlock + wave_in_block()];
     WaveTask t;
-    int p0, p1;
-    if (d.x & kHugeFlag) {
-        t.huge = true;
-        t.lg = 4;
-        static_assert(kWavesPerBlock == 16, "a huge-row work-group spreads one share over all 16 waves");
-        t.part = w;
-        t.row = d.y;
-        p0 = d.z;
-        p1 = d.w;
-        t.lead = w == 0 && (d.x & ~kHugeFlag) == 0;
-    } else {
-        t.huge = false;
-        t.lg = d.x & 0xff;
-        const int slot = w >> t.lg;
-        t.part = w & ((1 << t.lg) - 1);
-        t.row = slot < (d.x >> 8) ? b.row_order[d.y + slot] : -1;
-        p0 = p1 = 0;
-        if (t.row >= 0) {
-            p0 = indptr[t.row];
-            p1 = indptr[t.row + 1];
-        }
-        t.lead = t.part == 0;
-    }
-    int per = ((p1 - p0) + (1 << t.lg) - 1) >> t.lg;
-    per = (per + GRAIN - 1) / GRAIN * GRAIN;
-    t.s0 = min(p0 + t.part * per, p1);
-    t.s1 = min(t.s0 + per, p1);
+    t.row = d.x;
+    t.s0 = d.y;
+    t.s1 = d.z;
+    t.part = d.w & 15;
+    t.lg = (d.w >> 4) & 15;
+    t.lead = (d.w >> 8) & 1;
+    t.huge = (d.w >> 9) & 1;
     return t;
 }
 
@@ -296,6 +277,120 @@ __device__ __forceinline__ void spmm_body(const SpmmArgs &a, const int block, co
     }
 }
 
+// SpMM for batches of at most GS*4 columns, GS in {16, 32}: a gather instruction costs the
+// memory pipeline the same whether 25 or 64 lanes take part, so each group of GS lanes works on
+// its own stored entry and one instruction fetches 64/GS rows of the dense operand.  Entries of
+// the wave's share are dealt to the groups round-robin; the groups' partial sums meet in LDS
+// together with those of the other waves of the row and are added in (wave, group) order.
+template <int GS, bool XMASK>
+__device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int block)
+{
+    constexpr int NE = kWave / GS;   // entries per gather instruction
+    constexpr int U = 8;             // gather instructions in flight (32 registers: two work-groups per compute unit)
+    __shared__ float red[kWavesPerBlock][4][kWave];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int grp = lane / GS;
+    const int lig = lane % GS;
+    const WaveTask task = wave_task<1>(a.blocks, a.indptr, block);
+    const int col = lig * 4;
+    const bool on = col < a.batch;
+    const uint32_t off = static_cast<uint32_t>(on ? col : 0) * 4u;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+
+    if (task.row >= 0) {
+        const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
+        const uint32_t ldmb = XMASK ? static_cast<uint32_t>(a.ldxm) * 4u : 0u;
+        const char *Xb = reinterpret_cast<const char *>(a.X);
+        const char *Mb = reinterpret_cast<const char *>(a.XM);
+        const int bperm = grp * 4;
+        for (int pc = task.s0; pc < task.s1; pc += kWave) {
+            const int n = min(kWave, task.s1 - pc);
+            // entry pc+l of the chunk sits in lane l; step u hands entry u*NE+grp to group grp
+            const int my_j = lane < n ? a.indices[pc + lane] : 0;
+            const float my_w = lane < n ? a.values[pc + lane] : 0.f;
+            const int steps = (n + NE - 1) / NE;
+            for (int u0 = 0; u0 < steps; u0 += U) {
+                float4 x[U];
+                float w[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (u0 + u < steps) {  // wave-uniform
+                        const int src = bperm + (u0 + u) * NE * 4;
+                        const int j = __builtin_amdgcn_ds_bpermute(src, my_j);
+                        w[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, my_w)));
+                        x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if ((u0 + u) * NE + grp < n) {  // the last step may serve fewer groups
+                            x[u] = *reinterpret_cast<const float4 *>(Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb + off);
+                            if constexpr (XMASK)
+                                x[u] = keep_where_positive(x[u], *reinterpret_cast<const float4 *>(Mb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldmb + off));
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (u0 + u < steps && (u0 + u) * NE + grp < n) {
+                        acc[0] = fmaf(w[u], x[u].x, acc[0]);
+                        acc[1] = fmaf(w[u], x[u].y, acc[1]);
+                        acc[2] = fmaf(w[u], x[u].z, acc[2]);
+                        acc[3] = fmaf(w[u], x[u].w, acc[3]);
+                    }
+                }
+            }
+        }
+    }
+
+    // every wave leaves its 64 lanes' partial sums in LDS; the row's first wave adds them up
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[wv][k][lane] = acc[k];
+    __syncthreads();
+    if (task.row < 0 || task.part != 0 || grp != 0) return;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = 0.f;
+    for (int s = 0; s < (1 << task.lg); ++s)
+#pragma unroll
+        for (int g = 0; g < NE; ++g)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] += red[wv + s][k][g * GS + lig];
+    if (!on) return;
+
+    if (task.huge) {
+        float *sr = a.scratch + static_cast<int64_t>(block) * a.scratch_ld;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (col + k < a.batch) sr[col + k] = acc[k];
+        return;
+    }
+    const float b = a.bias ? a.bias[task.row] : 0.f;
+    float *yr = a.Y + static_cast<int64_t>(task.row) * a.ldy;
+    const float *ym = a.YM ? a.YM + static_cast<int64_t>(task.row) * a.ldym : nullptr;
+    float y[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        y[k] = acc[k] + b;
+        if (a.relu) y[k] = y[k] > 0.f ? y[k] : 0.f;
+    }
+    if (col + 4 <= a.batch) {
+        float4 o = make_float4(y[0], y[1], y[2], y[3]);
+        if (ym) o = keep_where_positive(o, ld4(ym + col));
+        st4(yr + col, o);
+    } else {
+        for (int k = 0; k < 4; ++k)
+            if (col + k < a.batch) {
+                float o = y[k];
+                if (ym) o = keep_where_positive(o, ym[col + k]);
+                yr[col + k] = o;
+            }
+    }
+}
+
+template <int GS, bool XMASK>
+__global__ __launch_bounds__(kBlock) void spmm_grouped_kernel(const SpmmArgs a)
+{
+    spmm_body_grouped<GS, XMASK>(a, blockIdx.x);
+}
+
 template <int VEC, int NV, bool XMASK>
 __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
 {
@@ -331,7 +426,7 @@ template <int G, int NV, bool EXACT4>
 __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
 {
     constexpr int NG = kWave / G;
-    constexpr int UI = NV >= 4 ? 2 : 4;
+    constexpr int UI = NV >= 4 ? 2 : (NV == 2 ? 4 : 8);   // 32 registers of gathered data: two 16-wave work-groups fit a compute unit
     const int lane = threadIdx.x & (kWave - 1);
     const WaveTask task = wave_task<NG>(a.blocks, a.indptr, block);
     if (task.row < 0) return;
@@ -388,60 +483,74 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
 
     for (int pc = s0; pc < s1; pc += kWave) {
         const int n = min(kWave, s1 - pc);
-        const int my_j = q_mine < n ? a.indices[pc + q_mine] : 0;
+        const bool mine = q_mine < n;
+        const int p = pc + q_mine;
+        const int my_j = mine ? a.indices[p] : 0;
+        // operands of the fused update are requested now and used after the reductions
+        float w_old = 0.f, v_old = 0.f;
+        int mirror_pos = 0;
+        if (a.fused && mine) {
+            w_old = a.values[p];
+            v_old = a.velocity[p];
+            if (a.values_t) mirror_pos = a.pos_t[p];
+        }
         const int iters = (n + NG - 1) / NG;
         float res = 0.f;
-        // UI entries per group and pass: all index moves, then all gathers, then the dot products.
-        // Passes may run past `iters` (UI divides G): such slots read a valid row and land in lanes
-        // that are not stored.
+        // up to UI entries per group and pass: all index moves, then all gathers, then the dot products
         for (int it0 = 0; it0 < iters; it0 += UI) {
             float4 x[UI][NV];
 #pragma unroll
             for (int u = 0; u < UI; ++u) {
                 // group `grp` works on slot it*NG+grp, whose column index sits in lane grp*G+it
                 const int it = it0 + u;
-                if constexpr (G == kWave) {
-                    const gmem_ptr xr = row_base(a.X, __builtin_amdgcn_readlane(my_j, it), ldxb);
+                if (it < iters) {  // wave-uniform
+                    if constexpr (G == kWave) {
+                        const gmem_ptr xr = row_base(a.X, __builtin_amdgcn_readlane(my_j, it), ldxb);
 #pragma unroll
-                    for (int t = 0; t < NV; ++t) x[u][t] = gload<float4>(xr, off[t]);
-                } else {
-                    const int j = __builtin_amdgcn_ds_bpermute(bperm_base + it * 4, my_j);
-                    const char *xr = Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb;
+                        for (int t = 0; t < NV; ++t) x[u][t] = gload<float4>(xr, off[t]);
+                    } else {
+                        const int j = __builtin_amdgcn_ds_bpermute(bperm_base + it * 4, my_j);
 #pragma unroll
-                    for (int t = 0; t < NV; ++t) x[u][t] = *reinterpret_cast<const float4 *>(xr + off[t]);
+                        for (int t = 0; t < NV; ++t) x[u][t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (it * NG + grp < n) {  // the last pass may serve fewer groups
+                            const char *xr = Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb;
+#pragma unroll
+                            for (int t = 0; t < NV; ++t) x[u][t] = *reinterpret_cast<const float4 *>(xr + off[t]);
+                        }
+                    }
                 }
             }
 #pragma unroll
             for (int u = 0; u < UI; ++u) {
-                float part = 0.f;
+                if (it0 + u < iters) {
+                    float part = 0.f;
 #pragma unroll
-                for (int t = 0; t < NV; ++t) {
-                    if constexpr (!EXACT4) {
-                        // padding columns inside the access may hold anything, also NaN: drop them
-                        const int c = (t * G + lig) * 4;
-                        if (c + 1 >= a.batch) x[u][t].y = 0.f;
-                        if (c + 2 >= a.batch) x[u][t].z = 0.f;
-                        if (c + 3 >= a.batch) x[u][t].w = 0.f;
-                        if (c >= a.batch) x[u][t].x = 0.f;
+                    for (int t = 0; t < NV; ++t) {
+                        if constexpr (!EXACT4) {
+                            // padding columns inside the access may hold anything, also NaN: drop them
+                            const int c = (t * G + lig) * 4;
+                            if (c + 1 >= a.batch) x[u][t].y = 0.f;
+                            if (c + 2 >= a.batch) x[u][t].z = 0.f;
+                            if (c + 3 >= a.batch) x[u][t].w = 0.f;
+                            if (c >= a.batch) x[u][t].x = 0.f;
+                        }
+                        part = fmaf(dz[t].x, x[u][t].x, part);
+                        part = fmaf(dz[t].y, x[u][t].y, part);
+                        part = fmaf(dz[t].z, x[u][t].z, part);
+                        part = fmaf(dz[t].w, x[u][t].w, part);
                     }
-                    part = fmaf(dz[t].x, x[u][t].x, part);
-                    part = fmaf(dz[t].y, x[u][t].y, part);
-                    part = fmaf(dz[t].z, x[u][t].z, part);
-                    part = fmaf(dz[t].w, x[u][t].w, part);
+                    part = group_sum<G>(part);
+                    if (lig == it0 + u) res = part;
                 }
-                part = group_sum<G>(part);
-                if (lig == it0 + u) res = part;
             }
         }
-        if (q_mine < n) {
-            const int p = pc + q_mine;
+        if (mine) {
             if (a.g) a.g[p] = res;
             if (a.fused) {
-                float w = a.values[p], v = a.velocity[p];
-                momentum_step(w, v, res, a.lr, a.momentum);
-                a.values[p] = w;
-                a.velocity[p] = v;
-                if (a.values_t) a.values_t[a.pos_t[p]] = w;
+                momentum_step(w_old, v_old, res, a.lr, a.momentum);
+                a.values[p] = w_old;
+                a.velocity[p] = v_old;
+                if (a.values_t) a.values_t[mirror_pos] = w_old;
             }
         }
     }
@@ -455,13 +564,17 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
 
 // Two independent launches of a training step in one grid: work-groups [0, na) run the first,
 // the rest the second.  Saves a launch (and its drain) on the step's critical path.
-template <int NV_S, int G, int NV_D, bool EXACT4>
+template <int GS_S, int NV_S, int G, int NV_D, bool EXACT4>
 __global__ __launch_bounds__(kBlock) void spmm_sddmm_pair_kernel(const SpmmArgs a, const SddmmArgs b, const int na)
 {
-    if (static_cast<int>(blockIdx.x) < na)
-        spmm_body<4, NV_S, false>(a, blockIdx.x, 0);
-    else
+    if (static_cast<int>(blockIdx.x) < na) {
+        if constexpr (GS_S < kWave)
+            spmm_body_grouped<GS_S, false>(a, blockIdx.x);
+        else
+            spmm_body<4, NV_S, false>(a, blockIdx.x, 0);
+    } else {
         sddmm_body<G, NV_D, EXACT4>(b, blockIdx.x - na);
+    }
 }
 template <int G, int NV_D, bool EXACT4>
 __global__ __launch_bounds__(kBlock) void sddmm_pair_kernel(const SddmmArgs a, const SddmmArgs b, const int na)
@@ -671,6 +784,19 @@ hipError_t spmm_go(const SpmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+template <int GS>
+hipError_t spmm_grouped_go(const SpmmArgs &a, hipStream_t s)
+{
+    dim3 grid(a.blocks.n_blocks);
+    if (a.XM)
+        hipLaunchKernelGGL((spmm_grouped_kernel<GS, true>), grid, dim3(kBlock), 0, s, a);
+    else
+        hipLaunchKernelGGL((spmm_grouped_kernel<GS, false>), grid, dim3(kBlock), 0, s, a);
+    if (a.blocks.n_huge_rows > 0)
+        hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 template <int G, int NV>
 hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
 {
@@ -698,15 +824,15 @@ bool sddmm_vec_ok(const SddmmArgs &a)
     return vec;
 }
 
-template <int NV_S, int G, int NV_D>
+template <int GS_S, int NV_S, int G, int NV_D>
 hipError_t pair_go(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
 {
     const int na = a.blocks.n_blocks;
     dim3 grid(na + b.blocks.n_blocks);
     if (a.batch % 4 == 0)
-        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<NV_S, G, NV_D, true>), grid, dim3(kBlock), 0, s, a, b, na);
+        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<GS_S, NV_S, G, NV_D, true>), grid, dim3(kBlock), 0, s, a, b, na);
     else
-        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<NV_S, G, NV_D, false>), grid, dim3(kBlock), 0, s, a, b, na);
+        hipLaunchKernelGGL((spmm_sddmm_pair_kernel<GS_S, NV_S, G, NV_D, false>), grid, dim3(kBlock), 0, s, a, b, na);
     if (a.blocks.n_huge_rows > 0)
         hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
     return hipGetLastError();
@@ -740,11 +866,11 @@ bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
 
 hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
 {
-    if (a.batch <= 64) return pair_go<1, 16, 1>(a, b, s);
-    if (a.batch <= 128) return pair_go<1, 16, 2>(a, b, s);
-    if (a.batch <= 256) return pair_go<1, 16, 4>(a, b, s);
-    if (a.batch <= 512) return pair_go<2, 64, 2>(a, b, s);
-    return pair_go<4, 64, 4>(a, b, s);
+    if (a.batch <= 64) return pair_go<16, 1, 16, 1>(a, b, s);
+    if (a.batch <= 128) return pair_go<32, 1, 16, 2>(a, b, s);
+    if (a.batch <= 256) return pair_go<64, 1, 16, 4>(a, b, s);
+    if (a.batch <= 512) return pair_go<64, 2, 64, 2>(a, b, s);
+    return pair_go<64, 4, 64, 4>(a, b, s);
 }
 
 hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
@@ -760,6 +886,8 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
     if (spmm_vec_ok(a)) {
+        if (a.batch <= 64) return spmm_grouped_go<16>(a, s);
+        if (a.batch <= 128) return spmm_grouped_go<32>(a, s);
         if (a.batch <= 256) return spmm_go<4, 1>(a, s);
         if (a.batch <= 512) return spmm_go<4, 2>(a, s);
         return spmm_go<4, 4>(a, s);

@@ -246,7 +246,7 @@ def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
     """Power-law rows (one full row, many empty ones): every share count of the row partition."""
     torch = torch_mod
     z = wl.make_zipf_matrix(1024, 0.02, seed=5)
-    _, blocks, huge, nh = nb.nerva_plan_rows_host(1024, z.indptr)
+    _, blocks, huge, nh, _ = nb.nerva_plan_rows_host(1024, z.indptr)
     assert len(set((blocks[nh:, 0] & 0xFF).tolist())) >= 3 and len(huge) >= 1
     for batch in (128, 100):
         rng = np.random.default_rng(batch)

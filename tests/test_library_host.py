@@ -68,8 +68,29 @@ def test_validate_csr_rejects_broken_patterns(nb):
 
 
 def _check_plan(nb, indptr, rows):
-    order, blocks, huge, n_huge_blocks = nb.nerva_plan_rows_host(rows, indptr)
+    order, blocks, huge, n_huge_blocks, waves = nb.nerva_plan_rows_host(rows, indptr)
     W = nb.NERVA_WAVES_PER_BLOCK
+    # per-wave table: the shares of every row tile its entries exactly once, in order, in multiples of 4
+    seen = {}
+    for b in range(len(blocks)):
+        for w in range(W):
+            row, s0, s1, fl = waves[b, w].tolist()
+            if row < 0:
+                assert s0 == s1
+                continue
+            assert indptr[row] <= s0 <= s1 <= indptr[row + 1]
+            end = blocks[b, 3] if blocks[b, 0] & nb.NERVA_HUGE_FLAG else indptr[row + 1]
+            assert (s1 - s0) % 4 == 0 or s1 == end
+            assert ((fl >> 9) & 1) == (1 if blocks[b, 0] & nb.NERVA_HUGE_FLAG else 0)
+            seen.setdefault(row, []).append((b, w, s0, s1, (fl >> 8) & 1))
+    assert sorted(seen) == list(range(rows))
+    for row, shares in seen.items():
+        pos = int(indptr[row])
+        for k, (b, w, s0, s1, lead) in enumerate(shares):       # table order = entry order
+            assert s0 == pos or s0 == s1 == int(indptr[row + 1])
+            pos = max(pos, s1)
+            assert lead == (1 if k == 0 else 0)                  # exactly one owner per row: its first share
+        assert pos == int(indptr[row + 1])
     nnz = int(indptr[-1])
     target = min(64, max(8, nnz // 16384))
     cap = target * W
@@ -110,7 +131,7 @@ def test_row_plan_uniform_and_skewed(nb):
     for lay in mlp.layers:
         _check_plan(nb, lay.indptr, lay.rows)
     # layer 1 at 90 %: 307 entries per row on average -> a whole work-group per row, none huge
-    _, blocks, huge, nh = nb.nerva_plan_rows_host(1024, mlp.layers[0].indptr)
+    _, blocks, huge, nh, _ = nb.nerva_plan_rows_host(1024, mlp.layers[0].indptr)
     assert len(blocks) == 1024 and set((blocks[:, 0] & 0xFF).tolist()) == {4} and nh == 0 and len(huge) == 0
     z = wl.make_zipf_matrix(1024, 0.02, seed=5)
     order, blocks, huge, nh = _check_plan(nb, z.indptr, 1024)
