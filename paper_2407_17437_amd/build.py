@@ -34,5 +34,20 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def build_microbench(verbose: bool = False) -> str:
+    """The stand-alone gather-rate measurement (not part of the library)."""
+    exe = os.path.join(PKG, "microbench_gather")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "microbench_gather.hip"), "-o", exe]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed")
+    return exe
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_microbench(verbose=True))

@@ -423,7 +423,7 @@ int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
     a.blocks = layer->plan; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
     a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
-    a.rows = layer->rows; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
+    a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
     HIP_TRY(launch_spmm(a, as_stream(stream)));
     return NERVA_OK;
 }
@@ -450,7 +450,7 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
         a.indptr = layer->indptr_t; a.indices = layer->indices_t; a.values = layer->values_t;
         a.X = dY; a.ldx = lddy;
         if (relu) { a.XM = Y; a.ldxm = ldy; }
-        a.Y = dX; a.ldy = lddx; a.rows = layer->cols; a.batch = batch;
+        a.Y = dX; a.ldy = lddx; a.rows = layer->cols; a.x_rows = layer->rows; a.batch = batch;
         HIP_TRY(launch_spmm(a, s));
     }
     if (dvalues || dbias) {
@@ -609,7 +609,7 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
         a.blocks = ly->plan; a.nnz = ly->nnz; a.scratch = ly->scratch; a.scratch_ld = ly->scratch_ld;
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
-        a.rows = ly->rows; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
+        a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
         {
             Timed tm(mlp->prof, s, "spmm_forward", static_cast<int>(l));
             HIP_TRY(launch_spmm(a, s));
@@ -665,7 +665,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         t.indptr = ly->indptr_t; t.indices = ly->indices_t; t.values = ly->values_t;
         t.X = dZ(l); t.ldx = L.ld; t.Y = dZ(l - 1); t.ldy = L.ld;
         t.YM = A(l - 1); t.ldym = L.ld;
-        t.rows = ly->cols; t.batch = batch;
+        t.rows = ly->cols; t.x_rows = ly->rows; t.batch = batch;
         return t;
     };
     auto make_S = [&](int l) {

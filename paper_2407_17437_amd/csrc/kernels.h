@@ -43,6 +43,7 @@ struct SpmmArgs {
     const float *YM;         // optional (rows, ldym): result is multiplied by [YM[i,c] > 0]
     int64_t ldym;
     int32_t rows;
+    int32_t x_rows;          // rows of the gathered operand (columns of the sparse matrix)
     int32_t batch;
     int32_t relu;            // clamp the result at zero
     int32_t nnz;             // length of indices/values

@@ -283,7 +283,7 @@ __device__ __forceinline__ void spmm_body(const SpmmArgs &a, const int block, co
 // the wave's share are dealt to the groups round-robin; the groups' partial sums meet in LDS
 // together with those of the other waves of the row and are added in (wave, group) order.
 template <int GS, bool XMASK>
-__device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int block)
+__device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int block, const int col0 = 0)
 {
     constexpr int NE = kWave / GS;   // entries per gather instruction
     constexpr int U = 8;             // gather instructions in flight (32 registers: two work-groups per compute unit)
@@ -294,9 +294,9 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
     const int grp = lane / GS;
     const int lig = lane % GS;
     const WaveTask task = wave_task<1>(a.blocks, a.indptr, block);
-    const int col = lig * 4;
+    const int col = col0 + lig * 4;
     const bool on = col < a.batch;
-    const uint32_t off = static_cast<uint32_t>(on ? col : 0) * 4u;
+    const uint32_t off = static_cast<uint32_t>(on ? col : col0) * 4u;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
 
     if (task.row >= 0) {
@@ -389,6 +389,29 @@ template <int GS, bool XMASK>
 __global__ __launch_bounds__(kBlock) void spmm_grouped_kernel(const SpmmArgs a)
 {
     spmm_body_grouped<GS, XMASK>(a, blockIdx.x);
+}
+
+// Column-tiled launch for dense operands that do not fit an L2: the batch is cut into tiles of
+// GS*4 columns, narrow enough that one tile of the whole operand (x_rows x GS*4 floats) stays
+// resident in a 4 MiB L2 while every stored entry gathers from it.  Work-groups are dealt to the
+// 8 XCDs round-robin by their id, so the id is decoded XCD-first: with 8 or more tiles each XCD
+// owns every 8th tile (each tile is fetched from HBM by one L2 only) and sweeps the row partition
+// once per tile; with fewer tiles every XCD walks all tiles in the same order.
+template <int GS, bool XMASK>
+__global__ __launch_bounds__(kBlock) void spmm_tiled_kernel(const SpmmArgs a, const int n_tiles, const int spread)
+{
+    const int nrb = a.blocks.n_blocks;
+    int tile, rb;
+    if (spread) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        tile = (k / nrb) * 8 + xcd;
+        rb = k % nrb;
+    } else {
+        tile = blockIdx.x / nrb;
+        rb = blockIdx.x % nrb;
+    }
+    if (tile >= n_tiles) return;
+    spmm_body_grouped<GS, XMASK>(a, rb, tile * GS * 4);
 }
 
 template <int VEC, int NV, bool XMASK>
@@ -797,6 +820,41 @@ hipError_t spmm_grouped_go(const SpmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// The gathered operand (and its mask) should stay in one 4 MiB L2 while it is being gathered
+// from: if the whole operand is too large for that, the batch is walked in column tiles of
+// 4 * (return value) columns.  0: no tiling.
+int spmm_tile_group(const SpmmArgs &a)
+{
+    const int64_t budget = (a.XM ? 5 : 10) * (1 << 18);  // 2.5 MiB (half of it with a mask operand)
+    const int64_t row_bytes = static_cast<int64_t>(a.x_rows) * 4;
+    if (a.x_rows <= 0 || row_bytes * a.batch <= budget) return 0;
+    if (static_cast<int64_t>(a.blocks.n_blocks) * ((a.batch + 31) / 32 + 8) >= (1ll << 31)) return 0;
+    if (row_bytes * 128 <= budget && a.batch > 128) return 32;
+    if (row_bytes * 64 <= budget && a.batch > 64) return 16;
+    // Narrower tiles multiply the per-wave set-up (one pass over the row partition per tile) by 32 or
+    // more; measured, that only pays when rows are long (a 16384^2 matrix at 10 % density gains 1.4x,
+    // at 1 % it loses).
+    if (a.batch > 32 && static_cast<int64_t>(a.nnz) >= static_cast<int64_t>(a.rows) * 1024) return 8;
+    return 0;
+}
+
+template <int GS>
+hipError_t spmm_tiled_go(const SpmmArgs &a, hipStream_t s)
+{
+    const int n_tiles = (a.batch + GS * 4 - 1) / (GS * 4);
+    const int spread = n_tiles >= 8;
+    const int64_t ids = spread ? static_cast<int64_t>((n_tiles + 7) / 8) * 8 * a.blocks.n_blocks
+                               : static_cast<int64_t>(n_tiles) * a.blocks.n_blocks;
+    dim3 grid(static_cast<unsigned>(ids));
+    if (a.XM)
+        hipLaunchKernelGGL((spmm_tiled_kernel<GS, true>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
+    else
+        hipLaunchKernelGGL((spmm_tiled_kernel<GS, false>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
+    if (a.blocks.n_huge_rows > 0)
+        hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 template <int G, int NV>
 hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
 {
@@ -855,7 +913,8 @@ hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
-           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && sddmm_vec_ok(b);
+           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && sddmm_vec_ok(b) &&
+           spmm_tile_group(a) == 0;
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
@@ -886,6 +945,12 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
     if (spmm_vec_ok(a)) {
+        switch (spmm_tile_group(a)) {
+            case 32: return spmm_tiled_go<32>(a, s);
+            case 16: return spmm_tiled_go<16>(a, s);
+            case 8: return spmm_tiled_go<8>(a, s);
+            default: break;
+        }
         if (a.batch <= 64) return spmm_grouped_go<16>(a, s);
         if (a.batch <= 128) return spmm_grouped_go<32>(a, s);
         if (a.batch <= 256) return spmm_go<4, 1>(a, s);
