@@ -171,10 +171,15 @@ def main() -> int:
             kernels.append({"kernel": name, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
                             "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})
         dom = max(kernels, key=lambda r: r["avg_us"])
+        # HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this same command
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
+        if os.path.exists(tpath) and not graphs and not args.unfused:
+            traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dom["kernel"])
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],
-                    "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": None,
-                    "timing": f"HIP events around each launch, {steps_done} steps"}
+                    "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": traffic,
+                    "timing": f"HIP events between the launches of a step, {steps_done} steps"}
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None

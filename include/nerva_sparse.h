@@ -209,11 +209,12 @@ int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch,
                 void *workspace, size_t workspace_bytes, void *stream);
 
 /* Per-kernel timing of mlp_train_step with HIP events, for benchmarks.  After
- * mlp_profile_enable(mlp, max_steps > 0) the next max_steps training steps record a pair of
- * events around every kernel launch on the step's stream (events are created on the fly: a
- * profiled step allocates, must not be captured in a graph, and runs slower than a plain one).
- * mlp_profile_read waits for the recorded events and returns, per launch slot of a step (in
- * launch order), the summed elapsed milliseconds over the recorded steps; the slots keep their
+ * mlp_profile_enable(mlp, max_steps > 0) the next max_steps training steps record an event
+ * before every kernel launch and one after the last, on the step's stream (events are created
+ * on the fly: a profiled step allocates, must not be captured in a graph, and runs slower than
+ * a plain one).  mlp_profile_read waits for the recorded events and returns, per launch slot of
+ * a step (in launch order), the elapsed milliseconds from its event to the next one, summed over
+ * the recorded steps (the launches of a step run back to back, so the slots add up to the step); the slots keep their
  * meaning until the next mlp_profile_enable.  mlp_profile_enable(mlp, 0) switches timing off
  * and frees the events.  Slot names look like "spmm_forward[0]", "sddmm_update[2]".
  *   n_slots_host, steps_host: HOST int32; ms_sum_host: HOST double[max_slots]. */

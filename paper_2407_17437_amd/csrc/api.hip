@@ -66,13 +66,15 @@ struct nerva_layer {
     int64_t scratch_ld = 0;
 };
 
-// Optional per-kernel timing of mlp_train_step: one pair of HIP events around every launch of
-// the first `max_steps` steps after mlp_profile_enable.
+// Optional per-kernel timing of mlp_train_step: one HIP event before every launch and one after
+// the last launch of each of the first `max_steps` steps after mlp_profile_enable.  A launch's
+// time is the span to the next event: kernels of a step run back to back on one stream, so the
+// spans add up to the step and each carries the cost of one event, not two.
 struct StepProfiler {
     bool on = false;
     int32_t max_steps = 0, step = 0, slot = 0;
     std::vector<std::string> names;    // one per launch of a step, in launch order
-    std::vector<hipEvent_t> events;    // [step][slot][begin, end], grown while recording
+    std::vector<hipEvent_t> events;    // [step][slot 0 .. n, end of step], grown while recording
     void release()
     {
         for (hipEvent_t e : events) (void)hipEventDestroy(e);
@@ -246,7 +248,7 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->pos_t);
 }
 
-// Brackets one launch with events while profiling is on; costs one branch otherwise.
+// Marks the start of one launch with an event while profiling is on; costs one branch otherwise.
 struct Timed {
     StepProfiler &P;
     hipStream_t s;
@@ -259,15 +261,10 @@ struct Timed {
             snprintf(buf, sizeof buf, "%s[%d]", kind, layer);
             P.names.push_back(buf);
         }
-        hipEvent_t b = nullptr, e = nullptr;
-        if (hipEventCreate(&b) != hipSuccess || hipEventCreate(&e) != hipSuccess) { live = false; return; }
+        hipEvent_t b = nullptr;
+        if (hipEventCreate(&b) != hipSuccess) { live = false; return; }
         P.events.push_back(b);
-        P.events.push_back(e);
         (void)hipEventRecord(b, s);
-    }
-    ~Timed()
-    {
-        if (live) (void)hipEventRecord(P.events.back(), s);
     }
 };
 
@@ -545,9 +542,10 @@ int mlp_profile_read(nerva_mlp *mlp, int32_t max_slots, int32_t *n_slots_host, d
     *n_slots_host = n;
     *steps_host = P.step;
     for (int32_t k = 0; k < n; ++k) ms_sum_host[k] = 0.0;
+    if (P.events.size() != static_cast<size_t>(P.step) * (n + 1)) return fail(NERVA_ERR_HIP, "event bookkeeping is inconsistent");
     for (int32_t t = 0; t < P.step; ++t)
         for (int32_t k = 0; k < n; ++k) {
-            const size_t i = (static_cast<size_t>(t) * n + k) * 2;
+            const size_t i = static_cast<size_t>(t) * (n + 1) + k;
             HIP_TRY(hipEventSynchronize(P.events[i + 1]));
             float ms = 0.f;
             HIP_TRY(hipEventElapsedTime(&ms, P.events[i], P.events[i + 1]));
@@ -746,7 +744,13 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             }
         }
     }
-    if (mlp->prof.on && mlp->prof.step < mlp->prof.max_steps) ++mlp->prof.step;
+    if (mlp->prof.on && mlp->prof.step < mlp->prof.max_steps) {
+        hipEvent_t e = nullptr;  // closes the last launch of the step
+        HIP_TRY(hipEventCreate(&e));
+        mlp->prof.events.push_back(e);
+        HIP_TRY(hipEventRecord(e, s));
+        ++mlp->prof.step;
+    }
     return NERVA_OK;
 }
 

@@ -214,3 +214,27 @@ def test_mlp_forward_and_errors(nb, torch_mod, oracle):
         nb.mlp_create([a.handle, b.handle], [a.velocity, b.velocity], [a.bias_velocity, b.bias_velocity], 8)
     assert e.value.code in (nb.NERVA_ERR_SHAPE, nb.NERVA_ERR_ARGUMENT)
     a.close(); b.close(); M.close()
+
+
+def test_step_profiler_slots(nb, torch_mod):
+    """Per-launch event timing: one slot per launch in launch order, and it does not change results."""
+    torch = torch_mod
+    mlp = wl.make_mlp((256, 128, 64, 10), sparsity=0.8)
+    Xs, Ts = wl.make_batches(256, 10, 100, 3, seed=13)
+    ref = nb.MLP(mlp, 100); M = nb.MLP(mlp, 100)
+    nb.mlp_profile_enable(M.handle, 2)
+    for t in range(3):                                   # the third step is past max_steps: not recorded
+        for m in (ref, M):
+            m.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), 100, 0.05, 0.9)
+    torch.cuda.synchronize()
+    steps, slots = nb.mlp_profile_read(M.handle)
+    assert steps == 2
+    names = [n for n, _ in slots]
+    assert names == ["spmm_forward[0]", "spmm_forward[1]", "spmm_forward[2]", "softmax_ce[2]", "spmm_transposed[2]",
+                     "spmm_transposed+sddmm_update[1]", "sddmm_update+sddmm_update[0]"]
+    assert all(0.0 < ms < 50.0 for _, ms in slots)
+    nb.mlp_profile_enable(M.handle, 0)
+    assert nb.mlp_profile_read(M.handle) == (0, [])
+    for a, b in zip(ref.layers, M.layers):
+        assert torch.equal(a.values, b.values) and torch.equal(a.velocity, b.velocity)
+    ref.close(); M.close()
