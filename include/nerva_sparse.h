@@ -148,6 +148,15 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx,
 int sgd_update_values(float *values, float *velocity, const float *grad, int64_t n,
                       float lr, float momentum, void *stream);
 
+/* The same step with Nesterov momentum, the optimiser of the paper's experiments (Section 5.1:
+ * momentum 0.9, Nesterov, no weight decay): the weight moves by the look-ahead of the velocity,
+ *     velocity[k] <- momentum * velocity[k] - lr * grad[k]
+ *     values[k]   <- values[k] + momentum * velocity[k] - lr * grad[k]
+ * For a constant lr this is the usual formulation buf <- momentum*buf + grad,
+ * values <- values - lr*(grad + momentum*buf) with velocity = -lr*buf. */
+int sgd_update_values_nesterov(float *values, float *velocity, const float *grad, int64_t n,
+                               float lr, float momentum, void *stream);
+
 /* Softmax cross-entropy on logits Z (classes, ldz), mean over the batch, and its gradient
  * divided by the batch size (Appendix B listing: loss.gradient(Y, T) / batch_size):
  *     lse_c = log sum_i exp Z[i,c]      (computed with the column maximum subtracted)
@@ -171,7 +180,9 @@ enum {
     /* Run S = A B^T, the momentum update and the mirror refresh as separate kernels that
      * store the gradient arrays in the workspace (the composition of the calls above),
      * instead of one fused kernel per layer that never stores dvalues. */
-    NERVA_MLP_UNFUSED = 1
+    NERVA_MLP_UNFUSED = 1,
+    /* Nesterov momentum (see sgd_update_values_nesterov) for weights and biases. */
+    NERVA_MLP_NESTEROV = 2
 };
 int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers,
                float *const *velocities, float *const *bias_velocities,

@@ -156,8 +156,9 @@ def softmax_ce(Z, labels, dtype=np.float32, want_S=True):
     return float(out[0]), float(out[1]), dZ, SdZ
 
 
-def momentum(w, v, g, lr, mu, Sg=None, dtype=np.float32):
-    """v <- mu v - lr g ; w <- w + v.  Returns new (w, v, Sw, Sv); inputs are not modified.
+def momentum(w, v, g, lr, mu, Sg=None, dtype=np.float32, nesterov=False):
+    """v <- mu v - lr g ; w <- w + v  (nesterov: w <- w + mu v_new - lr g).
+    Returns new (w, v, Sw, Sv); inputs are not modified.
     For float32 storage lr and mu are first rounded to float32, as a float argument would be."""
     w = _vec(w, dtype).copy(); v = _vec(v, dtype).copy(); g = _vec(g, dtype)
     n = w.shape[0]
@@ -167,7 +168,7 @@ def momentum(w, v, g, lr, mu, Sg=None, dtype=np.float32):
     Sg = None if Sg is None else _vec(Sg, np.float64)
     Sv = np.empty(n, dtype=np.float64); Sw = np.empty(n, dtype=np.float64)
     getattr(_load(), "oracle_momentum" + _suffix(dtype))(
-        I64(n), _p(w), _p(v), _p(g), DBL(lr), DBL(mu), _p(Sg), _p(Sv), _p(Sw))
+        I64(n), _p(w), _p(v), _p(g), DBL(lr), DBL(mu), I32(1 if nesterov else 0), _p(Sg), _p(Sv), _p(Sw))
     return w, v, Sw, Sv
 
 
@@ -203,7 +204,7 @@ def mlp_loss(state, X, labels, dtype=np.float64) -> float:
 
 
 def mlp_step(state, X, labels, lr, mu, dtype=np.float32, update=True,
-             relu_masks: Optional[Sequence[Optional[np.ndarray]]] = None):
+             relu_masks: Optional[Sequence[Optional[np.ndarray]]] = None, nesterov=False):
     """One iteration of the training loop (Appendix B listing), in place on `state`.
 
     feedforward -> loss gradient / batch size -> backpropagate (all gradients from the
@@ -237,8 +238,8 @@ def mlp_step(state, X, labels, lr, mu, dtype=np.float32, update=True,
     if update:
         Sw, Sv, Sbw, Sbv = [], [], [], []
         for l, st in enumerate(state):
-            st["values"], st["vel_w"], sw, sv = momentum(st["values"], st["vel_w"], g[l], lr, mu, Sg[l], dtype)
-            st["bias"], st["vel_b"], sbw, sbv = momentum(st["bias"], st["vel_b"], db[l], lr, mu, Sdb[l], dtype)
+            st["values"], st["vel_w"], sw, sv = momentum(st["values"], st["vel_w"], g[l], lr, mu, Sg[l], dtype, nesterov)
+            st["bias"], st["vel_b"], sbw, sbv = momentum(st["bias"], st["vel_b"], db[l], lr, mu, Sdb[l], dtype, nesterov)
             Sw.append(sw); Sv.append(sv); Sbw.append(sbw); Sbv.append(sbv)
         out.update(Sw=Sw, Sv=Sv, Sbw=Sbw, Sbv=Sbv)
     return out

@@ -20,14 +20,14 @@ LIB_PATH = os.path.join(_PKG, "libnerva_sparse.so")
 NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
-NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED = 0, 1
+NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV = 0, 1, 2
 NERVA_WAVES_PER_BLOCK = 16
 NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
     "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host",
     "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_mirror",
-    "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values",
+    "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_workspace_bytes",
     "mlp_workspace_layout", "mlp_train_step", "mlp_forward", "nerva_copy_f32",
     "mlp_profile_enable", "mlp_profile_read", "mlp_profile_slot_name",
@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
         "sparse_linear_forward": (ctypes.c_int, [vp, vp, i32, vp, i32, i32, vp]),
         "sparse_linear_backward": (ctypes.c_int, [vp, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp]),
         "sgd_update_values": (ctypes.c_int, [vp, vp, vp, i64, f32, f32, vp]),
+        "sgd_update_values_nesterov": (ctypes.c_int, [vp, vp, vp, i64, f32, f32, vp]),
         "softmax_cross_entropy": (ctypes.c_int, [vp, i32, vp, i32, i32, vp, i32, vp, vp]),
         "mlp_create": (ctypes.c_int, [vp, i32, vp, vp, vp, i32, i32]),
         "mlp_destroy": (None, [vp]),
@@ -168,6 +169,10 @@ def sparse_linear_backward(layer: int, X, Y, dY, dX, dvalues, dbias, batch: int,
 
 def sgd_update_values(values, velocity, grad, n: int, lr: float, momentum: float, stream=None) -> None:
     _check(lib.sgd_update_values(_ptr(values), _ptr(velocity), _ptr(grad), n, lr, momentum, _stream(stream)))
+
+
+def sgd_update_values_nesterov(values, velocity, grad, n: int, lr: float, momentum: float, stream=None) -> None:
+    _check(lib.sgd_update_values_nesterov(_ptr(values), _ptr(velocity), _ptr(grad), n, lr, momentum, _stream(stream)))
 
 
 def softmax_cross_entropy(Z, labels, classes: int, batch: int, dZ, loss_out, stream=None) -> None:

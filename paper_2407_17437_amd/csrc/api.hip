@@ -469,7 +469,16 @@ int sgd_update_values(float *values, float *velocity, const float *grad, int64_t
 {
     if (n < 0) return fail(NERVA_ERR_ARGUMENT, "n is negative");
     if (n > 0 && (!values || !velocity || !grad)) return fail(NERVA_ERR_ARGUMENT, "null argument");
-    HIP_TRY(launch_momentum(values, velocity, grad, n, lr, momentum, as_stream(stream)));
+    HIP_TRY(launch_momentum(values, velocity, grad, n, lr, momentum, 0, as_stream(stream)));
+    return NERVA_OK;
+}
+
+int sgd_update_values_nesterov(float *values, float *velocity, const float *grad, int64_t n, float lr, float momentum,
+                               void *stream)
+{
+    if (n < 0) return fail(NERVA_ERR_ARGUMENT, "n is negative");
+    if (n > 0 && (!values || !velocity || !grad)) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    HIP_TRY(launch_momentum(values, velocity, grad, n, lr, momentum, 1, as_stream(stream)));
     return NERVA_OK;
 }
 
@@ -492,7 +501,7 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     *out = nullptr;
     if (n_layers <= 0 || !layers || !velocities || !bias_velocities) return fail(NERVA_ERR_ARGUMENT, "null or empty layer list");
     if (max_batch <= 0) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive");
-    if (flags & ~NERVA_MLP_UNFUSED) return fail(NERVA_ERR_ARGUMENT, "unknown flags 0x%x", flags);
+    if (flags & ~(NERVA_MLP_UNFUSED | NERVA_MLP_NESTEROV)) return fail(NERVA_ERR_ARGUMENT, "unknown flags 0x%x", flags);
     for (int32_t l = 0; l < n_layers; ++l) {
         if (!layers[l]) return fail(NERVA_ERR_ARGUMENT, "layer %d is null", l);
         if (layers[l]->nnz > 0 && !velocities[l]) return fail(NERVA_ERR_ARGUMENT, "velocity of layer %d is null", l);
@@ -638,6 +647,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
     char *ws = static_cast<char *>(workspace);
     const int n = static_cast<int>(mlp->layers.size());
     const bool fused = !(mlp->flags & NERVA_MLP_UNFUSED);
+    const int nesterov = (mlp->flags & NERVA_MLP_NESTEROV) ? 1 : 0;
     auto A = [&](int l) { return reinterpret_cast<float *>(ws + L.A[l]); };
     auto dZ = [&](int l) { return reinterpret_cast<float *>(ws + L.dZ[l]); };
 
@@ -675,7 +685,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
         g.rows = ly->rows; g.batch = batch;
         if (fused) {
-            g.fused = 1; g.lr = lr; g.momentum = momentum;
+            g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
@@ -732,11 +742,11 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             }
             {
                 Timed tm(mlp->prof, s, "momentum_values", l);
-                HIP_TRY(launch_momentum(ly->values, mlp->vel[l], g.g, ly->nnz, lr, momentum, s));
+                HIP_TRY(launch_momentum(ly->values, mlp->vel[l], g.g, ly->nnz, lr, momentum, nesterov, s));
             }
             if (ly->bias) {
                 Timed tm(mlp->prof, s, "momentum_bias", l);
-                HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], g.db, ly->rows, lr, momentum, s));
+                HIP_TRY(launch_momentum(ly->bias, mlp->bias_vel[l], g.db, ly->rows, lr, momentum, nesterov, s));
             }
             if (l > 0) {
                 Timed tm(mlp->prof, s, "mirror_refresh", l);

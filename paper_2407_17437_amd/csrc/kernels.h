@@ -71,6 +71,7 @@ struct SddmmArgs {
     int32_t skip_products;   // only db is wanted: do not touch indptr/indices/X
     // fused momentum step (fused != 0): g/db are not stored unless non-null
     int32_t fused;
+    int32_t nesterov;
     float lr, momentum;
     float *values;           // [nnz]
     float *velocity;         // [nnz]
@@ -87,7 +88,7 @@ bool can_pair(const SddmmArgs &a, const SddmmArgs &b);
 hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s);
 hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s);
 
-hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu,
+hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu, int nesterov,
                            hipStream_t s);
 // values_t[q] = values[perm[q]]
 hipError_t launch_gather(float *values_t, const float *values, const int32_t *perm, int64_t n,

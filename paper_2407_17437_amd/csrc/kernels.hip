@@ -66,10 +66,12 @@ __device__ __forceinline__ float group_sum(float x)
 }
 
 // The momentum step of one element; the same expression in the fused and the stand-alone path.
-__device__ __forceinline__ void momentum_step(float &w, float &v, float g, float lr, float mu)
+// nesterov: the weight moves by the look-ahead mu*v_new - lr*g instead of v_new.
+__device__ __forceinline__ void momentum_step(float &w, float &v, float g, float lr, float mu, int nesterov)
 {
-    v = fmaf(mu, v, -(lr * g));
-    w = w + v;
+    const float step = lr * g;
+    v = fmaf(mu, v, -step);
+    w = nesterov ? w + fmaf(mu, v, -step) : w + v;
 }
 
 // Which row, and which contiguous run [s0, s1) of its stored entries, the calling wave serves.
@@ -489,7 +491,7 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
             if (a.db) a.db[row] = s;
             if (a.fused && a.bias) {
                 float w = a.bias[row], v = a.bias_velocity[row];
-                momentum_step(w, v, s, a.lr, a.momentum);
+                momentum_step(w, v, s, a.lr, a.momentum, a.nesterov);
                 a.bias[row] = w;
                 a.bias_velocity[row] = v;
             }
@@ -570,7 +572,7 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
         if (mine) {
             if (a.g) a.g[p] = res;
             if (a.fused) {
-                momentum_step(w_old, v_old, res, a.lr, a.momentum);
+                momentum_step(w_old, v_old, res, a.lr, a.momentum, a.nesterov);
                 a.values[p] = w_old;
                 a.velocity[p] = v_old;
                 if (a.values_t) a.values_t[mirror_pos] = w_old;
@@ -631,7 +633,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
             if (a.db) a.db[row] = s;
             if (a.fused && a.bias) {
                 float w = a.bias[row], v = a.bias_velocity[row];
-                momentum_step(w, v, s, a.lr, a.momentum);
+                momentum_step(w, v, s, a.lr, a.momentum, a.nesterov);
                 a.bias[row] = w;
                 a.bias_velocity[row] = v;
             }
@@ -654,7 +656,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
             if (a.g) a.g[p] = part;
             if (a.fused) {
                 float w = a.values[p], v = a.velocity[p];
-                momentum_step(w, v, part, a.lr, a.momentum);
+                momentum_step(w, v, part, a.lr, a.momentum, a.nesterov);
                 a.values[p] = w;
                 a.velocity[p] = v;
                 if (a.values_t) a.values_t[a.pos_t[p]] = w;
@@ -670,7 +672,7 @@ constexpr int kEwBlock = 256;
 
 __global__ __launch_bounds__(kEwBlock) void momentum_kernel(float *__restrict__ w, float *__restrict__ v,
                                                             const float *__restrict__ g, int64_t n,
-                                                            float lr, float mu, int vec4)
+                                                            float lr, float mu, int nesterov, int vec4)
 {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
     int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -679,24 +681,24 @@ __global__ __launch_bounds__(kEwBlock) void momentum_kernel(float *__restrict__ 
         for (int64_t k = i; k < n4; k += stride) {
             float4 ww = ld4(w + 4 * k), vv = ld4(v + 4 * k);
             const float4 gg = ld4(g + 4 * k);
-            momentum_step(ww.x, vv.x, gg.x, lr, mu);
-            momentum_step(ww.y, vv.y, gg.y, lr, mu);
-            momentum_step(ww.z, vv.z, gg.z, lr, mu);
-            momentum_step(ww.w, vv.w, gg.w, lr, mu);
+            momentum_step(ww.x, vv.x, gg.x, lr, mu, nesterov);
+            momentum_step(ww.y, vv.y, gg.y, lr, mu, nesterov);
+            momentum_step(ww.z, vv.z, gg.z, lr, mu, nesterov);
+            momentum_step(ww.w, vv.w, gg.w, lr, mu, nesterov);
             st4(v + 4 * k, vv);
             st4(w + 4 * k, ww);
         }
         i += n4 << 2;  // tail: elements 4*n4 .. n-1, one per thread of the first work-group
         if (i < n) {
             float ww = w[i], vv = v[i];
-            momentum_step(ww, vv, g[i], lr, mu);
+            momentum_step(ww, vv, g[i], lr, mu, nesterov);
             v[i] = vv;
             w[i] = ww;
         }
     } else {
         for (; i < n; i += stride) {
             float ww = w[i], vv = v[i];
-            momentum_step(ww, vv, g[i], lr, mu);
+            momentum_step(ww, vv, g[i], lr, mu, nesterov);
             v[i] = vv;
             w[i] = ww;
         }
@@ -976,12 +978,13 @@ hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu, hipStream_t s)
+hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float lr, float mu, int nesterov,
+                           hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     const int vec4 = aligned16(w) && aligned16(v) && aligned16(g);
     hipLaunchKernelGGL(momentum_kernel, dim3(elementwise_blocks(vec4 ? (n + 3) / 4 : n)), dim3(kEwBlock), 0, s,
-                       w, v, g, n, lr, mu, vec4);
+                       w, v, g, n, lr, mu, nesterov, vec4);
     return hipGetLastError();
 }
 

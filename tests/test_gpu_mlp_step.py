@@ -37,7 +37,7 @@ def snapshot(M):
             for l in M.layers]
 
 
-def stage_parity(nb, torch, oracle, M, mlp, before, X, labels, batch, lr, mu, unfused):
+def stage_parity(nb, torch, oracle, M, mlp, before, X, labels, batch, lr, mu, unfused, nesterov=False):
     """Compare one finished GPU step, stage by stage, with the oracle fed the GPU's inputs."""
     L = len(M.layers)
     A = [M.view("A", l, batch).cpu().numpy() for l in range(L)]
@@ -62,10 +62,10 @@ def stage_parity(nb, torch, oracle, M, mlp, before, X, labels, batch, lr, mu, un
         if unfused:
             worst = max(worst, close(M.view("g", l, batch).cpu().numpy(), g, Sg, what=f"g[{l}]"))
             worst = max(worst, close(M.view("db", l, batch).cpu().numpy(), db, Sdb, what=f"db[{l}]"))
-        w, v, Sw, Sv = oracle.momentum(before[l]["values"], before[l]["vel_w"], g, lr, mu, Sg)
+        w, v, Sw, Sv = oracle.momentum(before[l]["values"], before[l]["vel_w"], g, lr, mu, Sg, nesterov=nesterov)
         worst = max(worst, close(M.layers[l].velocity.cpu().numpy(), v, Sv, what=f"velocity[{l}]"))
         worst = max(worst, close(M.layers[l].values.cpu().numpy(), w, Sw, what=f"values[{l}]"))
-        b, bv, Sb, Sbv = oracle.momentum(before[l]["bias"], before[l]["vel_b"], db, lr, mu, Sdb)
+        b, bv, Sb, Sbv = oracle.momentum(before[l]["bias"], before[l]["vel_b"], db, lr, mu, Sdb, nesterov=nesterov)
         worst = max(worst, close(M.layers[l].bias_velocity.cpu().numpy(), bv, Sbv, what=f"bias_velocity[{l}]"))
         worst = max(worst, close(M.layers[l].bias.cpu().numpy(), b, Sb, what=f"bias[{l}]"))
     return worst
@@ -238,3 +238,28 @@ def test_step_profiler_slots(nb, torch_mod):
     for a, b in zip(ref.layers, M.layers):
         assert torch.equal(a.values, b.values) and torch.equal(a.velocity, b.velocity)
     ref.close(); M.close()
+
+
+@pytest.mark.parametrize("unfused", [False, True])
+def test_stage_parity_nesterov(nb, torch_mod, oracle, unfused):
+    """Nesterov momentum (the optimiser of the paper's experiments) with a learning rate that follows the
+    paper's step decay: the rate is an argument of every step."""
+    from paper_2407_17437_amd import schedule
+    torch = torch_mod
+    sizes, batch, mu = (100, 300, 50, 10), 100, 0.9
+    mlp = wl.make_mlp(sizes, sparsity=0.9, pattern_seed=110, value_seed=210, bias_std=0.1)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 4, seed=310)
+    flags = nb.NERVA_MLP_NESTEROV | (nb.NERVA_MLP_UNFUSED if unfused else 0)
+    M = nb.MLP(mlp, batch, flags)
+    plain = nb.MLP(mlp, batch)
+    lr0 = schedule.initial_learning_rate(0.1)
+    for t in range(4):
+        lr = schedule.learning_rate(t, 4, lr0)                   # 0.03, 0.03, 0.003, 0.0003
+        before = snapshot(M)
+        Xd = nb.to_dense(Xs[t]); lab = torch.as_tensor(Ts[t]).cuda()
+        M.train_step(Xd, lab, batch, lr, mu)
+        plain.train_step(Xd, lab, batch, lr, mu)
+        torch.cuda.synchronize()
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, lr, mu, unfused, nesterov=True)
+    assert not torch.equal(M.layers[0].values, plain.layers[0].values)     # the variant is really a different update
+    M.close(); plain.close()

@@ -209,15 +209,16 @@ def test_shape_errors(nb, torch_mod):
 
 @pytest.mark.parametrize("n", [0, 1, 3, 4, 1000, 1027, 314573])
 @pytest.mark.parametrize("offset", [0, 1])
-def test_sgd_update_parity(nb, torch_mod, oracle, n, offset):
+@pytest.mark.parametrize("nesterov", [False, True])
+def test_sgd_update_parity(nb, torch_mod, oracle, n, offset, nesterov):
     torch = torch_mod
     rng = np.random.default_rng(n + offset)
     w, v, g = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
     pad = lambda a: torch.as_tensor(np.concatenate([np.zeros(offset, np.float32), a])).cuda()[offset:]
     wd, vd, gd = pad(w), pad(v), pad(g)     # offset 1: not 16-byte aligned -> scalar kernel
-    nb.sgd_update_values(wd, vd, gd, n, 0.01, 0.9)
+    (nb.sgd_update_values_nesterov if nesterov else nb.sgd_update_values)(wd, vd, gd, n, 0.01, 0.9)
     torch.cuda.synchronize()
-    wr, vr, Sw, Sv = oracle.momentum(w, v, g, 0.01, 0.9)
+    wr, vr, Sw, Sv = oracle.momentum(w, v, g, 0.01, 0.9, nesterov=nesterov)
     close(vd.cpu().numpy(), vr, Sv, what="velocity")
     close(wd.cpu().numpy(), wr, Sw, what="values")
     assert np.array_equal(gd.cpu().numpy(), g)

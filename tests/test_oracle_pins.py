@@ -331,3 +331,41 @@ def test_oracle_threads_do_not_change_results(oracle):
     for l in range(3):
         assert np.array_equal(outs[0][1][l]["values"], outs[1][1][l]["values"])
         assert np.array_equal(outs[0][0]["dZ"][l], outs[1][0]["dZ"][l])
+
+
+@pytest.mark.parametrize("nesterov", [False, True])
+def test_momentum_matches_library_sgd(oracle, nesterov):
+    """torch.optim.SGD (momentum 0.9, no dampening, no weight decay; Nesterov or not) on the CPU, constant
+    learning rate: its buffer is -velocity/lr, its weights must follow the oracle's step for step."""
+    import torch
+    rng = np.random.default_rng(41)
+    n, lr, mu, T = 64, 0.03, 0.9, 15
+    w0 = rng.standard_normal(n)
+    grads = rng.standard_normal((T, n))
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, nesterov=nesterov)
+    w, v = w0.copy(), np.zeros(n)
+    for t in range(T):
+        p.grad = torch.tensor(grads[t], dtype=torch.float64)
+        opt.step()
+        w, v, _, _ = oracle.momentum(w, v, grads[t], lr, mu, dtype=np.float64, nesterov=nesterov)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-13), t
+        assert np.allclose(v, -lr * opt.state[p]["momentum_buffer"].numpy(), rtol=1e-12, atol=1e-14), t
+
+
+def test_nesterov_closed_forms(oracle):
+    rng = np.random.default_rng(43)
+    n = 20
+    w0, v0, g = rng.standard_normal(n), rng.standard_normal(n), rng.standard_normal(n)
+    # mu = 0: both variants are plain gradient descent
+    a = oracle.momentum(w0, v0, g, 0.05, 0.0, dtype=np.float64, nesterov=True)
+    b = oracle.momentum(w0, v0, g, 0.05, 0.0, dtype=np.float64, nesterov=False)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # one step from rest: v = -lr g, w = w0 - (1 + mu) lr g
+    w, v, Sw, Sv = oracle.momentum(w0, np.zeros(n), g, 0.1, 0.9, dtype=np.float64, nesterov=True)
+    assert np.allclose(v, -0.1 * g, rtol=1e-14) and np.allclose(w, w0 - 1.9 * 0.1 * g, rtol=1e-13, atol=1e-15)
+    assert np.allclose(Sw, np.abs(w0) + 1.9 * 0.1 * np.abs(g), rtol=1e-13)
+    # the velocity itself is the same in both variants
+    w2, v2, _, _ = oracle.momentum(w0, v0, g, 0.1, 0.9, dtype=np.float64, nesterov=False)
+    w3, v3, _, _ = oracle.momentum(w0, v0, g, 0.1, 0.9, dtype=np.float64, nesterov=True)
+    assert np.array_equal(v2, v3) and np.allclose(w3 - w2, 0.9 * v3 - 0.1 * g - v3, rtol=1e-12, atol=1e-15)

@@ -130,3 +130,19 @@ def test_batches_shape_and_labels():
     assert X.shape == (3, 3072, 100) and X.dtype == np.float32
     assert T.shape == (3, 100) and T.dtype == np.int32 and T.min() >= 0 and T.max() <= 9
     assert abs(float(X.mean())) < 0.01 and abs(float(X.std()) - 1) < 0.01
+
+
+def test_learning_rate_schedule_matches_table1_and_decay_rule():
+    from paper_2407_17437_amd import schedule
+    for dens, lr in GOLD["initial_learning_rate_by_density"]["value"].items():
+        assert schedule.initial_learning_rate(float(dens)) == lr
+    assert schedule.initial_learning_rate(0.02) == 0.1 and schedule.initial_learning_rate(0.3) == 0.01
+    rule = GOLD["lr_decay"]["value"]
+    E = rule["epochs"]
+    lrs = [schedule.learning_rate(e, E, 0.1) for e in range(E)]
+    assert lrs[0] == 0.1 and lrs[49] == 0.1                      # unchanged through the first half
+    assert lrs[50] == pytest.approx(0.01) and lrs[74] == pytest.approx(0.01)
+    assert lrs[75] == pytest.approx(0.001) and lrs[99] == pytest.approx(0.001)
+    assert sorted(set(round(x, 12) for x in lrs), reverse=True) == [0.1, 0.01, 0.001]
+    with pytest.raises(ValueError):
+        schedule.learning_rate(100, 100, 0.1)
