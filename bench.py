@@ -62,6 +62,48 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
     return 0.0
 
 
+def inference(args, np, torch, nb, wl) -> int:
+    """Batch-1 inference (Section 5.4 of the paper measures the time for one example): K forward passes, each on
+    its own resident example stored as a plain vector, microseconds per example."""
+    sizes, sparsity, er, _, _, desc = WORKLOADS[args.workload]
+    mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
+    pool = 256
+    Xs, _ = wl.make_batches(sizes[0], sizes[-1], 1, pool, seed=3000)
+    Xd = torch.as_tensor(Xs).cuda().contiguous()              # (pool, features, 1): leading dimension 1
+    M = nb.MLP(mlp, 1)
+    x_ptr, x_stride = Xd.data_ptr(), sizes[0] * 4
+
+    def run(first, count):
+        for k in range(first, first + count):
+            nb.mlp_forward(M.handle, x_ptr + (k % pool) * x_stride, 1, 1, M.workspace)
+
+    K, W = args.steps, args.warmup
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, K)
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        st = oracle.new_state(mlp.layers, np.float32)
+        n = 50
+        t = time.perf_counter()
+        for k in range(n):
+            oracle.mlp_forward(st, Xs[k % pool], np.float32)
+        dt = time.perf_counter() - t
+        cpu = {"value": round(dt / n * 1e6, 1), "unit": "us/example", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{n} forward passes on single examples"}
+    print(json.dumps({"metric": "batch-1 inference time", "value": round(sec / K * 1e6, 3), "unit": "us/example",
+                      "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"{args.workload}, forward only, batch 1: {desc}",
+                                 "layer_nnz": [l.nnz for l in mlp.layers]},
+                      "cpu_baseline": cpu}))
+    M.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,6 +114,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0: skip)")
     ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--inference", action="store_true",
+                    help="instead of training steps: forward passes on ONE example (batch 1), microseconds per example")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
@@ -85,6 +129,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+    if args.inference:
+        return inference(args, np, torch, nb, wl)
     sizes, sparsity, er, batch, pool, desc = WORKLOADS[args.workload]
     mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
     Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, pool, seed=3000)

@@ -422,6 +422,61 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(const SpmmArgs a)
     spmm_body<VEC, NV, XMASK>(a, blockIdx.x, blockIdx.y);
 }
 
+// SpMM for batches of at most 4 columns (inference on one or a few examples): there is no batch
+// dimension to spread lanes over, so lanes run across the stored entries of the wave's share
+// instead -- coalesced index/weight reads, a 4-byte gather per entry and column, a DPP sum over
+// the wave, and the usual ordered LDS combine of the row's shares.  Any leading dimension.
+template <int NB>
+__global__ __launch_bounds__(kBlock) void spmv_kernel(const SpmmArgs a)
+{
+    __shared__ float red[kWavesPerBlock][NB];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const WaveTask task = wave_task<1>(a.blocks, a.indptr, blockIdx.x);
+    float acc[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) acc[c] = 0.f;
+    if (task.row >= 0) {
+        for (int p = task.s0 + lane; p < task.s1; p += kWave) {
+            const int64_t j = a.indices[p];
+            const float w = a.values[p];
+            const float *xr = a.X + j * a.ldx;
+            const float *mr = a.XM ? a.XM + j * a.ldxm : nullptr;
+#pragma unroll
+            for (int c = 0; c < NB; ++c)
+                if (c < a.batch) {
+                    float x = xr[c];
+                    if (mr) x = keep_where_positive(x, mr[c]);
+                    acc[c] = fmaf(w, x, acc[c]);
+                }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NB; ++c) acc[c] = group_sum<kWave>(acc[c]);  // all lanes of every wave take part
+    if (task.lg > 0) {
+        if (lane == 0)
+#pragma unroll
+            for (int c = 0; c < NB; ++c) red[wv][c] = acc[c];
+        __syncthreads();
+        if (task.part == 0)
+            for (int s = 1; s < (1 << task.lg); ++s)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) acc[c] += red[wv + s][c];
+    }
+    if (task.row < 0 || task.part != 0 || lane >= a.batch || lane >= NB) return;
+    float y = acc[0];
+#pragma unroll
+    for (int c = 1; c < NB; ++c) y = lane == c ? acc[c] : y;
+    if (task.huge) {
+        a.scratch[static_cast<int64_t>(blockIdx.x) * a.scratch_ld + lane] = y;
+        return;
+    }
+    y += a.bias ? a.bias[task.row] : 0.f;
+    if (a.relu) y = y > 0.f ? y : 0.f;
+    if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(task.row) * a.ldym + lane]);
+    a.Y[static_cast<int64_t>(task.row) * a.ldy + lane] = y;
+}
+
 // Second pass for huge rows: adds the partial rows of a row's work-groups in share order, then
 // bias, ReLU and the optional output mask.  One thread per column.
 __global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
@@ -914,7 +969,7 @@ hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
-    return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
+    return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && sddmm_vec_ok(b) &&
            spmm_tile_group(a) == 0;
 }
@@ -946,6 +1001,15 @@ hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    if (a.batch <= 4) {
+        if (a.batch == 1)
+            hipLaunchKernelGGL(spmv_kernel<1>, dim3(a.blocks.n_blocks), dim3(kBlock), 0, s, a);
+        else
+            hipLaunchKernelGGL(spmv_kernel<4>, dim3(a.blocks.n_blocks), dim3(kBlock), 0, s, a);
+        if (a.blocks.n_huge_rows > 0)
+            hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, 1), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
     if (spmm_vec_ok(a)) {
         switch (spmm_tile_group(a)) {
             case 32: return spmm_tiled_go<32>(a, s);

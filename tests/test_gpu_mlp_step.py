@@ -263,3 +263,23 @@ def test_stage_parity_nesterov(nb, torch_mod, oracle, unfused):
         stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, lr, mu, unfused, nesterov=True)
     assert not torch.equal(M.layers[0].values, plain.layers[0].values)     # the variant is really a different update
     M.close(); plain.close()
+
+
+@pytest.mark.parametrize("batch,ld", [(1, 1), (1, 32), (3, 4)])
+def test_mlp_forward_single_examples(nb, torch_mod, oracle, batch, ld):
+    """Inference on one (or a few) examples (Section 5.4 measures batch-1 inference)."""
+    torch = torch_mod
+    mlp = wl.make_mlp((3072, 1024, 512, 10), sparsity=0.95, bias_std=0.1)
+    Xs, _ = wl.make_batches(3072, 10, batch, 1, seed=14)
+    M = nb.MLP(mlp, 32)
+    logits = M.forward(nb.to_dense(Xs[0], ld=ld), batch)
+    torch.cuda.synchronize()
+    st = oracle.new_state(mlp.layers)
+    prev = Xs[0]
+    for l, lay in enumerate(mlp.layers):                       # every layer against the oracle fed the GPU's input
+        Y, S = oracle.spmm(lay.rows, lay.cols, lay.indptr, lay.indices, lay.values, lay.bias, prev, lay.relu)
+        got = M.view("A", l, batch).cpu().numpy()
+        close(got, Y, S, what=f"A[{l}] batch {batch}")
+        prev = got
+    assert logits.shape == (10, batch)
+    M.close()

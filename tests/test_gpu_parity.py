@@ -85,6 +85,11 @@ SHAPES = [
     (10, 2048, 1.0, 1024, None),     # dense rows cut over several work-groups (huge rows), wide batch
     (12, 4096, 0.9, 100, None),      # huge rows at the paper's batch size
     (6, 3000, 1.0, 37, 41),          # huge rows through the scalar kernels
+    (300, 200, 0.3, 1, 1),           # one example, stored as a plain vector: lanes across the row's entries
+    (1024, 3072, 0.1, 1, None),      # batch-1 inference on the first layer of the paper's MLP
+    (64, 4096, 0.9, 2, None),        # few columns and huge rows
+    (33, 65, 0.2, 4, 5),
+    (33, 65, 0.2, 3, None),
 ]
 
 
