@@ -457,7 +457,7 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
         a.dZ = dY; a.lddz = lddy;
         if (relu) { a.ZM = Y; a.ldzm = ldy; }
         a.X = X; a.ldx = ldx; a.g = dvalues; a.db = dbias;
-        a.rows = layer->rows; a.batch = batch;
+        a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch;
         a.skip_products = dvalues ? 0 : 1;  // only the bias gradient is wanted
         HIP_TRY(launch_sddmm(a, s));
     }
@@ -683,7 +683,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         g.indptr = ly->indptr; g.indices = ly->indices;
         g.dZ = dZ(l); g.lddz = L.ld;
         g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
-        g.rows = ly->rows; g.batch = batch;
+        g.rows = ly->rows; g.x_rows = ly->cols; g.batch = batch;
         if (fused) {
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];

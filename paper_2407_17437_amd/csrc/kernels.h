@@ -67,6 +67,7 @@ struct SddmmArgs {
     float *g;                // [nnz] or nullptr
     float *db;               // [rows] or nullptr
     int32_t rows;
+    int32_t x_rows;          // rows of X (columns of the sparse matrix)
     int32_t batch;
     int32_t skip_products;   // only db is wanted: do not touch indptr/indices/X
     // fused momentum step (fused != 0): g/db are not stored unless non-null

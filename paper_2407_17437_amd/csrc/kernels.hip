@@ -112,6 +112,7 @@ __device__ __forceinline__ gmem_ptr row_base(const void *base, int j, uint32_t l
     const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(addr >> 32));
     return reinterpret_cast<gmem_ptr>((static_cast<uint64_t>(hi) << 32) | lo);
 }
+__device__ __forceinline__ gmem_ptr as_gmem(const void *p) { return reinterpret_cast<gmem_ptr>(reinterpret_cast<uint64_t>(p)); }
 typedef float v4f __attribute__((ext_vector_type(4)));
 template <typename V>
 __device__ __forceinline__ V gload(gmem_ptr row, uint32_t byte_offset);
@@ -279,16 +280,52 @@ __device__ __forceinline__ void spmm_body(const SpmmArgs &a, const int block, co
     }
 }
 
-// SpMM for batches of at most GS*4 columns, GS in {16, 32}: a gather instruction costs the
+// One pass of U gather instructions of the grouped SpMM: every index move, then every gather,
+// then the FMAs.  Straight-line on purpose: with no branch between the gathers the compiler
+// counts outstanding loads exactly (vmcnt U-1 ... 0) and all U stay in flight; a branch inside
+// makes it wait for every earlier load before each later one.
+// src: byte address (lane * 4) of the lane that holds this group's entry of the pass's first
+// step; consecutive steps lie STEP_BYTES further on.
+template <int U, int STEP_BYTES, bool XMASK>
+__device__ __forceinline__ void grouped_pass(gmem_ptr Xg, gmem_ptr Mg, int src, int my_ro, int my_mo, float my_w,
+                                             uint32_t off, float (&acc)[4])
+{
+    uint32_t ro[U], mo[U];
+    float w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        ro[u] = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(src + u * STEP_BYTES, my_ro));
+        w[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src + u * STEP_BYTES, __builtin_bit_cast(int, my_w)));
+        if constexpr (XMASK) mo[u] = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(src + u * STEP_BYTES, my_mo));
+    }
+    float4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = gload<float4>(Xg, ro[u] + off);
+    if constexpr (XMASK) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = keep_where_positive(x[u], gload<float4>(Mg, mo[u] + off));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        acc[0] = fmaf(w[u], x[u].x, acc[0]);
+        acc[1] = fmaf(w[u], x[u].y, acc[1]);
+        acc[2] = fmaf(w[u], x[u].z, acc[2]);
+        acc[3] = fmaf(w[u], x[u].w, acc[3]);
+    }
+}
+
+// SpMM for batches of at most GS*4 columns, GS in {8, 16, 32}: a gather instruction costs the
 // memory pipeline the same whether 25 or 64 lanes take part, so each group of GS lanes works on
 // its own stored entry and one instruction fetches 64/GS rows of the dense operand.  Entries of
 // the wave's share are dealt to the groups round-robin; the groups' partial sums meet in LDS
 // together with those of the other waves of the row and are added in (wave, group) order.
+// Row offsets are 32-bit byte offsets from the operand's base: the operand (and its mask) must
+// span less than 4 GiB, which the launcher checks.
 template <int GS, bool XMASK>
 __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int block, const int col0 = 0)
 {
     constexpr int NE = kWave / GS;   // entries per gather instruction
-    constexpr int U = 8;             // gather instructions in flight (32 registers: two work-groups per compute unit)
+    constexpr int SB = NE * 4;       // lane-address distance between consecutive steps
     __shared__ float red[kWavesPerBlock][4][kWave];
 
     const int lane = threadIdx.x & (kWave - 1);
@@ -304,42 +341,33 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
     if (task.row >= 0) {
         const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
         const uint32_t ldmb = XMASK ? static_cast<uint32_t>(a.ldxm) * 4u : 0u;
-        const char *Xb = reinterpret_cast<const char *>(a.X);
-        const char *Mb = reinterpret_cast<const char *>(a.XM);
-        const int bperm = grp * 4;
+        const gmem_ptr Xg = as_gmem(a.X);
+        const gmem_ptr Mg = as_gmem(a.XM);
         for (int pc = task.s0; pc < task.s1; pc += kWave) {
             const int n = min(kWave, task.s1 - pc);
-            // entry pc+l of the chunk sits in lane l; step u hands entry u*NE+grp to group grp
-            const int my_j = lane < n ? a.indices[pc + lane] : 0;
-            const float my_w = lane < n ? a.values[pc + lane] : 0.f;
+            // Entry pc+l of the chunk sits in lane l; step u hands entry u*NE+grp to group grp.
+            // Lanes past the chunk's end repeat its first entry with weight 0: a gather of theirs
+            // reads a row this output row reads anyway, and adds nothing.
+            const int q = lane < n ? lane : 0;
+            const int my_j = a.indices[pc + q];
+            float my_w = a.values[pc + q];
+            my_w = lane < n ? my_w : 0.f;
+            const int my_ro = static_cast<int>(static_cast<uint32_t>(my_j) * ldxb);
+            const int my_mo = XMASK ? static_cast<int>(static_cast<uint32_t>(my_j) * ldmb) : 0;
             const int steps = (n + NE - 1) / NE;
-            for (int u0 = 0; u0 < steps; u0 += U) {
-                float4 x[U];
-                float w[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (u0 + u < steps) {  // wave-uniform
-                        const int src = bperm + (u0 + u) * NE * 4;
-                        const int j = __builtin_amdgcn_ds_bpermute(src, my_j);
-                        w[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src, __builtin_bit_cast(int, my_w)));
-                        x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if ((u0 + u) * NE + grp < n) {  // the last step may serve fewer groups
-                            x[u] = *reinterpret_cast<const float4 *>(Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb + off);
-                            if constexpr (XMASK)
-                                x[u] = keep_where_positive(x[u], *reinterpret_cast<const float4 *>(Mb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldmb + off));
-                        }
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (u0 + u < steps && (u0 + u) * NE + grp < n) {
-                        acc[0] = fmaf(w[u], x[u].x, acc[0]);
-                        acc[1] = fmaf(w[u], x[u].y, acc[1]);
-                        acc[2] = fmaf(w[u], x[u].z, acc[2]);
-                        acc[3] = fmaf(w[u], x[u].w, acc[3]);
-                    }
-                }
+            int src = grp * 4;
+            int u0 = 0;
+            for (; u0 + 8 <= steps; u0 += 8, src += 8 * SB)
+                grouped_pass<8, SB, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+            if (u0 + 4 <= steps) {
+                grouped_pass<4, SB, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+                u0 += 4; src += 4 * SB;
             }
+            if (u0 + 2 <= steps) {
+                grouped_pass<2, SB, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+                u0 += 2; src += 2 * SB;
+            }
+            if (u0 < steps) grouped_pass<1, SB, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
         }
     }
 
@@ -502,6 +530,52 @@ __global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
 // EXACT4: batch is a multiple of 4 (no column tail inside a 4-wide access).
 // Lanes whose columns lie beyond the batch hold dZ = 0 and re-read columns 0..3 of the row.
 // ---------------------------------------------------------------------------------------
+// One pass of the SDDMM over U stored entries per group: every index move, then every gather,
+// then the dot products and their reductions.  Straight-line, so that all U*NV gathers stay in
+// flight (see grouped_pass).  Group `grp` works on slot it*NG+grp of the chunk in iteration it;
+// that slot's row offset sits in lane grp*G+it, and its result is kept by the lane with lig == it.
+template <int G, int NV, bool EXACT4, int U>
+__device__ __forceinline__ void sddmm_pass(gmem_ptr Xg, int it0, int my_ro, const uint32_t (&off)[NV],
+                                           const float4 (&dz)[NV], int batch, float &res)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int lig = lane % G;
+    uint32_t ro[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (G == kWave)
+            ro[u] = static_cast<uint32_t>(__builtin_amdgcn_readlane(my_ro, it0 + u));
+        else
+            ro[u] = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(((lane / G) * G + it0 + u) * 4, my_ro));
+    }
+    float4 x[U][NV];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int t = 0; t < NV; ++t) x[u][t] = gload<float4>(Xg, ro[u] + off[t]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float part = 0.f;
+#pragma unroll
+        for (int t = 0; t < NV; ++t) {
+            if constexpr (!EXACT4) {
+                // padding columns inside the access may hold anything, also NaN: drop them
+                const int c = (t * G + lig) * 4;
+                if (c + 1 >= batch) x[u][t].y = 0.f;
+                if (c + 2 >= batch) x[u][t].z = 0.f;
+                if (c + 3 >= batch) x[u][t].w = 0.f;
+                if (c >= batch) x[u][t].x = 0.f;
+            }
+            part = fmaf(dz[t].x, x[u][t].x, part);
+            part = fmaf(dz[t].y, x[u][t].y, part);
+            part = fmaf(dz[t].z, x[u][t].z, part);
+            part = fmaf(dz[t].w, x[u][t].w, part);
+        }
+        part = group_sum<G>(part);
+        if (lig == it0 + u) res = part;
+    }
+}
+
 template <int G, int NV, bool EXACT4>
 __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
 {
@@ -557,73 +631,33 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
     const int s0 = task.s0;
     const int s1 = task.s1;
     const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
-    const char *Xb = reinterpret_cast<const char *>(a.X);
+    const gmem_ptr Xg = as_gmem(a.X);
     const int q_mine = lig * NG + grp;  // slot of this lane inside a chunk of 64 entries
-    const int bperm_base = grp * G * 4;
 
     for (int pc = s0; pc < s1; pc += kWave) {
         const int n = min(kWave, s1 - pc);
         const bool mine = q_mine < n;
-        const int p = pc + q_mine;
-        const int my_j = mine ? a.indices[p] : 0;
-        // operands of the fused update are requested now and used after the reductions
+        // lanes whose slot lies past the chunk's end work on its first entry and store nothing
+        const int p = pc + (mine ? q_mine : 0);
+        const int my_j = a.indices[p];
+        // operands of the fused update travel together with the column index
         float w_old = 0.f, v_old = 0.f;
         int mirror_pos = 0;
-        if (a.fused && mine) {
+        if (a.fused) {
             w_old = a.values[p];
             v_old = a.velocity[p];
             if (a.values_t) mirror_pos = a.pos_t[p];
         }
+        const int my_ro = static_cast<int>(static_cast<uint32_t>(my_j) * ldxb);
         const int iters = (n + NG - 1) / NG;
         float res = 0.f;
-        // up to UI entries per group and pass: all index moves, then all gathers, then the dot products
-        for (int it0 = 0; it0 < iters; it0 += UI) {
-            float4 x[UI][NV];
-#pragma unroll
-            for (int u = 0; u < UI; ++u) {
-                // group `grp` works on slot it*NG+grp, whose column index sits in lane grp*G+it
-                const int it = it0 + u;
-                if (it < iters) {  // wave-uniform
-                    if constexpr (G == kWave) {
-                        const gmem_ptr xr = row_base(a.X, __builtin_amdgcn_readlane(my_j, it), ldxb);
-#pragma unroll
-                        for (int t = 0; t < NV; ++t) x[u][t] = gload<float4>(xr, off[t]);
-                    } else {
-                        const int j = __builtin_amdgcn_ds_bpermute(bperm_base + it * 4, my_j);
-#pragma unroll
-                        for (int t = 0; t < NV; ++t) x[u][t] = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (it * NG + grp < n) {  // the last pass may serve fewer groups
-                            const char *xr = Xb + static_cast<uint64_t>(static_cast<uint32_t>(j)) * ldxb;
-#pragma unroll
-                            for (int t = 0; t < NV; ++t) x[u][t] = *reinterpret_cast<const float4 *>(xr + off[t]);
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < UI; ++u) {
-                if (it0 + u < iters) {
-                    float part = 0.f;
-#pragma unroll
-                    for (int t = 0; t < NV; ++t) {
-                        if constexpr (!EXACT4) {
-                            // padding columns inside the access may hold anything, also NaN: drop them
-                            const int c = (t * G + lig) * 4;
-                            if (c + 1 >= a.batch) x[u][t].y = 0.f;
-                            if (c + 2 >= a.batch) x[u][t].z = 0.f;
-                            if (c + 3 >= a.batch) x[u][t].w = 0.f;
-                            if (c >= a.batch) x[u][t].x = 0.f;
-                        }
-                        part = fmaf(dz[t].x, x[u][t].x, part);
-                        part = fmaf(dz[t].y, x[u][t].y, part);
-                        part = fmaf(dz[t].z, x[u][t].z, part);
-                        part = fmaf(dz[t].w, x[u][t].w, part);
-                    }
-                    part = group_sum<G>(part);
-                    if (lig == it0 + u) res = part;
-                }
-            }
-        }
+        int it = 0;
+        for (; it + UI <= iters; it += UI) sddmm_pass<G, NV, EXACT4, UI>(Xg, it, my_ro, off, dz, a.batch, res);
+        if constexpr (UI >= 8)
+            if (it + 4 <= iters) { sddmm_pass<G, NV, EXACT4, 4>(Xg, it, my_ro, off, dz, a.batch, res); it += 4; }
+        if constexpr (UI >= 4)
+            if (it + 2 <= iters) { sddmm_pass<G, NV, EXACT4, 2>(Xg, it, my_ro, off, dz, a.batch, res); it += 2; }
+        if (it < iters) sddmm_pass<G, NV, EXACT4, 1>(Xg, it, my_ro, off, dz, a.batch, res);
         if (mine) {
             if (a.g) a.g[p] = res;
             if (a.fused) {
@@ -923,6 +957,14 @@ hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// The grouped kernels address the gathered operand with 32-bit byte offsets from its base.
+inline bool spans_below_4gib(int64_t rows, int64_t ld) { return rows * ld * 4 < (1ll << 32); }
+
+bool spmm_offsets_ok(const SpmmArgs &a)
+{
+    return spans_below_4gib(a.x_rows, a.ldx) && (!a.XM || spans_below_4gib(a.x_rows, a.ldxm));
+}
+
 bool spmm_vec_ok(const SpmmArgs &a)
 {
     bool vec = a.ldx % 4 == 0 && a.ldy % 4 == 0 && aligned16(a.X) && aligned16(a.Y);
@@ -934,7 +976,7 @@ bool spmm_vec_ok(const SpmmArgs &a)
 bool sddmm_vec_ok(const SddmmArgs &a)
 {
     bool vec = a.lddz % 4 == 0 && aligned16(a.dZ);
-    if (!a.skip_products) vec = vec && a.ldx % 4 == 0 && aligned16(a.X);
+    if (!a.skip_products) vec = vec && a.ldx % 4 == 0 && aligned16(a.X) && spans_below_4gib(a.x_rows, a.ldx);
     if (a.ZM) vec = vec && a.ldzm % 4 == 0 && aligned16(a.ZM);
     return vec;
 }
@@ -970,8 +1012,8 @@ hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
-           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && sddmm_vec_ok(b) &&
-           spmm_tile_group(a) == 0;
+           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && spmm_offsets_ok(a) &&
+           sddmm_vec_ok(b) && spmm_tile_group(a) == 0;
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
@@ -1011,14 +1053,16 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
         return hipGetLastError();
     }
     if (spmm_vec_ok(a)) {
-        switch (spmm_tile_group(a)) {
-            case 32: return spmm_tiled_go<32>(a, s);
-            case 16: return spmm_tiled_go<16>(a, s);
-            case 8: return spmm_tiled_go<8>(a, s);
-            default: break;
+        if (spmm_offsets_ok(a)) {
+            switch (spmm_tile_group(a)) {
+                case 32: return spmm_tiled_go<32>(a, s);
+                case 16: return spmm_tiled_go<16>(a, s);
+                case 8: return spmm_tiled_go<8>(a, s);
+                default: break;
+            }
+            if (a.batch <= 64) return spmm_grouped_go<16>(a, s);
+            if (a.batch <= 128) return spmm_grouped_go<32>(a, s);
         }
-        if (a.batch <= 64) return spmm_grouped_go<16>(a, s);
-        if (a.batch <= 128) return spmm_grouped_go<32>(a, s);
         if (a.batch <= 256) return spmm_go<4, 1>(a, s);
         if (a.batch <= 512) return spmm_go<4, 2>(a, s);
         return spmm_go<4, 4>(a, s);
