@@ -59,6 +59,9 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
         return 12 * nnz
     if kind == "softmax_ce":
         return 8 * n * m + 4 * n
+    if kind == "spmm_forward+softmax_ce+spmm_transposed":
+        # pattern, mirror and both copies of the values; X in (also the ReLU mask); Z, dZ and dX out; bias, labels
+        return 16 * nnz + 4 * (m + 1) + 4 * (k + 1) + 4 * m + 4 * n * k + 8 * n * m + 4 * n + 4 * n * k
     return 0.0
 
 
@@ -114,6 +117,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0: skip)")
     ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--separate-head", action="store_true",
+                    help="keep the output layer's forward product, loss and transposed product as three launches")
     ap.add_argument("--inference", action="store_true",
                     help="instead of training steps: forward passes on ONE example (batch 1), microseconds per example")
     args = ap.parse_args()
@@ -138,7 +143,8 @@ def main() -> int:
     Xd = torch.zeros((pool, sizes[0], ld), dtype=torch.float32, device="cuda")
     Xd[:, :, :batch] = torch.as_tensor(Xs).cuda()
     Td = torch.as_tensor(Ts).cuda()
-    M = nb.MLP(mlp, batch, nb.NERVA_MLP_UNFUSED if args.unfused else nb.NERVA_MLP_DEFAULT)
+    M = nb.MLP(mlp, batch, (nb.NERVA_MLP_UNFUSED if args.unfused else 0) |
+               (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0))
     x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4
     t_ptr, t_stride = Td.data_ptr(), batch * 4
     lr, mu = 0.01, 0.9
@@ -207,8 +213,11 @@ def main() -> int:
         nb.mlp_profile_enable(M.handle, 0)
         for name, ms in slots:
             # "a+b[l]" is one grid that runs kernel a of layer l and kernel b of layer l+1
+            # (the three-part name is the fused head of the output layer: all of layer l)
             l = int(name.split("[")[1].rstrip("]"))
             kinds = name.split("[")[0].split("+")
+            if len(kinds) == 3:
+                kinds = ["+".join(kinds)]
             byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
             if len(kinds) == 2:
                 l2 = l + 1
@@ -220,7 +229,7 @@ def main() -> int:
         # HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this same command
         traffic = None
         tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
-        if os.path.exists(tpath) and not graphs and not args.unfused:
+        if os.path.exists(tpath) and not graphs and not args.unfused and not args.separate_head:
             traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dom["kernel"])
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],

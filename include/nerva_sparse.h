@@ -182,7 +182,12 @@ enum {
      * instead of one fused kernel per layer that never stores dvalues. */
     NERVA_MLP_UNFUSED = 1,
     /* Nesterov momentum (see sgd_update_values_nesterov) for weights and biases. */
-    NERVA_MLP_NESTEROV = 2
+    NERVA_MLP_NESTEROV = 2,
+    /* A small output layer (at most 32 rows and 8192 stored entries, as the 10-class layers
+     * of Section 5.1) normally runs its forward product, the softmax cross-entropy and its
+     * transposed product in one launch, each work-group owning four columns of the batch.
+     * This flag keeps the three separate launches that larger output layers always use. */
+    NERVA_MLP_SEPARATE_HEAD = 4
 };
 int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers,
                float *const *velocities, float *const *bias_velocities,

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_PKG, "libnerva_sparse.so")
 NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
-NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV = 0, 1, 2
+NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV, NERVA_MLP_SEPARATE_HEAD = 0, 1, 2, 4
 NERVA_WAVES_PER_BLOCK = 16
 NERVA_HUGE_FLAG = 0x40000000
 

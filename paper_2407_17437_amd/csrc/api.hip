@@ -91,6 +91,9 @@ struct nerva_mlp {
     std::vector<float *> bias_vel;
     int32_t max_batch = 0;
     int32_t flags = 0;
+    // fused head of a small output layer: per-column losses [max_batch]
+    bool head = false;
+    float *head_scratch = nullptr;
     StepProfiler prof;
 };
 
@@ -501,7 +504,7 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     *out = nullptr;
     if (n_layers <= 0 || !layers || !velocities || !bias_velocities) return fail(NERVA_ERR_ARGUMENT, "null or empty layer list");
     if (max_batch <= 0) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive");
-    if (flags & ~(NERVA_MLP_UNFUSED | NERVA_MLP_NESTEROV)) return fail(NERVA_ERR_ARGUMENT, "unknown flags 0x%x", flags);
+    if (flags & ~(NERVA_MLP_UNFUSED | NERVA_MLP_NESTEROV | NERVA_MLP_SEPARATE_HEAD)) return fail(NERVA_ERR_ARGUMENT, "unknown flags 0x%x", flags);
     for (int32_t l = 0; l < n_layers; ++l) {
         if (!layers[l]) return fail(NERVA_ERR_ARGUMENT, "layer %d is null", l);
         if (layers[l]->nnz > 0 && !velocities[l]) return fail(NERVA_ERR_ARGUMENT, "velocity of layer %d is null", l);
@@ -521,6 +524,18 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     m->bias_vel.assign(bias_velocities, bias_velocities + n_layers);
     m->max_batch = max_batch;
     m->flags = flags;
+    const nerva_layer *last = layers[n_layers - 1];
+    m->head = n_layers >= 2 && !(flags & NERVA_MLP_SEPARATE_HEAD) && head_ok(last->rows, last->cols, last->nnz);
+    if (m->head) {
+        const size_t bytes = static_cast<size_t>(max_batch) * 4;
+        hipError_t e = hipMalloc(&m->head_scratch, bytes);
+        if (e == hipSuccess) e = hipMemset(m->head_scratch, 0, bytes);
+        if (e != hipSuccess) {
+            if (m->head_scratch) (void)hipFree(m->head_scratch);
+            delete m;
+            return fail(NERVA_ERR_HIP, "head work space: %s", hipGetErrorString(e));
+        }
+    }
     *out = m;
     return NERVA_OK;
 }
@@ -529,6 +544,7 @@ void mlp_destroy(nerva_mlp *mlp)
 {
     if (!mlp) return;
     mlp->prof.release();
+    if (mlp->head_scratch) (void)hipFree(mlp->head_scratch);
     delete mlp;
 }
 
@@ -605,11 +621,11 @@ static int check_step_args(const nerva_mlp *mlp, const float *X, int32_t ldx, in
 }
 
 static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, char *ws, const Layout &L,
-                         hipStream_t s)
+                         hipStream_t s, size_t n_layers)
 {
     const float *in = X;
     int64_t ldin = ldx;
-    for (size_t l = 0; l < mlp->layers.size(); ++l) {
+    for (size_t l = 0; l < n_layers; ++l) {
         const nerva_layer *ly = mlp->layers[l];
         float *A = reinterpret_cast<float *>(ws + L.A[l]);
         SpmmArgs a{};
@@ -633,7 +649,7 @@ int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, void
     Layout L;
     int rc = check_step_args(mlp, X, ldx, batch, workspace, workspace_bytes, L);
     if (rc != NERVA_OK) return rc;
-    return forward_chain(mlp, X, ldx, batch, static_cast<char *>(workspace), L, as_stream(stream));
+    return forward_chain(mlp, X, ldx, batch, static_cast<char *>(workspace), L, as_stream(stream), mlp->layers.size());
 }
 
 int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
@@ -651,13 +667,23 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
     auto A = [&](int l) { return reinterpret_cast<float *>(ws + L.A[l]); };
     auto dZ = [&](int l) { return reinterpret_cast<float *>(ws + L.dZ[l]); };
 
-    // feedforward
-    rc = forward_chain(mlp, X, ldx, batch, ws, L, s);
-    if (rc != NERVA_OK) return rc;
-
-    // loss gradient / batch size
+    // feedforward, then the loss gradient / batch size
     const nerva_layer *last = mlp->layers[n - 1];
-    {
+    const bool head = mlp->head;
+    rc = forward_chain(mlp, X, ldx, batch, ws, L, s, head ? n - 1 : n);
+    if (rc != NERVA_OK) return rc;
+    if (head) {
+        // output layer, loss and the gradient handed to layer n-2 in one launch
+        HeadArgs h{};
+        h.indptr = last->indptr; h.indices = last->indices; h.values = last->values; h.bias = last->bias;
+        h.indptr_t = last->indptr_t; h.indices_t = last->indices_t; h.values_t = last->values_t;
+        h.rows = last->rows; h.cols = last->cols; h.batch = batch;
+        h.X = A(n - 2); h.ldx = L.ld; h.Z = A(n - 1); h.ldz = L.ld; h.labels = labels;
+        h.dZ = dZ(n - 1); h.lddz = L.ld; h.dX = dZ(n - 2); h.lddx = L.ld;
+        h.loss_cols = mlp->head_scratch;  // their mean is taken by the launch that runs S_{n-1}
+        Timed tm(mlp->prof, s, "spmm_forward+softmax_ce+spmm_transposed", n - 1);
+        HIP_TRY(launch_head(h, s));
+    } else {
         Timed tm(mlp->prof, s, "softmax_ce", n - 1);
         HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
     }
@@ -684,6 +710,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         g.dZ = dZ(l); g.lddz = L.ld;
         g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
         g.rows = ly->rows; g.x_rows = ly->cols; g.batch = batch;
+        if (head && l == n - 1 && loss_out) { g.loss_cols = mlp->head_scratch; g.loss_out = loss_out; g.loss_n = batch; }
         if (fused) {
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
@@ -700,7 +727,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         // Launch order T_{n-1} | T_{n-2} + S_{n-1} | ... | T_1 + S_2 | S_1 + S_0: the fused
         // SDDMM+update S_l of a layer shares a grid with the transposed product of the layer
         // below, which no longer depends on it (S_l only needs dZ_l and must follow T_l).
-        if (n > 1) {
+        if (n > 1 && !head) {
             Timed tm(mlp->prof, s, "spmm_transposed", n - 1);
             HIP_TRY(launch_spmm(make_T(n - 1), s));
         }
@@ -731,7 +758,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
     } else {
         for (int l = n - 1; l >= 0; --l) {
             nerva_layer *ly = mlp->layers[l];
-            if (l > 0) {
+            if (l > 0 && !(head && l == n - 1)) {
                 Timed tm(mlp->prof, s, "spmm_transposed", l);
                 HIP_TRY(launch_spmm(make_T(l), s));
             }

@@ -80,6 +80,12 @@ struct SddmmArgs {
     const int32_t *pos_t;    // CSR position -> mirror position (needed iff values_t)
     float *bias;             // [rows] or nullptr
     float *bias_velocity;    // [rows] or nullptr
+    // by-product, unrelated to the layer: *loss_out = mean(loss_cols[0..loss_n)), summed in one fixed
+    // order by the first wave of the launch.  The head kernel leaves one loss per batch column; a
+    // grid-wide sum inside it would need device-scope fences, which write back and invalidate the L2s.
+    const float *loss_cols;  // or nullptr
+    float *loss_out;
+    int32_t loss_n;
 };
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
 
@@ -97,5 +103,30 @@ hipError_t launch_gather(float *values_t, const float *values, const int32_t *pe
 hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels, int32_t classes,
                              int32_t batch, float *dZ, int64_t lddz, float *loss, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
+
+// The end of the forward pass and the start of the backward pass for a small output layer, in
+// one launch: logits Z = W X + b, softmax cross-entropy (loss and dZ = (softmax - onehot) / batch),
+// and the gradient handed to the layer below, dX = (W^T dZ) * [X > 0] (X is that layer's ReLU
+// output).  Every step is local to a column of the batch, so a work-group owns 4 columns.
+constexpr int kHeadMaxRows = 32;
+struct HeadArgs {
+    const int32_t *indptr, *indices;      // W in CSR (rows x cols)
+    const float *values, *bias;           // bias may be null
+    const int32_t *indptr_t, *indices_t;  // its mirror: CSR of W^T
+    const float *values_t;
+    int32_t rows, cols, batch;
+    const float *X;                       // (cols, ldx)
+    int64_t ldx;
+    float *Z;                             // (rows, ldz)
+    int64_t ldz;
+    const int32_t *labels;                // [batch]
+    float *dZ;                            // (rows, lddz)
+    int64_t lddz;
+    float *dX;                            // (cols, lddx)
+    int64_t lddx;
+    float *loss_cols;                     // [batch]: per-column losses; a later launch takes their mean (SddmmArgs)
+};
+bool head_ok(int32_t rows, int32_t cols, int32_t nnz);
+hipError_t launch_head(const HeadArgs &a, hipStream_t s);
 
 }  // namespace nerva

@@ -530,6 +530,17 @@ __global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
 // EXACT4: batch is a multiple of 4 (no column tail inside a 4-wide access).
 // Lanes whose columns lie beyond the batch hold dZ = 0 and re-read columns 0..3 of the row.
 // ---------------------------------------------------------------------------------------
+// By-product carried by an SDDMM launch: the mean of the per-column losses the head kernel left.
+__device__ __forceinline__ void mean_loss_task(const SddmmArgs &a, int block)
+{
+    if (!a.loss_cols || block != 0 || wave_in_block() != 0) return;  // wave-uniform
+    const int lane = threadIdx.x & (kWave - 1);
+    float s = 0.f;
+    for (int c = lane; c < a.loss_n; c += kWave) s += a.loss_cols[c];
+    s = group_sum<kWave>(s);
+    if (lane == 0) *a.loss_out = s / static_cast<float>(a.loss_n);
+}
+
 // One pass of the SDDMM over U stored entries per group: every index move, then every gather,
 // then the dot products and their reductions.  Straight-line, so that all U*NV gathers stay in
 // flight (see grouped_pass).  Group `grp` works on slot it*NG+grp of the chunk in iteration it;
@@ -582,6 +593,7 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
     constexpr int NG = kWave / G;
     constexpr int UI = NV >= 4 ? 2 : (NV == 2 ? 4 : 8);   // 32 registers of gathered data: two 16-wave work-groups fit a compute unit
     const int lane = threadIdx.x & (kWave - 1);
+    mean_loss_task(a, block);
     const WaveTask task = wave_task<NG>(a.blocks, a.indptr, block);
     if (task.row < 0) return;
     const int row = task.row;
@@ -704,6 +716,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_pair_kernel(const SddmmArgs a, c
 __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
+    mean_loss_task(a, blockIdx.x);
     const WaveTask task = wave_task<1>(a.blocks, a.indptr, blockIdx.x);
     if (task.row < 0) return;
     const int row = task.row;
@@ -871,6 +884,117 @@ __global__ __launch_bounds__(kSoftmaxBlock) void softmax_ce_kernel(const float *
         float total = 0.f;
         for (int w = 0; w < static_cast<int>(blockDim.x >> 6); ++w) total += wave_loss[w];
         *loss_out = total * inv_b;
+    }
+}
+
+// Output-layer head (see HeadArgs).  Forward: wave w takes rows w, w+16, ..., lanes run across
+// the row's stored entries, DPP sum.  Softmax-CE: one wave per column, one class per lane.
+// Transposed product: one thread per row of W^T, dZ read from LDS.  Each column's loss goes to
+// loss_cols; their mean is taken by a later launch of the step (SddmmArgs::loss_cols).
+constexpr int kHeadCols = 4;
+__device__ __forceinline__ float wave_max(float x)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) x = fmaxf(x, __shfl_xor(x, m, kWave));
+    return x;
+}
+__global__ __launch_bounds__(kBlock) void head_kernel(const HeadArgs a)
+{
+    __shared__ float z[kHeadMaxRows][kHeadCols];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int c0 = blockIdx.x * kHeadCols;
+    const int nc = min(kHeadCols, a.batch - c0);
+    const bool vec = nc == kHeadCols && a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0;
+
+    // Operands of the last phase are requested first: their latency passes behind the forward product.
+    const int j0 = threadIdx.x;
+    int q0 = 0, q1 = 0;
+    float mask[kHeadCols] = {0.f, 0.f, 0.f, 0.f};
+    if (j0 < a.cols) {
+        q0 = a.indptr_t[j0];
+        q1 = a.indptr_t[j0 + 1];
+        const float *mr = a.X + static_cast<int64_t>(j0) * a.ldx + c0;
+        if (vec) {
+            const float4 m = ld4(mr);
+            mask[0] = m.x; mask[1] = m.y; mask[2] = m.z; mask[3] = m.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < kHeadCols; ++c)
+                if (c < nc) mask[c] = mr[c];
+        }
+    }
+    const int label = wv < nc ? a.labels[c0 + wv] : 0;
+
+    for (int i = wv; i < a.rows; i += kWavesPerBlock) {
+        float acc[kHeadCols] = {0.f, 0.f, 0.f, 0.f};
+        for (int p = a.indptr[i] + lane; p < a.indptr[i + 1]; p += kWave) {
+            const float w = a.values[p];
+            const float *xr = a.X + static_cast<int64_t>(a.indices[p]) * a.ldx + c0;
+            if (vec) {
+                const float4 x = ld4(xr);
+                acc[0] = fmaf(w, x.x, acc[0]);
+                acc[1] = fmaf(w, x.y, acc[1]);
+                acc[2] = fmaf(w, x.z, acc[2]);
+                acc[3] = fmaf(w, x.w, acc[3]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < kHeadCols; ++c)
+                    if (c < nc) acc[c] = fmaf(w, xr[c], acc[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kHeadCols; ++c) acc[c] = group_sum<kWave>(acc[c]);
+        if (lane == 0) {
+            const float b = a.bias ? a.bias[i] : 0.f;
+#pragma unroll
+            for (int c = 0; c < kHeadCols; ++c) z[i][c] = acc[c] + b;
+        }
+    }
+    __syncthreads();
+
+    // softmax cross-entropy of column c0+wv by wave wv: one class per lane (rows <= 32)
+    if (wv < nc) {
+        const bool live = lane < a.rows;
+        const float zi = live ? z[lane][wv] : -INFINITY;
+        const float m = wave_max(zi);
+        const float lse = m + logf(group_sum<kWave>(live ? expf(zi - m) : 0.f));
+        const float zt = group_sum<kWave>(lane == label ? zi : 0.f);  // one non-zero term: exact
+        const float d = (expf(zi - lse) - (lane == label ? 1.f : 0.f)) / static_cast<float>(a.batch);
+        if (live) {
+            a.Z[static_cast<int64_t>(lane) * a.ldz + c0 + wv] = zi;
+            a.dZ[static_cast<int64_t>(lane) * a.lddz + c0 + wv] = d;
+            z[lane][wv] = d;
+        }
+        if (lane == 0) a.loss_cols[c0 + wv] = lse - zt;
+    }
+    __syncthreads();
+
+    for (int j = j0; j < a.cols; j += kBlock) {
+        if (j != j0) {
+            q0 = a.indptr_t[j];
+            q1 = a.indptr_t[j + 1];
+            const float *mr = a.X + static_cast<int64_t>(j) * a.ldx + c0;
+#pragma unroll
+            for (int c = 0; c < kHeadCols; ++c)
+                if (c < nc) mask[c] = mr[c];
+        }
+        float acc[kHeadCols] = {0.f, 0.f, 0.f, 0.f};
+        for (int q = q0; q < q1; ++q) {
+            const float w = a.values_t[q];
+            const int i = a.indices_t[q];
+#pragma unroll
+            for (int c = 0; c < kHeadCols; ++c) acc[c] = fmaf(w, z[i][c], acc[c]);
+        }
+        float *dr = a.dX + static_cast<int64_t>(j) * a.lddx + c0;
+        if (vec && a.lddx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.dX) & 15u) == 0) {
+            st4(dr, make_float4(keep_where_positive(acc[0], mask[0]), keep_where_positive(acc[1], mask[1]),
+                                keep_where_positive(acc[2], mask[2]), keep_where_positive(acc[3], mask[3])));
+        } else {
+#pragma unroll
+            for (int c = 0; c < kHeadCols; ++c)
+                if (c < nc) dr[c] = keep_where_positive(acc[c], mask[c]);
+        }
     }
 }
 
@@ -1114,6 +1238,18 @@ hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels,
     else
         hipLaunchKernelGGL(softmax_ce_kernel<0>, dim3(1), dim3(threads), 0, s, Z, ldz, labels, classes, batch, dZ,
                            lddz, loss);
+    return hipGetLastError();
+}
+
+// One work-group re-reads the whole layer for its 4 columns: only for layers of a few thousand entries.
+bool head_ok(int32_t rows, int32_t cols, int32_t nnz)
+{
+    return rows > 0 && rows <= kHeadMaxRows && cols > 0 && nnz <= 8192;
+}
+
+hipError_t launch_head(const HeadArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(head_kernel, dim3((a.batch + kHeadCols - 1) / kHeadCols), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 

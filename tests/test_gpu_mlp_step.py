@@ -83,11 +83,15 @@ CASES = [
 
 @pytest.mark.parametrize("sizes,kw,batch,steps", CASES)
 @pytest.mark.parametrize("unfused", [False, True])
-def test_stage_parity_small(nb, torch_mod, oracle, sizes, kw, batch, steps, unfused):
+@pytest.mark.parametrize("separate_head", [False, True])
+def test_stage_parity_small(nb, torch_mod, oracle, sizes, kw, batch, steps, unfused, separate_head):
+    """Every stage of a step against the oracle, with the output layer's forward product, loss
+    and transposed product in one launch (the default for small output layers) and as three."""
     torch = torch_mod
     mlp = wl.make_mlp(sizes, pattern_seed=100, value_seed=200, **kw)
     Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, steps, seed=300)
-    M = nb.MLP(mlp, batch, nb.NERVA_MLP_UNFUSED if unfused else nb.NERVA_MLP_DEFAULT)
+    flags = (nb.NERVA_MLP_UNFUSED if unfused else 0) | (nb.NERVA_MLP_SEPARATE_HEAD if separate_head else 0)
+    M = nb.MLP(mlp, batch, flags)
     for t in range(steps):
         before = snapshot(M)
         Xd = nb.to_dense(Xs[t]); lab = torch.as_tensor(Ts[t]).cuda()
@@ -230,7 +234,7 @@ def test_step_profiler_slots(nb, torch_mod):
     steps, slots = nb.mlp_profile_read(M.handle)
     assert steps == 2
     names = [n for n, _ in slots]
-    assert names == ["spmm_forward[0]", "spmm_forward[1]", "spmm_forward[2]", "softmax_ce[2]", "spmm_transposed[2]",
+    assert names == ["spmm_forward[0]", "spmm_forward[1]", "spmm_forward+softmax_ce+spmm_transposed[2]",
                      "spmm_transposed+sddmm_update[1]", "sddmm_update+sddmm_update[0]"]
     assert all(0.0 < ms < 50.0 for _, ms in slots)
     nb.mlp_profile_enable(M.handle, 0)
@@ -238,6 +242,39 @@ def test_step_profiler_slots(nb, torch_mod):
     for a, b in zip(ref.layers, M.layers):
         assert torch.equal(a.values, b.values) and torch.equal(a.velocity, b.velocity)
     ref.close(); M.close()
+    # the same network with the output layer's three launches kept apart
+    S = nb.MLP(mlp, 100, nb.NERVA_MLP_SEPARATE_HEAD)
+    nb.mlp_profile_enable(S.handle, 1)
+    S.train_step(nb.to_dense(Xs[0]), torch.as_tensor(Ts[0]).cuda(), 100, 0.05, 0.9)
+    torch.cuda.synchronize()
+    steps, slots = nb.mlp_profile_read(S.handle)
+    assert steps == 1
+    assert [n for n, _ in slots] == ["spmm_forward[0]", "spmm_forward[1]", "spmm_forward[2]", "softmax_ce[2]",
+                                     "spmm_transposed[2]", "spmm_transposed+sddmm_update[1]",
+                                     "sddmm_update+sddmm_update[0]"]
+    S.close()
+
+
+def test_head_loss_is_reproducible(nb, torch_mod):
+    """The fused head leaves one loss per column and a later launch of the step takes their mean in
+    a fixed order: many steps in a row give the same losses on two identical runs, also with a
+    batch that is not a multiple of the four columns a work-group owns."""
+    torch = torch_mod
+    for batch in (100, 37, 3):
+        mlp = wl.make_mlp((96, 64, 10), sparsity=0.7, bias_std=0.1)
+        Xs, Ts = wl.make_batches(96, 10, batch, 12, seed=21)
+        runs = []
+        for _ in range(2):
+            M = nb.MLP(mlp, batch)
+            losses = []
+            for t in range(12):
+                M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+                losses.append(float(M.loss.item()))
+            runs.append((losses, [l.values.clone() for l in M.layers]))
+            M.close()
+        assert runs[0][0] == runs[1][0]
+        assert all(torch.equal(a, b) for a, b in zip(runs[0][1], runs[1][1]))
+        assert all(np.isfinite(x) and x > 0 for x in runs[0][0])
 
 
 @pytest.mark.parametrize("unfused", [False, True])
