@@ -94,6 +94,20 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
                          int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host,
                          int32_t *counts_host);
 
+/* The second partition, which the products Y = S X and Y = S^T X use on matrices with many short
+ * rows (HOST arrays, needs no GPU).  Rows of at most NERVA_PACK_MAX_LEN stored entries are listed
+ * longest first (ties in row order) and are served one row per group of lanes, several rows per
+ * wave; the remaining rows get a partition of their own with the records of waves_host above.
+ * With fewer than NERVA_PACK_MIN_ROWS short rows (or no stored entry) there is no second
+ * partition and every count is 0.  Outputs (arrays may be NULL to get only the counts):
+ *   counts_host[3]            {short rows, work-groups of the remaining rows, huge ones among them}
+ *   short_rows_host[4*ns64]   ns64 = short rows rounded up to a multiple of 64:
+ *                               {row, first entry, entries, 0}, padding {-1, 0, 0, 0}
+ *   long_waves_host[4*16*nl]  per wave of the nl work-groups of the remaining rows */
+enum { NERVA_PACK_MAX_LEN = 128, NERVA_PACK_MIN_ROWS = 2048 };
+int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *short_rows_host,
+                               int32_t *long_waves_host, int32_t *counts_host);
+
 /* ---- layer -------------------------------------------------------------------------
  * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays
  * (which must outlive the layer) and builds, once, what a static pattern allows to be

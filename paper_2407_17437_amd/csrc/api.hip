@@ -7,6 +7,8 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <algorithm>
+#include <functional>
 #include <vector>
 
 #include "kernels.h"
@@ -64,6 +66,11 @@ struct nerva_layer {
     // owned: partial rows of huge-row work-groups, shared by the forward and the transposed product
     float *scratch = nullptr;
     int64_t scratch_ld = 0;
+    // owned: per-tile partial products of the column-tiled SDDMM (only for layers whose input
+    // at max_batch columns does not fit an L2)
+    float *partial = nullptr;
+    int64_t partial_stride = 0, partial_db_at = 0;
+    int32_t partial_tiles = 0;
 };
 
 // Optional per-kernel timing of mlp_train_step: one HIP event before every launch and one after
@@ -140,7 +147,8 @@ struct RowPlan {
     int32_t n_huge_rows() const { return static_cast<int32_t>(huge_rows.size() / 4); }
 };
 
-RowPlan plan_rows(int32_t rows, const int32_t *indptr)
+// skip_upto >= 0: rows with at most that many entries are left out (they go to the packed path).
+RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
 {
     RowPlan P;
     const int64_t nnz = indptr[rows];
@@ -154,6 +162,10 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr)
     std::vector<int32_t> count(max_lg + 1, 0);
     for (int32_t i = 0; i < rows; ++i) {
         const int64_t n = indptr[i + 1] - indptr[i];
+        if (n <= skip_upto) {
+            lg_of[i] = -2;
+            continue;
+        }
         if (n > 4 * block_cap) {
             lg_of[i] = -1;
             const int32_t parts = static_cast<int32_t>((n + 2 * block_cap - 1) / (2 * block_cap));
@@ -216,14 +228,66 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr)
     return P;
 }
 
-hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, RowBlocks *plan, hipStream_t s,
-                       std::vector<int32_t> &staging)
+// Rows of at most kPackMaxLen entries, longest first (ties in row order), 4 ints per row
+// {row, first entry, entries, 0}, padded with {-1, 0, 0, 0} to a multiple of 64 rows.  Empty when
+// there are fewer than kPackMinRows of them: the packed path pays off on large matrices only.
+std::vector<int32_t> short_row_table(int32_t rows, const int32_t *indptr, int32_t *n_short)
+{
+    std::vector<int32_t> count(kPackMaxLen + 2, 0);
+    int32_t n = 0;
+    for (int32_t i = 0; i < rows; ++i) {
+        const int64_t len = indptr[i + 1] - indptr[i];
+        if (len <= kPackMaxLen) { ++count[kPackMaxLen - len + 1]; ++n; }
+    }
+    *n_short = 0;
+    std::vector<int32_t> t;
+    if (n < kPackMinRows || indptr[rows] == 0) return t;
+    for (int k = 1; k <= kPackMaxLen + 1; ++k) count[k] += count[k - 1];  // counting sort by descending length
+    t.assign(static_cast<size_t>(round_up(n, 64)) * 4, 0);
+    for (int64_t k = n; k < round_up(n, 64); ++k) t[4 * k] = -1;
+    for (int32_t i = 0; i < rows; ++i) {
+        const int64_t len = indptr[i + 1] - indptr[i];
+        if (len > kPackMaxLen) continue;
+        const int32_t k = count[kPackMaxLen - len]++;
+        t[4 * k] = i; t[4 * k + 1] = indptr[i]; t[4 * k + 2] = static_cast<int32_t>(len);
+    }
+    *n_short = n;
+    return t;
+}
+
+// Share of the stored entries that gather one of the kHotRows most referenced operand rows;
+// other_indptr is the row-pointer array of the transposed orientation (its row lengths are the
+// reference counts).
+float hot_row_share(int32_t other_rows, const int32_t *other_indptr)
+{
+    const int64_t nnz = other_indptr[other_rows];
+    if (nnz == 0) return 0.f;
+    if (other_rows <= kHotRows) return 1.f;
+    std::vector<int32_t> len(other_rows);
+    for (int32_t i = 0; i < other_rows; ++i) len[i] = other_indptr[i + 1] - other_indptr[i];
+    std::nth_element(len.begin(), len.begin() + kHotRows, len.end(), std::greater<int32_t>());
+    int64_t top = 0;
+    for (int32_t i = 0; i < kHotRows; ++i) top += len[i];
+    return static_cast<float>(static_cast<double>(top) / static_cast<double>(nnz));
+}
+
+hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t other_rows, const int32_t *other_indptr_host,
+                       int32_t **mem, RowBlocks *plan, hipStream_t s, std::vector<int32_t> &staging)
 {
     const RowPlan P = plan_rows(rows, indptr_host);
+    int32_t n_short = 0;
+    const std::vector<int32_t> short_rows = short_row_table(rows, indptr_host, &n_short);
+    RowPlan Q;
+    if (n_short > 0) Q = plan_rows(rows, indptr_host, kPackMaxLen);
     // 16-byte records first so that they stay 16-byte aligned
     staging = P.blocks;
     staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
     staging.insert(staging.end(), P.waves.begin(), P.waves.end());
+    const size_t long_at = staging.size();
+    staging.insert(staging.end(), Q.waves.begin(), Q.waves.end());
+    const size_t short_at = staging.size();
+    staging.insert(staging.end(), short_rows.begin(), short_rows.end());
+    const size_t order_at = staging.size();
     staging.insert(staging.end(), P.row_order.begin(), P.row_order.end());
     if (staging.empty()) staging.push_back(0);
     hipError_t e = hipMalloc(mem, staging.size() * 4);
@@ -232,7 +296,12 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t **mem, 
     plan->blocks = reinterpret_cast<const int4 *>(*mem);
     plan->huge_rows = reinterpret_cast<const int4 *>(*mem + P.blocks.size());
     plan->waves = reinterpret_cast<const int4 *>(*mem + P.blocks.size() + P.huge_rows.size());
-    plan->row_order = *mem + P.blocks.size() + P.huge_rows.size() + P.waves.size();
+    plan->row_order = *mem + order_at;
+    plan->long_waves = reinterpret_cast<const int4 *>(*mem + long_at);
+    plan->short_rows = reinterpret_cast<const int4 *>(*mem + short_at);
+    plan->n_short = n_short;
+    plan->hot_share = hot_row_share(other_rows, other_indptr_host);
+    plan->n_long_blocks = Q.n_blocks();
     plan->n_blocks = P.n_blocks();
     plan->n_huge_rows = P.n_huge_rows();
     plan->n_huge_blocks = P.n_huge_blocks;
@@ -247,6 +316,7 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->indptr_t);
     (void)hipFree(l->indices_t);
     (void)hipFree(l->values_t);
+    (void)hipFree(l->partial);
     (void)hipFree(l->perm);
     (void)hipFree(l->pos_t);
 }
@@ -325,6 +395,22 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
     return NERVA_OK;
 }
 
+int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *short_rows_host,
+                               int32_t *long_waves_host, int32_t *counts_host)
+{
+    if (rows <= 0 || !indptr_host || !counts_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    int32_t n_short = 0;
+    const std::vector<int32_t> t = short_row_table(rows, indptr_host, &n_short);
+    RowPlan Q;
+    if (n_short > 0) Q = plan_rows(rows, indptr_host, kPackMaxLen);
+    counts_host[0] = n_short;
+    counts_host[1] = Q.n_blocks();
+    counts_host[2] = Q.n_huge_blocks;
+    if (short_rows_host && !t.empty()) memcpy(short_rows_host, t.data(), t.size() * 4);
+    if (long_waves_host && !Q.waves.empty()) memcpy(long_waves_host, Q.waves.data(), Q.waves.size() * 4);
+    return NERVA_OK;
+}
+
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
                          const int32_t *indices, float *values, float *bias, int32_t activation, int32_t max_batch,
                          void *stream)
@@ -375,8 +461,22 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
     if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->perm, h_perm.data(), nb, hipMemcpyHostToDevice, s);
     if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->pos_t, h_pos_t.data(), nb, hipMemcpyHostToDevice, s);
     std::vector<int32_t> stage_a, stage_b;
-    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), &l->plan_mem, &l->plan, s, stage_a);
-    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
+    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), cols, h_indptr_t.data(), &l->plan_mem, &l->plan, s, stage_a);
+    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), rows, h_indptr.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
+    if (e == hipSuccess) {
+        // room for the column-tiled SDDMM at max_batch columns, if that batch would be tiled
+        const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false);
+        if (w > 0) {
+            l->partial_tiles = (max_batch + w - 1) / w;
+            l->partial_db_at = round_up(nnz, 64);
+            l->partial_stride = l->partial_db_at + round_up(rows, 64);
+            const size_t bytes = static_cast<size_t>(l->partial_tiles) * l->partial_stride * 4;
+            if (bytes <= (4ull << 30))
+                e = hipMalloc(&l->partial, bytes);
+            else
+                l->partial_tiles = 0;  // too large to be worth it: the untiled kernel stays
+        }
+    }
     if (e == hipSuccess) {
         const int64_t slots = l->plan.n_huge_blocks > l->plan_t.n_huge_blocks ? l->plan.n_huge_blocks : l->plan_t.n_huge_blocks;
         l->scratch_ld = round_up(max_batch, 64);
@@ -460,7 +560,9 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
         a.dZ = dY; a.lddz = lddy;
         if (relu) { a.ZM = Y; a.ldzm = ldy; }
         a.X = X; a.ldx = ldx; a.g = dvalues; a.db = dbias;
-        a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch;
+        a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch; a.nnz = layer->nnz;
+        a.partial = layer->partial; a.partial_stride = layer->partial_stride;
+        a.partial_db_at = layer->partial_db_at; a.partial_tiles = layer->partial_tiles;
         a.skip_products = dvalues ? 0 : 1;  // only the bias gradient is wanted
         HIP_TRY(launch_sddmm(a, s));
     }
@@ -709,7 +811,9 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         g.indptr = ly->indptr; g.indices = ly->indices;
         g.dZ = dZ(l); g.lddz = L.ld;
         g.X = l > 0 ? A(l - 1) : X; g.ldx = l > 0 ? L.ld : ldx;
-        g.rows = ly->rows; g.x_rows = ly->cols; g.batch = batch;
+        g.rows = ly->rows; g.x_rows = ly->cols; g.batch = batch; g.nnz = ly->nnz;
+        g.partial = ly->partial; g.partial_stride = ly->partial_stride;
+        g.partial_db_at = ly->partial_db_at; g.partial_tiles = ly->partial_tiles;
         if (head && l == n - 1 && loss_out) { g.loss_cols = mlp->head_scratch; g.loss_out = loss_out; g.loss_n = batch; }
         if (fused) {
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;

@@ -23,8 +23,23 @@ struct RowBlocks {
     int32_t n_blocks;
     int32_t n_huge_rows;
     int32_t n_huge_blocks;
+    // Optional second partition, built for matrices with many short rows (n_short > 0): rows of
+    // at most kPackMaxLen entries are listed longest first and served one row per lane group,
+    // several rows per wave (spmm_packed_kernel); the remaining rows keep a partition of their
+    // own, huge work-groups first exactly as in `waves` (same scratch slots, same huge_rows).
+    const int4 *short_rows;    // [n_short rounded up to a multiple of 64] {row or -1, first entry, entries, 0}
+    const int4 *long_waves;    // [n_long_blocks * kWavesPerBlock], records as in `waves`
+    int32_t n_short;
+    int32_t n_long_blocks;
+    // Share of the stored entries whose gathered operand row is one of the kHotRows most
+    // referenced ones: when it is large the gathers hit in cache without any column tiling.
+    float hot_share;
 };
+constexpr int32_t kHotRows = 1024;
 constexpr int32_t kHugeFlag = 0x40000000;
+constexpr int32_t kPackMaxLen = 128;     // longest row served by the packed path
+constexpr int32_t kPackMinRows = 2048;   // fewer short rows than this: no packed path
+constexpr int32_t kPackSets = 4;         // row sets (64/GS rows each) per wave
 
 // Y = epilogue( W * gather(X) ) for a CSR matrix W (rows x cols); also used on the CSC
 // mirror, where "rows" are W's columns.
@@ -86,7 +101,19 @@ struct SddmmArgs {
     const float *loss_cols;  // or nullptr
     float *loss_out;
     int32_t loss_n;
+    // column-tiled route for operands X that no L2 holds: per-tile partial products
+    // [tile][partial_stride] (values first, then the per-row sums of dZ at partial_db_at), added in
+    // tile order by a second kernel that also applies the update.  nullptr: route not available.
+    float *partial;
+    int64_t partial_stride;   // floats per tile, >= partial_db_at + rows
+    int64_t partial_db_at;    // >= nnz
+    int32_t partial_tiles;    // tiles the buffer has room for
+    int32_t nnz;
 };
+// Column-tile width (in columns) the products use when their gathered operand has x_rows rows and
+// does not fit an L2; 0: no tiling.  Shared by the kernels' dispatch and by the sizing of the
+// SDDMM partial buffer when a layer is created.
+int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked);
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
 
 // Two independent launches in one grid (both on the 16-byte path, batch <= 1024, one column tile).

@@ -15,6 +15,7 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kEwBlock = 256;  // work-group of the element-wise kernels
 
 __device__ __forceinline__ int wave_in_block()
 {
@@ -52,10 +53,17 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
-// Sum over groups of G lanes (16: per row; 64: whole wave, returned wave-uniform).
+// Sum over groups of G lanes (8: per half row; 16: per row; 64: whole wave, returned wave-uniform).
 template <int G>
 __device__ __forceinline__ float group_sum(float x)
 {
+    static_assert(G == 8 || G == 16 || G == 64, "group sizes with a DPP reduction");
+    if constexpr (G == 8) {
+        x += dpp<0xB1>(x);   // quad_perm [1,0,3,2]
+        x += dpp<0x4E>(x);   // quad_perm [2,3,0,1]
+        x += dpp<0x141>(x);  // row_half_mirror
+        return x;
+    }
     x = row16_sum(x);
     if constexpr (G == 64) {
         x += dpp<0x142, 0xA>(x);  // row_bcast15 into rows 1 and 3
@@ -88,7 +96,6 @@ struct WaveTask {
 template <int GRAIN>
 __device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, const int32_t *, int block)
 {
-    static_assert(GRAIN == 1 || GRAIN == 2 || GRAIN == 4, "shares are cut in multiples of 4 entries");
     const int4 d = b.waves[block * kWavesPerBlock + wave_in_block()];
     WaveTask t;
     t.row = d.x;
@@ -415,6 +422,111 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
     }
 }
 
+// Packed SpMM for short rows: each group of GS lanes owns one row, so a gather instruction
+// fetches one entry of each of 64/GS rows and no sum across groups or waves is needed; a wave
+// serves kPackSets sets of rows one after the other, which spreads its start-up (descriptor and
+// index fetches) over several rows.  The rows come from RowBlocks::short_rows, longest first, so
+// the rows of a set have nearly the same length; a group whose row is exhausted repeats that
+// row's first entry with weight 0.
+template <int GS, bool XMASK>
+__device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int block, const int col0)
+{
+    constexpr int NE = kWave / GS;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int grp = lane / GS;
+    const int lig = lane % GS;
+    const int col = col0 + lig * 4;
+    const bool on = col < a.batch;
+    const uint32_t off = static_cast<uint32_t>(on ? col : col0) * 4u;
+    const uint32_t ldxb = static_cast<uint32_t>(a.ldx) * 4u;
+    const uint32_t ldmb = XMASK ? static_cast<uint32_t>(a.ldxm) * 4u : 0u;
+    const gmem_ptr Xg = as_gmem(a.X);
+    const gmem_ptr Mg = as_gmem(a.XM);
+    const int n_sets = (a.blocks.n_short + NE - 1) / NE;
+    const int src0 = grp * GS * 4;  // byte address of the group's first lane
+
+    for (int r = 0; r < kPackSets; ++r) {
+        const int set = (block * kWavesPerBlock + wv) * kPackSets + r;
+        if (set >= n_sets) break;  // wave-uniform
+        const int4 d = a.blocks.short_rows[set * NE + grp];  // the table is padded to whole sets
+        const int row = d.x, s0 = d.y, len = d.z;
+        const int maxlen = __builtin_amdgcn_readfirstlane(len);  // group 0 holds the set's longest row
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int base = 0; base < maxlen; base += GS) {
+            const int e = base + lig;
+            const bool ok = e < len;
+            const int p = len > 0 ? s0 + (ok ? e : 0) : 0;
+            const int my_j = a.indices[p];
+            float my_w = a.values[p];
+            my_w = ok ? my_w : 0.f;
+            const int my_ro = static_cast<int>(static_cast<uint32_t>(my_j) * ldxb);
+            const int my_mo = XMASK ? static_cast<int>(static_cast<uint32_t>(my_j) * ldmb) : 0;
+            const int steps = min(GS, maxlen - base);
+            int src = src0;
+            int u0 = 0;
+            for (; u0 + 8 <= steps; u0 += 8, src += 32) grouped_pass<8, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+            if (u0 + 4 <= steps) {
+                grouped_pass<4, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+                u0 += 4; src += 16;
+            }
+            if (u0 + 2 <= steps) {
+                grouped_pass<2, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+                u0 += 2; src += 8;
+            }
+            if (u0 < steps) grouped_pass<1, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
+        }
+        if (row < 0 || !on) continue;
+        const float b = a.bias ? a.bias[row] : 0.f;
+        float *yr = a.Y + static_cast<int64_t>(row) * a.ldy;
+        const float *ym = a.YM ? a.YM + static_cast<int64_t>(row) * a.ldym : nullptr;
+        float y[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            y[k] = (len > 0 ? acc[k] : 0.f) + b;  // an empty row gathered (with weight 0) from entry 0 of the matrix
+            if (a.relu) y[k] = y[k] > 0.f ? y[k] : 0.f;
+        }
+        if (col + 4 <= a.batch) {
+            float4 o = make_float4(y[0], y[1], y[2], y[3]);
+            if (ym) o = keep_where_positive(o, ld4(ym + col));
+            st4(yr + col, o);
+        } else {
+            for (int k = 0; k < 4; ++k)
+                if (col + k < a.batch) {
+                    float o = y[k];
+                    if (ym) o = keep_where_positive(o, ym[col + k]);
+                    yr[col + k] = o;
+                }
+        }
+    }
+}
+
+// Short rows through the packed body, the remaining rows through the grouped body, in one grid,
+// for every column tile; work-group ids are decoded XCD-first as in spmm_tiled_kernel.
+template <int GS, bool XMASK>
+__global__ __launch_bounds__(kBlock) void spmm_packed_kernel(const SpmmArgs a, const int n_tiles, const int spread,
+                                                             const int n_pack_blocks)
+{
+    const int nrb = n_pack_blocks + a.blocks.n_long_blocks;
+    int tile, rb;
+    if (spread) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        tile = (k / nrb) * 8 + xcd;
+        rb = k % nrb;
+    } else {
+        tile = blockIdx.x / nrb;
+        rb = blockIdx.x % nrb;
+    }
+    if (tile >= n_tiles) return;
+    if (rb < n_pack_blocks) {
+        spmm_body_packed<GS, XMASK>(a, rb, tile * GS * 4);
+    } else {
+        SpmmArgs al = a;
+        al.blocks.waves = a.blocks.long_waves;
+        spmm_body_grouped<GS, XMASK>(al, rb - n_pack_blocks, tile * GS * 4);
+    }
+}
+
 template <int GS, bool XMASK>
 __global__ __launch_bounds__(kBlock) void spmm_grouped_kernel(const SpmmArgs a)
 {
@@ -688,6 +800,69 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a)
     sddmm_body<G, NV, EXACT4>(a, blockIdx.x);
 }
 
+// Column-tiled SDDMM for operands X that no L2 holds: tile t covers columns [t*W, t*W + W), W =
+// G*4*NV; a work-group computes the partial products of its rows over one tile, as sddmm_body on
+// the sub-matrices that start at the tile's first column, and stores them (and the partial row
+// sums of dZ) in the tile's slice of the partial buffer.  Work-group ids are decoded XCD-first as
+// in spmm_tiled_kernel, so an operand tile stays in one L2 while every entry gathers from it.
+template <int G, int NV, bool EXACT4>
+__global__ __launch_bounds__(kBlock) void sddmm_tiled_kernel(const SddmmArgs a, const int n_tiles, const int spread)
+{
+    const int nrb = a.blocks.n_blocks;
+    int tile, rb;
+    if (spread) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        tile = (k / nrb) * 8 + xcd;
+        rb = k % nrb;
+    } else {
+        tile = blockIdx.x / nrb;
+        rb = blockIdx.x % nrb;
+    }
+    if (tile >= n_tiles) return;
+    const int col0 = tile * (G * 4 * NV);
+    SddmmArgs t = a;
+    t.dZ = a.dZ + col0;
+    t.X = a.X + col0;
+    if (a.ZM) t.ZM = a.ZM + col0;
+    t.batch = min(G * 4 * NV, a.batch - col0);
+    t.fused = 0;
+    t.g = a.partial + static_cast<int64_t>(tile) * a.partial_stride;
+    t.db = t.g + a.partial_db_at;
+    if (tile != 0) t.loss_cols = nullptr;
+    sddmm_body<G, NV, EXACT4>(t, rb);
+}
+
+// Second pass of the tiled SDDMM: adds the tiles' partial products in tile order, then stores the
+// gradient or applies the fused momentum step (and the mirror scatter); the same for the biases.
+__global__ __launch_bounds__(kEwBlock) void sddmm_finish_kernel(const SddmmArgs a, const int n_tiles)
+{
+    const int64_t stride = static_cast<int64_t>(blockDim.x) * gridDim.x;
+    for (int64_t p = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; p < a.nnz; p += stride) {
+        float g = 0.f;
+        for (int t = 0; t < n_tiles; ++t) g += a.partial[static_cast<int64_t>(t) * a.partial_stride + p];
+        if (a.g) a.g[p] = g;
+        if (a.fused) {
+            float w = a.values[p], v = a.velocity[p];
+            momentum_step(w, v, g, a.lr, a.momentum, a.nesterov);
+            a.values[p] = w;
+            a.velocity[p] = v;
+            if (a.values_t) a.values_t[a.pos_t[p]] = w;
+        }
+    }
+    if (!(a.db || (a.fused && a.bias))) return;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < a.rows; i += stride) {
+        float s = 0.f;
+        for (int t = 0; t < n_tiles; ++t) s += a.partial[static_cast<int64_t>(t) * a.partial_stride + a.partial_db_at + i];
+        if (a.db) a.db[i] = s;
+        if (a.fused && a.bias) {
+            float w = a.bias[i], v = a.bias_velocity[i];
+            momentum_step(w, v, s, a.lr, a.momentum, a.nesterov);
+            a.bias[i] = w;
+            a.bias_velocity[i] = v;
+        }
+    }
+}
+
 // Two independent launches of a training step in one grid: work-groups [0, na) run the first,
 // the rest the second.  Saves a launch (and its drain) on the step's critical path.
 template <int GS_S, int NV_S, int G, int NV_D, bool EXACT4>
@@ -770,7 +945,6 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
 // ---------------------------------------------------------------------------------------
 // Element-wise kernels
 // ---------------------------------------------------------------------------------------
-constexpr int kEwBlock = 256;
 
 __global__ __launch_bounds__(kEwBlock) void momentum_kernel(float *__restrict__ w, float *__restrict__ v,
                                                             const float *__restrict__ g, int64_t n,
@@ -1040,17 +1214,8 @@ hipError_t spmm_grouped_go(const SpmmArgs &a, hipStream_t s)
 // 4 * (return value) columns.  0: no tiling.
 int spmm_tile_group(const SpmmArgs &a)
 {
-    const int64_t budget = (a.XM ? 5 : 10) * (1 << 18);  // 2.5 MiB (half of it with a mask operand)
-    const int64_t row_bytes = static_cast<int64_t>(a.x_rows) * 4;
-    if (a.x_rows <= 0 || row_bytes * a.batch <= budget) return 0;
     if (static_cast<int64_t>(a.blocks.n_blocks) * ((a.batch + 31) / 32 + 8) >= (1ll << 31)) return 0;
-    if (row_bytes * 128 <= budget && a.batch > 128) return 32;
-    if (row_bytes * 64 <= budget && a.batch > 64) return 16;
-    // Narrower tiles multiply the per-wave set-up (one pass over the row partition per tile) by 32 or
-    // more; measured, that only pays when rows are long (a 16384^2 matrix at 10 % density gains 1.4x,
-    // at 1 % it loses).
-    if (a.batch > 32 && static_cast<int64_t>(a.nnz) >= static_cast<int64_t>(a.rows) * 1024) return 8;
-    return 0;
+    return tile_columns(a.x_rows, a.batch, a.nnz, a.rows, a.blocks.hot_share, a.XM != nullptr) / 4;
 }
 
 template <int GS>
@@ -1065,6 +1230,26 @@ hipError_t spmm_tiled_go(const SpmmArgs &a, hipStream_t s)
         hipLaunchKernelGGL((spmm_tiled_kernel<GS, true>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
     else
         hipLaunchKernelGGL((spmm_tiled_kernel<GS, false>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
+    if (a.blocks.n_huge_rows > 0)
+        hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int GS>
+hipError_t spmm_packed_go(const SpmmArgs &a, hipStream_t s)
+{
+    constexpr int NE = kWave / GS;
+    const int n_tiles = (a.batch + GS * 4 - 1) / (GS * 4);
+    const int spread = n_tiles >= 8;
+    const int n_sets = (a.blocks.n_short + NE - 1) / NE;
+    const int n_pack_blocks = (n_sets + kWavesPerBlock * kPackSets - 1) / (kWavesPerBlock * kPackSets);
+    const int64_t nrb = static_cast<int64_t>(n_pack_blocks) + a.blocks.n_long_blocks;
+    const int64_t ids = (spread ? static_cast<int64_t>((n_tiles + 7) / 8) * 8 : n_tiles) * nrb;
+    dim3 grid(static_cast<unsigned>(ids));
+    if (a.XM)
+        hipLaunchKernelGGL((spmm_packed_kernel<GS, true>), grid, dim3(kBlock), 0, s, a, n_tiles, spread, n_pack_blocks);
+    else
+        hipLaunchKernelGGL((spmm_packed_kernel<GS, false>), grid, dim3(kBlock), 0, s, a, n_tiles, spread, n_pack_blocks);
     if (a.blocks.n_huge_rows > 0)
         hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, (a.batch + 255) / 256), dim3(256), 0, s, a);
     return hipGetLastError();
@@ -1087,6 +1272,23 @@ inline bool spans_below_4gib(int64_t rows, int64_t ld) { return rows * ld * 4 < 
 bool spmm_offsets_ok(const SpmmArgs &a)
 {
     return spans_below_4gib(a.x_rows, a.ldx) && (!a.XM || spans_below_4gib(a.x_rows, a.ldxm));
+}
+
+template <int G, int NV>
+hipError_t sddmm_tiled_go(const SddmmArgs &a, hipStream_t s)
+{
+    const int W = G * 4 * NV;
+    const int n_tiles = (a.batch + W - 1) / W;
+    const int spread = n_tiles >= 8;
+    const int64_t ids = (spread ? static_cast<int64_t>((n_tiles + 7) / 8) * 8 : n_tiles) * a.blocks.n_blocks;
+    dim3 grid(static_cast<unsigned>(ids));
+    if (a.batch % 4 == 0)
+        hipLaunchKernelGGL((sddmm_tiled_kernel<G, NV, true>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
+    else
+        hipLaunchKernelGGL((sddmm_tiled_kernel<G, NV, false>), grid, dim3(kBlock), 0, s, a, n_tiles, spread);
+    const int64_t work = a.nnz > a.rows ? a.nnz : a.rows;
+    hipLaunchKernelGGL(sddmm_finish_kernel, dim3(elementwise_blocks(work)), dim3(kEwBlock), 0, s, a, n_tiles);
+    return hipGetLastError();
 }
 
 bool spmm_vec_ok(const SpmmArgs &a)
@@ -1133,17 +1335,41 @@ hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 
 }  // namespace
 
+int sddmm_tile_columns(const SddmmArgs &a);
+
+int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked)
+{
+    const int64_t budget = (masked ? 5 : 10) * (1 << 18);  // 2.5 MiB (half of it with a mask operand)
+    const int64_t row_bytes = static_cast<int64_t>(x_rows) * 4;
+    if (x_rows <= 0 || row_bytes * batch <= budget) return 0;
+    // A matrix of few rows is in flight as a whole: its rows gather the same operand rows at about
+    // the same time, which serves them from cache without tiling (measured on a dense 10 x 8192 layer).
+    if (rows <= 256) return 0;
+    if (row_bytes * 128 <= budget && batch > 128) return 128;
+    if (row_bytes * 64 <= budget && batch > 64) return 64;
+    // Narrower tiles multiply the per-wave set-up (one pass over the row partition per tile) by 32 or
+    // more.  Measured on 16384^2 matrices at batch 1024: they pay from about 128 entries per row on
+    // (1 % density: 1.48 -> 1.18 ms, 10 %: 1.4x) unless a few operand rows take most of the gathers
+    // (the transposed product of a power-law matrix: 0.58 -> 1.08 ms); at 16 entries per row they lose,
+    // and so they do on an 8 MiB operand (batch 128), half of which an L2 holds anyway.
+    if (batch <= 32) return 0;
+    if (nnz >= static_cast<int64_t>(rows) * 1024) return 32;
+    if (nnz >= static_cast<int64_t>(rows) * 128 && hot_share < 0.5f && row_bytes * batch >= (16ll << 20)) return 32;
+    return 0;
+}
+
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && spmm_offsets_ok(a) &&
-           sddmm_vec_ok(b) && spmm_tile_group(a) == 0;
+           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && sddmm_tile_columns(b) == 0;
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && a.rows > 0 && b.rows > 0 &&
-           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && sddmm_vec_ok(a) && sddmm_vec_ok(b);
+           a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && sddmm_vec_ok(a) && sddmm_vec_ok(b) &&
+           sddmm_tile_columns(a) == 0 && sddmm_tile_columns(b) == 0;
 }
 
 hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
@@ -1178,7 +1404,16 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
     }
     if (spmm_vec_ok(a)) {
         if (spmm_offsets_ok(a)) {
-            switch (spmm_tile_group(a)) {
+            const int tg = spmm_tile_group(a);
+            if (a.blocks.n_short > 0 && tg != 0 &&
+                (static_cast<int64_t>(a.blocks.n_short / 64 + 1 + a.blocks.n_long_blocks) * ((a.batch + 31) / 32 + 8) < (1ll << 31))) {
+                switch (tg ? tg : (a.batch <= 64 ? 16 : 32)) {
+                    case 32: return spmm_packed_go<32>(a, s);
+                    case 16: return spmm_packed_go<16>(a, s);
+                    default: return spmm_packed_go<8>(a, s);
+                }
+            }
+            switch (tg) {
                 case 32: return spmm_tiled_go<32>(a, s);
                 case 16: return spmm_tiled_go<16>(a, s);
                 case 8: return spmm_tiled_go<8>(a, s);
@@ -1196,9 +1431,29 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
     return spmm_go<1, 4>(a, s);
 }
 
+// Columns per tile of the column-tiled SDDMM, 0: one pass over the whole batch.
+int sddmm_tile_columns(const SddmmArgs &a)
+{
+    if (!a.partial || a.skip_products || !sddmm_vec_ok(a)) return 0;
+    // the operand rows an entry gathers are named by its column index: the matrix's own partition
+    // carries the share of the most referenced ones
+    const int w = tile_columns(a.x_rows, a.batch, a.nnz, a.rows, a.blocks.hot_share, false);
+    if (w == 0) return 0;
+    const int n_tiles = (a.batch + w - 1) / w;
+    if (n_tiles > a.partial_tiles) return 0;
+    if (static_cast<int64_t>(a.blocks.n_blocks) * (n_tiles + 8) >= (1ll << 31)) return 0;
+    return w;
+}
+
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    switch (sddmm_tile_columns(a)) {
+        case 128: return sddmm_tiled_go<16, 2>(a, s);
+        case 64: return sddmm_tiled_go<16, 1>(a, s);
+        case 32: return sddmm_tiled_go<8, 1>(a, s);
+        default: break;
+    }
     if (sddmm_vec_ok(a) && a.batch <= 1024) {
         if (a.batch <= 64) return sddmm_go<16, 1>(a, s);
         if (a.batch <= 128) return sddmm_go<16, 2>(a, s);

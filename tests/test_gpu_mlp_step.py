@@ -78,6 +78,7 @@ CASES = [
     ((100, 300, 50, 10), dict(sparsity=0.9), 100, 2),
     ((64, 40, 10), dict(sparsity=0.5), 260, 2),
     ((40, 30, 20, 10), dict(sparsity=0.999), 16, 2),          # almost every row empty
+    ((6000, 300, 10), dict(sparsity=0.98, bias_std=0.1), 200, 2),  # first layer's input beyond an L2: tiled SDDMM + update
 ]
 
 

@@ -90,6 +90,16 @@ SHAPES = [
     (64, 4096, 0.9, 2, None),        # few columns and huge rows
     (33, 65, 0.2, 4, 5),
     (33, 65, 0.2, 3, None),
+    # more than 2048 rows of at most 128 entries: the packed path (one row per lane group)
+    (2500, 300, 0.02, 100, None),    # 6 entries per row, some rows empty
+    (3000, 200, 0.1, 37, None),      # 4 rows per gather instruction, ragged batch
+    (2100, 5000, 0.01, 128, None),   # the mirror (5000 short rows) is packed too
+    (2400, 1000, 0.125, 64, None),   # rows around the 128-entry limit: packed and ordinary rows in one grid
+    (2200, 3000, 0.005, 300, None),  # operand beyond an L2: packed rows inside column tiles
+    (300, 2500, 0.02, 100, None),    # short rows only in the mirror
+    # operands beyond an L2: column tiles in the products and per-tile partial sums in the SDDMM
+    (300, 6000, 0.02, 200, None),    # 64-column tiles, ragged last tile
+    (320, 12000, 0.02, 360, None),   # 32-column tiles (240 entries per row, a 17 MB operand)
 ]
 
 
@@ -138,7 +148,7 @@ def test_backward_parity(nb, torch_mod, oracle, rows, cols, density, batch, ld, 
     db2 = torch.full((rows,), float("nan"), device="cuda")
     nb.sparse_linear_backward(L.handle, None, Yd, dYd, None, None, db2, batch)
     torch.cuda.synchronize()
-    assert torch.equal(db2, db)
+    close(db2.cpu().numpy(), dbr, Sdb, what="dbias alone")     # (with the products it may be summed per column tile)
     L.close()
 
 
@@ -246,6 +256,34 @@ def test_softmax_ce_parity(nb, torch_mod, oracle, classes, batch):
     Zd.zero_()
     nb.softmax_cross_entropy(Zd, lab, classes, batch, dZd, loss)
     assert abs(float(loss.item()) - np.log(classes)) < 1e-6 * np.log(max(classes, 2)) + 1e-7
+
+
+def test_zipf_matrix_packed_rows(nb, torch_mod, oracle):
+    """Power-law rows on a matrix large enough for the packed path: a few full rows (huge), a long
+    tail of rows with one or no entry; forward, transposed and SDDMM at batches that take the
+    grouped, the tiled and the wide kernels."""
+    torch = torch_mod
+    n = 4096
+    z = wl.make_zipf_matrix(n, 0.004, seed=9)
+    short, ns, waves, _ = nb.nerva_plan_short_rows_host(n, z.indptr)
+    assert ns >= nb.NERVA_PACK_MIN_ROWS and len(waves) >= 1
+    for batch in (100, 7, 512):
+        rng = np.random.default_rng(batch)
+        X = rng.standard_normal((n, batch)).astype(np.float32)
+        dY = rng.standard_normal((n, batch)).astype(np.float32)
+        L = nb.SparseLinear(z, max_batch=batch)
+        Xd = nb.to_dense(X); Yd = nb.dense(n, batch); dYd = nb.to_dense(dY); dXd = nb.dense(n, batch)
+        g = torch.empty(z.nnz, device="cuda"); db = torch.empty(n, device="cuda")
+        nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+        nb.sparse_linear_backward(L.handle, Xd, None, dYd, dXd, g, db, batch)
+        torch.cuda.synchronize()
+        Y, S = oracle.spmm(n, n, z.indptr, z.indices, z.values, z.bias, X, False)
+        close(Yd.cpu().numpy(), Y, S, what="Y")
+        dX, SdX = oracle.spmm_t(n, n, z.indptr, z.indices, z.values, dY)
+        close(dXd.cpu().numpy(), dX, SdX, what="dX")
+        gr, Sg, dbr, Sdb = oracle.sddmm(n, n, z.indptr, z.indices, dY, X)
+        close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+        L.close()
 
 
 def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):

@@ -126,6 +126,46 @@ def _check_plan(nb, indptr, rows):
     return order, blocks, huge, n_huge_blocks
 
 
+def test_short_row_partition(nb):
+    """Second partition: short rows longest first, each exactly once; the other rows tiled by the
+    long partition; none at all below the row-count threshold."""
+    W = nb.NERVA_WAVES_PER_BLOCK
+    rng = np.random.default_rng(5)
+    for rows, lens in [(5000, rng.integers(0, 40, 5000)),
+                       (4096, np.where(rng.random(4096) < 0.1, rng.integers(129, 3000, 4096), rng.integers(0, 129, 4096))),
+                       (3000, np.full(3000, 128))]:
+        indptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        short, ns, waves, n_long_huge = nb.nerva_plan_short_rows_host(rows, indptr)
+        is_short = lens <= nb.NERVA_PACK_MAX_LEN
+        assert ns == int(is_short.sum()) and len(short) == (ns + 63) // 64 * 64
+        got = short[:ns]
+        assert sorted(got[:, 0].tolist()) == np.nonzero(is_short)[0].tolist()
+        assert np.array_equal(got[:, 1], indptr[got[:, 0]]) and np.array_equal(got[:, 2], lens[got[:, 0]])
+        key = list(zip((-got[:, 2]).tolist(), got[:, 0].tolist()))
+        assert key == sorted(key)                                   # longest first, ties in row order
+        assert (short[ns:] == np.array([-1, 0, 0, 0])).all() and (got[:, 3] == 0).all()
+        seen = {}
+        for b in range(len(waves)):
+            for w in range(W):
+                row, s0, s1, fl = waves[b, w].tolist()
+                if row >= 0:
+                    seen.setdefault(row, []).append((s0, s1))
+        assert sorted(seen) == np.nonzero(~is_short)[0].tolist()
+        for row, shares in seen.items():
+            pos = int(indptr[row])
+            for s0, s1 in shares:
+                assert s0 == pos or s0 == s1
+                pos = max(pos, s1)
+            assert pos == int(indptr[row + 1])
+        # the huge work-groups of the long partition are those of the full one, in the same slots
+        _, blocks, _, nh, full_waves = nb.nerva_plan_rows_host(rows, indptr)
+        assert n_long_huge == nh and np.array_equal(waves[:nh], full_waves[:nh])
+    # too few short rows, or an empty matrix: no second partition
+    indptr = np.concatenate([[0], np.cumsum(np.full(2047, 3))]).astype(np.int32)
+    assert nb.nerva_plan_short_rows_host(2047, indptr)[1] == 0
+    assert nb.nerva_plan_short_rows_host(4000, np.zeros(4001, dtype=np.int32))[1] == 0
+
+
 def test_row_plan_uniform_and_skewed(nb):
     mlp = wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9)
     for lay in mlp.layers:
