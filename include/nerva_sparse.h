@@ -126,6 +126,21 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
                          void *stream);
 void sparse_linear_destroy(nerva_layer *layer);
 
+/* Topology-update hook for dynamic sparse training (Section 2, "Sparse Training"; announced as
+ * the next step in "Discussion and Conclusion"): the caller has written a new pattern for the
+ * same rows x cols matrix -- entries pruned, others grown, nnz free to change -- as a canonical
+ * CSR in device arrays indptr[rows+1], indices[nnz], values[nnz] (caller-owned; they replace the
+ * arrays given at creation, which the layer no longer touches; bias, activation and max_batch
+ * stay).  The call waits for the stream, validates the pattern as sparse_linear_create does,
+ * rebuilds the mirror, the position maps, the partitions and the work buffers, then switches
+ * over.  On any error (bad CSR: NERVA_ERR_CSR, allocation: NERVA_ERR_HIP) the layer keeps its
+ * old pattern and stays usable.  Momentum buffers are the caller's: after a rebind of a layer
+ * that belongs to an MLP, hand the MLP a velocity array of the new length, mapped to the new
+ * entries as the method prescribes (zero for grown ones), with mlp_rebind_velocity.  Host-side
+ * integer work proportional to nnz; not meant for every step. */
+int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
+                         const int32_t *indices, float *values, void *stream);
+
 /* Device pointers of the mirror, for inspection: indptr_t[cols+1], indices_t[nnz],
  * values_t[nnz], perm[nnz] (mirror position -> CSR position). Any output may be NULL. */
 int sparse_linear_mirror(const nerva_layer *layer, const int32_t **indptr_t,
@@ -207,6 +222,10 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers,
                float *const *velocities, float *const *bias_velocities,
                int32_t max_batch, int32_t flags);
 void mlp_destroy(nerva_mlp *mlp);
+
+/* After sparse_linear_rebind on layer `layer_index` of the MLP: the momentum buffer float[new nnz]
+ * (device, caller-owned) that later training steps use for that layer's weights. */
+int mlp_rebind_velocity(nerva_mlp *mlp, int32_t layer_index, float *velocity);
 
 /* Bytes of scratch mlp_train_step needs for `batch` columns (256-byte aligned base). */
 size_t mlp_workspace_bytes(const nerva_mlp *mlp, int32_t batch);

@@ -27,9 +27,9 @@ NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
     "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host",
-    "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_mirror",
+    "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
-    "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_workspace_bytes",
+    "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
     "mlp_workspace_layout", "mlp_train_step", "mlp_forward", "nerva_copy_f32",
     "mlp_profile_enable", "mlp_profile_read", "mlp_profile_slot_name",
 ]
@@ -56,6 +56,8 @@ def _load() -> ctypes.CDLL:
         "nerva_plan_short_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
+        "sparse_linear_rebind": (ctypes.c_int, [vp, i32, vp, vp, vp, vp]),
+        "mlp_rebind_velocity": (ctypes.c_int, [vp, i32, vp]),
         "sparse_linear_mirror": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sparse_linear_forward": (ctypes.c_int, [vp, vp, i32, vp, i32, i32, vp]),
         "sparse_linear_backward": (ctypes.c_int, [vp, vp, i32, vp, i32, vp, i32, vp, i32, vp, vp, i32, vp]),
@@ -162,6 +164,14 @@ def sparse_linear_create(rows, cols, nnz, indptr, indices, values, bias, activat
 
 def sparse_linear_destroy(layer: int) -> None:
     lib.sparse_linear_destroy(layer)
+
+
+def sparse_linear_rebind(layer: int, nnz, indptr, indices, values, stream=None) -> None:
+    _check(lib.sparse_linear_rebind(layer, nnz, _ptr(indptr), _ptr(indices), _ptr(values), _stream(stream)))
+
+
+def mlp_rebind_velocity(mlp: int, layer_index: int, velocity) -> None:
+    _check(lib.mlp_rebind_velocity(mlp, layer_index, _ptr(velocity)))
 
 
 def sparse_linear_mirror(layer: int):
@@ -289,6 +299,21 @@ class SparseLinear:
         self.handle = sparse_linear_create(d.rows, d.cols, d.nnz, self.indptr, self.indices, self.values, self.bias,
                                            NERVA_ACT_RELU if d.relu else NERVA_ACT_NONE, max_batch)
 
+    def rebind(self, indptr, indices, values, velocity=None):
+        """New pattern for the same rows x cols matrix (numpy arrays; canonical CSR).  The device copies
+        replace the old ones once the library has accepted the pattern; velocity defaults to zeros."""
+        nnz = int(indptr[-1])
+        dev = self.values.device
+        new_indptr = torch.as_tensor(indptr, dtype=torch.int32).to(dev)
+        new_indices = torch.as_tensor(indices, dtype=torch.int32).to(dev)
+        new_values = torch.as_tensor(values, dtype=torch.float32).to(dev)
+        sparse_linear_rebind(self.handle, nnz, new_indptr, new_indices, new_values)
+        self.indptr, self.indices, self.values, self.nnz = new_indptr, new_indices, new_values, nnz
+        if velocity is None:
+            self.velocity = torch.zeros(max(1, nnz), dtype=torch.float32, device=dev)[:nnz]
+        else:
+            self.velocity = torch.as_tensor(velocity, dtype=torch.float32).to(dev)
+
     def close(self):
         if self.handle:
             sparse_linear_destroy(self.handle)
@@ -332,6 +357,11 @@ class MLP:
             return self.workspace[off: off + L.rows * ld].view(L.rows, ld)[:, :batch]
         n = L.nnz if kind == "g" else L.rows
         return self.workspace[off: off + n]
+
+    def rebind_layer(self, l: int, indptr, indices, values, velocity=None):
+        """Topology update of layer l between steps: new pattern, values and (re-mapped) momentum buffer."""
+        self.layers[l].rebind(indptr, indices, values, velocity)
+        mlp_rebind_velocity(self.handle, l, self.layers[l].velocity)
 
     def train_step(self, X, labels, batch: int, lr: float, momentum: float, ldx: Optional[int] = None):
         if ldx is None:

@@ -411,18 +411,15 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
     return NERVA_OK;
 }
 
-int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
-                         const int32_t *indices, float *values, float *bias, int32_t activation, int32_t max_batch,
-                         void *stream)
+// Everything a pattern allows to be precomputed, for a layer whose sizes, caller-owned arrays
+// and max_batch are set and whose owned pointers are all null: validates the CSR, builds the mirror
+// and the position maps (host counting sort), the two partitions and the work buffers.  On failure
+// the layer owns nothing.
+static int build_structures(nerva_layer *l, hipStream_t s)
 {
-    if (!out) return fail(NERVA_ERR_ARGUMENT, "out is null");
-    *out = nullptr;
-    if (rows <= 0 || cols <= 0 || nnz < 0) return fail(NERVA_ERR_ARGUMENT, "bad layer size %d x %d, nnz %d", rows, cols, nnz);
-    if (!indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
-    if (activation != NERVA_ACT_NONE && activation != NERVA_ACT_RELU) return fail(NERVA_ERR_ARGUMENT, "unknown activation %d", activation);
-    if (max_batch <= 0 || max_batch >= (1 << 30)) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive (got %d)", max_batch);
-    hipStream_t s = as_stream(stream);
-
+    const int32_t rows = l->rows, cols = l->cols, nnz = l->nnz, max_batch = l->max_batch;
+    const int32_t *indptr = l->indptr, *indices = l->indices;
+    float *values = l->values;
     std::vector<int32_t> h_indptr(static_cast<size_t>(rows) + 1), h_indices(static_cast<size_t>(nnz));
     HIP_TRY(hipMemcpyAsync(h_indptr.data(), indptr, h_indptr.size() * 4, hipMemcpyDeviceToHost, s));
     if (nnz) HIP_TRY(hipMemcpyAsync(h_indices.data(), indices, h_indices.size() * 4, hipMemcpyDeviceToHost, s));
@@ -431,7 +428,7 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
     if (rc != NERVA_OK) return rc;
 
     // Counting sort of the stored entries by column; ties keep row order, so the mirror is
-    // the canonical CSR of W^T.  Integer work, done once because the pattern never changes.
+    // the canonical CSR of W^T.  Integer work, done when a pattern is bound, not per step.
     std::vector<int32_t> h_indptr_t(static_cast<size_t>(cols) + 1, 0), h_indices_t(nnz), h_perm(nnz), h_pos_t(nnz);
     for (int32_t p = 0; p < nnz; ++p) ++h_indptr_t[h_indices[p] + 1];
     for (int32_t j = 0; j < cols; ++j) h_indptr_t[j + 1] += h_indptr_t[j];
@@ -446,10 +443,6 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
             }
     }
 
-    nerva_layer *l = new (std::nothrow) nerva_layer;
-    if (!l) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
-    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation; l->max_batch = max_batch;
-    l->indptr = indptr; l->indices = indices; l->values = values; l->bias = bias;
     const size_t nb = static_cast<size_t>(nnz > 0 ? nnz : 1) * 4;
     hipError_t e = hipMalloc(&l->indptr_t, (static_cast<size_t>(cols) + 1) * 4);
     if (e == hipSuccess) e = hipMalloc(&l->indices_t, nb);
@@ -486,10 +479,49 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
     if (e != hipSuccess) {
         free_layer_buffers(l);
+        return hip_fail(e, "building the layer's structures");
+    }
+    return NERVA_OK;
+}
+
+int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
+                         const int32_t *indices, float *values, float *bias, int32_t activation, int32_t max_batch,
+                         void *stream)
+{
+    if (!out) return fail(NERVA_ERR_ARGUMENT, "out is null");
+    *out = nullptr;
+    if (rows <= 0 || cols <= 0 || nnz < 0) return fail(NERVA_ERR_ARGUMENT, "bad layer size %d x %d, nnz %d", rows, cols, nnz);
+    if (!indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
+    if (activation != NERVA_ACT_NONE && activation != NERVA_ACT_RELU) return fail(NERVA_ERR_ARGUMENT, "unknown activation %d", activation);
+    if (max_batch <= 0 || max_batch >= (1 << 30)) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive (got %d)", max_batch);
+    nerva_layer *l = new (std::nothrow) nerva_layer;
+    if (!l) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
+    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation; l->max_batch = max_batch;
+    l->indptr = indptr; l->indices = indices; l->values = values; l->bias = bias;
+    const int rc = build_structures(l, as_stream(stream));
+    if (rc != NERVA_OK) {
         delete l;
-        return hip_fail(e, "sparse_linear_create");
+        return rc;
     }
     *out = l;
+    return NERVA_OK;
+}
+
+int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr, const int32_t *indices, float *values,
+                         void *stream)
+{
+    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
+    if (nnz < 0 || !indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
+    hipStream_t s = as_stream(stream);
+    HIP_TRY(hipStreamSynchronize(s));  // launches already queued on this stream still use the old structures
+    nerva_layer fresh;
+    fresh.rows = layer->rows; fresh.cols = layer->cols; fresh.nnz = nnz; fresh.activation = layer->activation;
+    fresh.max_batch = layer->max_batch; fresh.bias = layer->bias;
+    fresh.indptr = indptr; fresh.indices = indices; fresh.values = values;
+    const int rc = build_structures(&fresh, s);
+    if (rc != NERVA_OK) return rc;  // the layer keeps its old pattern
+    free_layer_buffers(layer);
+    *layer = fresh;
     return NERVA_OK;
 }
 
@@ -642,6 +674,16 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     return NERVA_OK;
 }
 
+int mlp_rebind_velocity(nerva_mlp *mlp, int32_t layer_index, float *velocity)
+{
+    if (!mlp) return fail(NERVA_ERR_ARGUMENT, "mlp is null");
+    if (layer_index < 0 || layer_index >= static_cast<int32_t>(mlp->layers.size()))
+        return fail(NERVA_ERR_ARGUMENT, "layer index %d out of range", layer_index);
+    if (!velocity && mlp->layers[layer_index]->nnz > 0) return fail(NERVA_ERR_ARGUMENT, "velocity is null");
+    mlp->vel[layer_index] = velocity;
+    return NERVA_OK;
+}
+
 void mlp_destroy(nerva_mlp *mlp)
 {
     if (!mlp) return;
@@ -771,7 +813,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
 
     // feedforward, then the loss gradient / batch size
     const nerva_layer *last = mlp->layers[n - 1];
-    const bool head = mlp->head;
+    const bool head = mlp->head && head_ok(last->rows, last->cols, last->nnz);  // (a rebind may have grown the layer)
     rc = forward_chain(mlp, X, ldx, batch, ws, L, s, head ? n - 1 : n);
     if (rc != NERVA_OK) return rc;
     if (head) {
