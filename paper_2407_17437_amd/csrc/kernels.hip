@@ -445,24 +445,42 @@ __device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int bl
     const gmem_ptr Mg = as_gmem(a.XM);
     const int n_sets = (a.blocks.n_short + NE - 1) / NE;
     const int src0 = grp * GS * 4;  // byte address of the group's first lane
+    const int first_set = (block * kWavesPerBlock + wv) * kPackSets;
+    if (first_set >= n_sets) return;  // wave-uniform
+    const int last_set = min(first_set + kPackSets, n_sets) - 1;
 
-    for (int r = 0; r < kPackSets; ++r) {
-        const int set = (block * kWavesPerBlock + wv) * kPackSets + r;
-        if (set >= n_sets) break;  // wave-uniform
-        const int4 d = a.blocks.short_rows[set * NE + grp];  // the table is padded to whole sets
+    // Entry base+lig of the group's row: column index and weight (0 past the row's end, where the
+    // row's first entry is repeated; an empty row reads entry 0 of the matrix and is zeroed below).
+    auto fetch = [&](int s0, int len, int base, int &j, float &w) {
+        const int e = base + lig;
+        const bool ok = e < len;
+        const int p = len > 0 ? s0 + (ok ? e : 0) : 0;
+        j = a.indices[p];
+        w = a.values[p];
+        w = ok ? w : 0.f;
+    };
+
+    // One step ahead: while a chunk of GS entries per row is gathered, the indices and weights of
+    // the next chunk (or of the next set's first chunk) and the next set's rows are on their way.
+    int4 d = a.blocks.short_rows[first_set * NE + grp];  // the table is padded to whole sets
+    int cur_j;
+    float cur_w;
+    fetch(d.y, d.z, 0, cur_j, cur_w);
+    for (int set = first_set; set <= last_set; ++set) {
         const int row = d.x, s0 = d.y, len = d.z;
         const int maxlen = __builtin_amdgcn_readfirstlane(len);  // group 0 holds the set's longest row
+        const int4 dn = a.blocks.short_rows[min(set + 1, last_set) * NE + grp];
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int base = 0; base < maxlen; base += GS) {
-            const int e = base + lig;
-            const bool ok = e < len;
-            const int p = len > 0 ? s0 + (ok ? e : 0) : 0;
-            const int my_j = a.indices[p];
-            float my_w = a.values[p];
-            my_w = ok ? my_w : 0.f;
-            const int my_ro = static_cast<int>(static_cast<uint32_t>(my_j) * ldxb);
-            const int my_mo = XMASK ? static_cast<int>(static_cast<uint32_t>(my_j) * ldmb) : 0;
-            const int steps = min(GS, maxlen - base);
+        int base = 0;
+        do {
+            const bool more = base + GS < maxlen;  // wave-uniform
+            int next_j;
+            float next_w;
+            fetch(more ? s0 : dn.y, more ? len : dn.z, more ? base + GS : 0, next_j, next_w);
+            const int my_ro = static_cast<int>(static_cast<uint32_t>(cur_j) * ldxb);
+            const int my_mo = XMASK ? static_cast<int>(static_cast<uint32_t>(cur_j) * ldmb) : 0;
+            const float my_w = cur_w;
+            const int steps = min(GS, maxlen - base);  // 0 for a set of empty rows
             int src = src0;
             int u0 = 0;
             for (; u0 + 8 <= steps; u0 += 8, src += 32) grouped_pass<8, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
@@ -475,7 +493,11 @@ __device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int bl
                 u0 += 2; src += 8;
             }
             if (u0 < steps) grouped_pass<1, 4, XMASK>(Xg, Mg, src, my_ro, my_mo, my_w, off, acc);
-        }
+            cur_j = next_j;
+            cur_w = next_w;
+            base += GS;
+        } while (base < maxlen);
+        d = dn;
         if (row < 0 || !on) continue;
         const float b = a.bias ? a.bias[row] : 0.f;
         float *yr = a.Y + static_cast<int64_t>(row) * a.ldy;
