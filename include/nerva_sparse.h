@@ -94,6 +94,14 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
                          int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host,
                          int32_t *counts_host);
 
+/* Measurement aid: which partition later sparse_linear_create / sparse_linear_rebind /
+ * nerva_plan_*_host calls build (process-wide; layers already bound keep theirs).
+ * NERVA_PARTITION_BALANCED (default): the partition described above.  NERVA_PARTITION_ROW_SPLIT:
+ * plain row splitting -- one wave per row whatever its length, no huge rows, no packed short
+ * rows -- so that the balanced partition can be timed against it on the same matrix. */
+enum { NERVA_PARTITION_BALANCED = 0, NERVA_PARTITION_ROW_SPLIT = 1 };
+int nerva_set_partition_mode(int32_t mode);
+
 /* The second partition, which the products Y = S X and Y = S^T X use on matrices with many short
  * rows (HOST arrays, needs no GPU).  Rows of at most NERVA_PACK_MAX_LEN stored entries are listed
  * longest first (ties in row order) and are served one row per group of lanes, several rows per

@@ -21,12 +21,13 @@ NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
 NERVA_PACK_MAX_LEN, NERVA_PACK_MIN_ROWS = 128, 2048
+NERVA_PARTITION_BALANCED, NERVA_PARTITION_ROW_SPLIT = 0, 1
 NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV, NERVA_MLP_SEPARATE_HEAD = 0, 1, 2, 4
 NERVA_WAVES_PER_BLOCK = 16
 NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
-    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host",
+    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_set_partition_mode",
     "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
@@ -54,6 +55,7 @@ def _load() -> ctypes.CDLL:
         "nerva_validate_csr_host": (ctypes.c_int, [i32, i32, i64, vp, vp]),
         "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp, vp]),
         "nerva_plan_short_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp]),
+        "nerva_set_partition_mode": (ctypes.c_int, [i32]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
         "sparse_linear_rebind": (ctypes.c_int, [vp, i32, vp, vp, vp, vp]),
@@ -138,6 +140,10 @@ def nerva_plan_rows_host(rows: int, indptr):
     _check(lib.nerva_plan_rows_host(rows, indptr.ctypes.data, order.ctypes.data, blocks.ctypes.data, huge.ctypes.data,
                                     waves.ctypes.data, counts.ctypes.data))
     return order[:counts[0]], blocks[:counts[1]], huge[:counts[2]], int(counts[3]), waves[:counts[1]]
+
+
+def nerva_set_partition_mode(mode: int) -> None:
+    _check(lib.nerva_set_partition_mode(mode))
 
 
 def nerva_plan_short_rows_host(rows: int, indptr):

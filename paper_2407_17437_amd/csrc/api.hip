@@ -8,6 +8,7 @@
 #include <new>
 #include <string>
 #include <algorithm>
+#include <atomic>
 #include <functional>
 #include <vector>
 
@@ -18,6 +19,7 @@ using namespace nerva;
 namespace {
 
 thread_local std::string g_last_error;
+std::atomic<int> g_partition_mode{0};  // see nerva_set_partition_mode
 
 int fail(int code, const char *fmt, ...)
 {
@@ -133,10 +135,12 @@ Layout make_layout(const nerva_mlp *m, int32_t batch)
 }
 
 // Rows are grouped by the number of waves that share one row: 2^lg, the smallest power of two
-// that leaves each wave at most `target` stored entries.  `target` aims at >= 16384 waves per
-// launch (64 per compute unit) but never fewer than 8 entries per wave.  A whole work-group on
-// one row may run up to 4x over the target; a row beyond that is huge: it is cut into work-groups
-// of at most 2 * kWavesPerBlock * target entries each.
+// that leaves each wave at most `target` stored entries, target = nnz / 4096 kept within 8..64
+// (measured: with every gather of a pass in flight, fewer and longer shares beat more waves).  A
+// row of more than 4 * kWavesPerBlock * huge_target entries is huge: it is cut into work-groups
+// of at most 2 * kWavesPerBlock * huge_target entries each, huge_target = nnz / 16384 within
+// 8..64 -- finer than `target`, because the few huge rows decide the run time and need many
+// work-groups (a dense 10 x 8192 layer: 320 work-groups instead of 130).
 struct RowPlan {
     std::vector<int32_t> row_order;  // ordinary rows
     std::vector<int32_t> blocks;     // 4 ints per work-group, huge ones first
@@ -152,18 +156,29 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
 {
     RowPlan P;
     const int64_t nnz = indptr[rows];
-    int64_t target = nnz / 16384;
+    // entries per wave aimed at: ordinary rows, and (finer, for more work-groups on the few rows
+    // that decide the run time) the shares of huge rows
+    int64_t target = nnz / 4096;
     if (target < 8) target = 8;
     if (target > 64) target = 64;
-    const int64_t block_cap = target * kWavesPerBlock;
+    int64_t huge_target = nnz / 16384;
+    if (huge_target < 8) huge_target = 8;
+    if (huge_target > 64) huge_target = 64;
+    const int64_t block_cap = huge_target * kWavesPerBlock;
     int max_lg = 0;
     while ((1 << max_lg) < kWavesPerBlock) ++max_lg;
     std::vector<int8_t> lg_of(rows);
     std::vector<int32_t> count(max_lg + 1, 0);
+    const bool row_split_only = g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT;
     for (int32_t i = 0; i < rows; ++i) {
         const int64_t n = indptr[i + 1] - indptr[i];
         if (n <= skip_upto) {
             lg_of[i] = -2;
+            continue;
+        }
+        if (row_split_only) {  // one wave per row whatever its length
+            lg_of[i] = 0;
+            ++count[0];
             continue;
         }
         if (n > 4 * block_cap) {
@@ -241,7 +256,7 @@ std::vector<int32_t> short_row_table(int32_t rows, const int32_t *indptr, int32_
     }
     *n_short = 0;
     std::vector<int32_t> t;
-    if (n < kPackMinRows || indptr[rows] == 0) return t;
+    if (n < kPackMinRows || indptr[rows] == 0 || g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT) return t;
     for (int k = 1; k <= kPackMaxLen + 1; ++k) count[k] += count[k - 1];  // counting sort by descending length
     t.assign(static_cast<size_t>(round_up(n, 64)) * 4, 0);
     for (int64_t k = n; k < round_up(n, 64); ++k) t[4 * k] = -1;
@@ -376,6 +391,13 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz, const int32
         }
     }
     if (indptr[rows] != nnz) return fail(NERVA_ERR_CSR, "indptr[rows] = %d, expected nnz = %lld", indptr[rows], (long long)nnz);
+    return NERVA_OK;
+}
+
+int nerva_set_partition_mode(int32_t mode)
+{
+    if (mode != NERVA_PARTITION_BALANCED && mode != NERVA_PARTITION_ROW_SPLIT) return fail(NERVA_ERR_ARGUMENT, "unknown partition mode %d", mode);
+    g_partition_mode.store(mode);
     return NERVA_OK;
 }
 

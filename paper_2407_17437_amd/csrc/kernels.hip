@@ -648,7 +648,15 @@ __global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
     if (c >= a.batch) return;
     const float *sr = a.scratch + static_cast<int64_t>(h.y) * a.scratch_ld + c;
     float y = 0.f;
-    for (int q = 0; q < h.z; ++q) y += sr[static_cast<int64_t>(q) * a.scratch_ld];
+    int q = 0;
+    for (; q + 8 <= h.z; q += 8) {  // eight loads in flight, added in share order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = sr[static_cast<int64_t>(q + u) * a.scratch_ld];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) y += v[u];
+    }
+    for (; q < h.z; ++q) y += sr[static_cast<int64_t>(q) * a.scratch_ld];
     y += a.bias ? a.bias[h.x] : 0.f;
     if (a.relu) y = y > 0.f ? y : 0.f;
     if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(h.x) * a.ldym + c]);
@@ -861,7 +869,15 @@ __global__ __launch_bounds__(kEwBlock) void sddmm_finish_kernel(const SddmmArgs 
     const int64_t stride = static_cast<int64_t>(blockDim.x) * gridDim.x;
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; p < a.nnz; p += stride) {
         float g = 0.f;
-        for (int t = 0; t < n_tiles; ++t) g += a.partial[static_cast<int64_t>(t) * a.partial_stride + p];
+        int t = 0;
+        for (; t + 8 <= n_tiles; t += 8) {  // eight loads in flight, added in tile order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = a.partial[static_cast<int64_t>(t + u) * a.partial_stride + p];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) g += v[u];
+        }
+        for (; t < n_tiles; ++t) g += a.partial[static_cast<int64_t>(t) * a.partial_stride + p];
         if (a.g) a.g[p] = g;
         if (a.fused) {
             float w = a.values[p], v = a.velocity[p];

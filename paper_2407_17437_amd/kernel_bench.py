@@ -30,6 +30,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, nargs="+", default=[128, 1024])
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--uniform", action="store_true", help="uniform random pattern instead of power-law rows")
+    ap.add_argument("--row-split", action="store_true",
+                    help="build the layers with plain row splitting (one wave per row) instead of the balanced partition")
     args = ap.parse_args()
 
     import numpy as np
@@ -38,6 +40,8 @@ def main() -> int:
     from paper_2407_17437_amd import workloads as wl
 
     assert torch.cuda.is_available()
+    if args.row_split:
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_ROW_SPLIT)
     n = args.n
     flush = torch.empty(768 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")   # larger than every cache
 
@@ -87,7 +91,8 @@ def main() -> int:
                 cold, warm = timed(fn, args.reps)
                 print(json.dumps({
                     "kernel": name, "n": n, "density": dens, "nnz": nnz, "batch": batch,
-                    "rows": "uniform" if args.uniform else "zipf1.2", "max_row": int(rn.max()), "median_row": float(np.median(rn)),
+                    "rows": "uniform" if args.uniform else "zipf1.2",
+                    "partition": "row-split" if args.row_split else "balanced", "max_row": int(rn.max()), "median_row": float(np.median(rn)),
                     "us_cold": round(cold, 2), "us_back_to_back": round(warm, 2), "algorithmic_MB": round(byt / 1e6, 2),
                     "gflop": round(2.0 * nnz * batch / 1e9, 3),
                     "gbs_cold": round(byt / cold / 1e3, 1), "frac_hbm_cold": round(byt / cold / 1e3 / HBM_PEAK_GBS, 4),
