@@ -57,6 +57,10 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
         return 20 * m
     if kind == "mirror_refresh":
         return 12 * nnz
+    if kind == "dense_forward":       # the dense copy of the weights, X in, Y out, bias
+        return 4 * m * k + 4 * n * (k + m) + 4 * m
+    if kind == "dense_transposed":    # the dense copy, dZ in, dX out, ReLU mask in
+        return 4 * m * k + 4 * n * (m + k) + 4 * n * k
     if kind == "softmax_ce":
         return 8 * n * m + 4 * n
     if kind == "spmm_forward+softmax_ce+spmm_transposed":
@@ -117,6 +121,8 @@ def main() -> int:
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0: skip)")
     ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
     ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--dense-from-density", type=float, default=None,
+                    help="layers of at least this density take the dense MFMA route for their two products (default: none)")
     ap.add_argument("--separate-head", action="store_true",
                     help="keep the output layer's forward product, loss and transposed product as three launches")
     ap.add_argument("--inference", action="store_true",
@@ -144,7 +150,7 @@ def main() -> int:
     Xd[:, :, :batch] = torch.as_tensor(Xs).cuda()
     Td = torch.as_tensor(Ts).cuda()
     M = nb.MLP(mlp, batch, (nb.NERVA_MLP_UNFUSED if args.unfused else 0) |
-               (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0))
+               (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0), dense_from_density=args.dense_from_density)
     x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4
     t_ptr, t_stride = Td.data_ptr(), batch * 4
     lr, mu = 0.01, 0.9
@@ -229,7 +235,7 @@ def main() -> int:
         # HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this same command
         traffic = None
         tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
-        if os.path.exists(tpath) and not graphs and not args.unfused and not args.separate_head:
+        if os.path.exists(tpath) and not graphs and not args.unfused and not args.separate_head and args.dense_from_density is None:
             traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dom["kernel"])
         roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],

@@ -144,10 +144,32 @@ void sparse_linear_destroy(nerva_layer *layer);
  * over.  On any error (bad CSR: NERVA_ERR_CSR, allocation: NERVA_ERR_HIP) the layer keeps its
  * old pattern and stays usable.  Momentum buffers are the caller's: after a rebind of a layer
  * that belongs to an MLP, hand the MLP a velocity array of the new length, mapped to the new
- * entries as the method prescribes (zero for grown ones), with mlp_rebind_velocity.  Host-side
- * integer work proportional to nnz; not meant for every step. */
+ * entries as the method prescribes (zero for grown ones), with mlp_rebind_velocity, and ask
+ * mlp_workspace_bytes / mlp_workspace_layout again: the workspace holds one float per stored
+ * entry of every layer, so its size and offsets move with nnz.  Host-side integer work
+ * proportional to nnz; not meant for every step. */
 int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
                          const int32_t *indices, float *values, void *stream);
+
+/* Density-adaptive layer ("Discussion and Conclusion": dense computation where a layer is not
+ * sparse enough for the sparse kernels to win; Section 5.5 / Table 2 show masks winning at 50 %
+ * sparsity).  After this call the layer's products Y = S X and Y = S^T X on batches of at
+ * least 16 columns run as dense fp32 MFMA products on two zero-filled dense copies of the weights
+ * (W and W^T, rows x cols floats each, owned by the layer); S = A B^T on the pattern, the
+ * momentum update and values[] stay sparse and remain the layer's state, and every update the
+ * library applies is written to the copies as well.  Results agree with the sparse route to
+ * rounding (other summation order); entries off the pattern contribute 0 * x, so an operand that
+ * holds Inf/NaN spreads differently.  Which layers to switch is the caller's choice (density at
+ * least 1/2 is the paper's regime; measured crossover in the design doc).  Survives
+ * sparse_linear_rebind.  Errors: NERVA_ERR_SHAPE (rows x cols beyond 2^31), NERVA_ERR_HIP. */
+int sparse_linear_enable_dense(nerva_layer *layer, void *stream);
+
+/* The library keeps derived copies of values[] (the mirror's values, the dense copies above) and
+ * updates them whenever it updates values[].  After the CALLER has written values[] (loaded
+ * weights, a prune-and-grow step without rebind), this call brings the copies up to date;
+ * mlp_train_step and mlp_forward rely on them.  sparse_linear_forward / sparse_linear_backward
+ * refresh what they read on every call and do not need it. */
+int sparse_linear_sync_values(nerva_layer *layer, void *stream);
 
 /* Device pointers of the mirror, for inspection: indptr_t[cols+1], indices_t[nnz],
  * values_t[nnz], perm[nnz] (mirror position -> CSR position). Any output may be NULL. */

@@ -28,7 +28,7 @@ NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
     "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_set_partition_mode",
-    "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_mirror",
+    "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_enable_dense", "sparse_linear_sync_values", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
     "mlp_workspace_layout", "mlp_train_step", "mlp_forward", "nerva_copy_f32",
@@ -59,6 +59,8 @@ def _load() -> ctypes.CDLL:
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
         "sparse_linear_rebind": (ctypes.c_int, [vp, i32, vp, vp, vp, vp]),
+        "sparse_linear_enable_dense": (ctypes.c_int, [vp, vp]),
+        "sparse_linear_sync_values": (ctypes.c_int, [vp, vp]),
         "mlp_rebind_velocity": (ctypes.c_int, [vp, i32, vp]),
         "sparse_linear_mirror": (ctypes.c_int, [vp, vp, vp, vp, vp]),
         "sparse_linear_forward": (ctypes.c_int, [vp, vp, i32, vp, i32, i32, vp]),
@@ -174,6 +176,14 @@ def sparse_linear_destroy(layer: int) -> None:
 
 def sparse_linear_rebind(layer: int, nnz, indptr, indices, values, stream=None) -> None:
     _check(lib.sparse_linear_rebind(layer, nnz, _ptr(indptr), _ptr(indices), _ptr(values), _stream(stream)))
+
+
+def sparse_linear_enable_dense(layer: int, stream=None) -> None:
+    _check(lib.sparse_linear_enable_dense(layer, _stream(stream)))
+
+
+def sparse_linear_sync_values(layer: int, stream=None) -> None:
+    _check(lib.sparse_linear_sync_values(layer, _stream(stream)))
 
 
 def mlp_rebind_velocity(mlp: int, layer_index: int, velocity) -> None:
@@ -332,10 +342,15 @@ class SparseLinear:
 class MLP:
     """A chain of SparseLinear layers, the library's MLP handle and its workspace."""
 
-    def __init__(self, mlp_data, max_batch: int, flags: int = NERVA_MLP_DEFAULT, device="cuda"):
+    def __init__(self, mlp_data, max_batch: int, flags: int = NERVA_MLP_DEFAULT, device="cuda", dense_from_density=None):
+        """dense_from_density: layers whose density is at least this take the dense route (None: none)."""
         self.handle = None
         self.layers = []
         self.layers = [SparseLinear(l, max_batch, device) for l in mlp_data.layers]
+        if dense_from_density is not None:
+            for l in self.layers:
+                if l.nnz >= dense_from_density * l.rows * l.cols:
+                    sparse_linear_enable_dense(l.handle)
         self.max_batch = max_batch
         self.handle = mlp_create([l.handle for l in self.layers], [l.velocity for l in self.layers],
                                  [l.bias_velocity for l in self.layers], max_batch, flags)
@@ -368,6 +383,11 @@ class MLP:
         """Topology update of layer l between steps: new pattern, values and (re-mapped) momentum buffer."""
         self.layers[l].rebind(indptr, indices, values, velocity)
         mlp_rebind_velocity(self.handle, l, self.layers[l].velocity)
+        # the workspace layout holds one float per stored entry of every layer: it moves with nnz
+        self._layout_batch = None
+        nbytes = mlp_workspace_bytes(self.handle, self.max_batch)
+        if nbytes // 4 > self.workspace.numel():
+            self.workspace = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device=self.workspace.device)
 
     def train_step(self, X, labels, batch: int, lr: float, momentum: float, ldx: Optional[int] = None):
         if ldx is None:

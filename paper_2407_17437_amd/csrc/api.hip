@@ -73,6 +73,13 @@ struct nerva_layer {
     float *partial = nullptr;
     int64_t partial_stride = 0, partial_db_at = 0;
     int32_t partial_tiles = 0;
+    // owned, only after sparse_linear_enable_dense: zero-filled dense copies of W (rows x dense_ld)
+    // and of W^T (cols x dense_t_ld), leading dimensions padded to multiples of 32
+    bool dense_on = false;
+    float *dense = nullptr, *dense_t = nullptr;
+    int64_t dense_ld = 0, dense_t_ld = 0;
+    float *dense_scratch = nullptr;  // partial tiles of a K-split product: kDenseMaxSplits x max(rows, cols) x dense_scratch_ld
+    int64_t dense_scratch_ld = 0;
 };
 
 // Optional per-kernel timing of mlp_train_step: one HIP event before every launch and one after
@@ -332,6 +339,9 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->indices_t);
     (void)hipFree(l->values_t);
     (void)hipFree(l->partial);
+    (void)hipFree(l->dense);
+    (void)hipFree(l->dense_t);
+    (void)hipFree(l->dense_scratch);
     (void)hipFree(l->perm);
     (void)hipFree(l->pos_t);
 }
@@ -433,6 +443,54 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
     return NERVA_OK;
 }
 
+// Dense copies for the dense route: allocated zero, then filled from the stored entries.
+static hipError_t build_dense_copies(nerva_layer *l, hipStream_t s)
+{
+    l->dense_ld = round_up(l->cols, 32);
+    l->dense_t_ld = round_up(l->rows, 32);
+    const size_t bytes = static_cast<size_t>(l->rows) * l->dense_ld * 4, bytes_t = static_cast<size_t>(l->cols) * l->dense_t_ld * 4;
+    l->dense_scratch_ld = round_up(l->max_batch, 32);
+    const size_t bytes_s = static_cast<size_t>(kDenseMaxSplits) * (l->rows > l->cols ? l->rows : l->cols) * l->dense_scratch_ld * 4;
+    hipError_t e = hipMalloc(&l->dense, bytes);
+    if (e == hipSuccess) e = hipMalloc(&l->dense_t, bytes_t);
+    if (e == hipSuccess) e = hipMalloc(&l->dense_scratch, bytes_s);
+    if (e == hipSuccess) e = hipMemsetAsync(l->dense, 0, bytes, s);
+    if (e == hipSuccess) e = hipMemsetAsync(l->dense_t, 0, bytes_t, s);
+    if (e == hipSuccess)
+        e = launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, l->dense_t, l->dense_t_ld, s);
+    return e;
+}
+
+static hipError_t refresh_dense_copies(const nerva_layer *l, hipStream_t s)
+{
+    return launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, l->dense_t, l->dense_t_ld, s);
+}
+
+// Y = act(W X + b) through the dense copy of W^T
+static hipError_t dense_forward(const nerva_layer *l, const float *X, int64_t ldx, float *Y, int64_t ldy, int32_t batch,
+                                hipStream_t s)
+{
+    DenseArgs d{};
+    d.AT = l->dense_t; d.lda = l->dense_t_ld; d.X = X; d.ldx = ldx; d.Y = Y; d.ldy = ldy; d.bias = l->bias;
+    d.M = l->rows; d.K = l->cols; d.batch = batch; d.relu = l->activation == NERVA_ACT_RELU;
+    d.scratch = l->dense_scratch; d.scratch_ld = l->dense_scratch_ld;
+    return launch_dense_gemm(d, s);
+}
+
+// dX = (W^T dZ) * [mask > 0] through the dense copy of W
+static hipError_t dense_transposed(const nerva_layer *l, const float *dZ, int64_t lddz, float *dX, int64_t lddx,
+                                   const float *mask, int64_t ldmask, int32_t batch, hipStream_t s)
+{
+    DenseArgs d{};
+    d.AT = l->dense; d.lda = l->dense_ld; d.X = dZ; d.ldx = lddz; d.Y = dX; d.ldy = lddx;
+    d.YM = mask; d.ldym = ldmask; d.M = l->cols; d.K = l->rows; d.batch = batch;
+    d.scratch = l->dense_scratch; d.scratch_ld = l->dense_scratch_ld;
+    return launch_dense_gemm(d, s);
+}
+
+// the dense route needs a batch wide enough to fill its 32-column tiles
+static bool use_dense(const nerva_layer *l, int32_t batch) { return l->dense_on && batch >= 16; }
+
 // Everything a pattern allows to be precomputed, for a layer whose sizes, caller-owned arrays
 // and max_batch are set and whose owned pointers are all null: validates the CSR, builds the mirror
 // and the position maps (host counting sort), the two partitions and the work buffers.  On failure
@@ -498,6 +556,7 @@ static int build_structures(nerva_layer *l, hipStream_t s)
         if (slots > 0) e = hipMalloc(&l->scratch, static_cast<size_t>(slots) * l->scratch_ld * 4);
     }
     if (e == hipSuccess) e = launch_gather(l->values_t, values, l->perm, nnz, s);
+    if (e == hipSuccess && l->dense_on) e = build_dense_copies(l, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
     if (e != hipSuccess) {
         free_layer_buffers(l);
@@ -538,12 +597,42 @@ int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
     HIP_TRY(hipStreamSynchronize(s));  // launches already queued on this stream still use the old structures
     nerva_layer fresh;
     fresh.rows = layer->rows; fresh.cols = layer->cols; fresh.nnz = nnz; fresh.activation = layer->activation;
-    fresh.max_batch = layer->max_batch; fresh.bias = layer->bias;
+    fresh.max_batch = layer->max_batch; fresh.bias = layer->bias; fresh.dense_on = layer->dense_on;
     fresh.indptr = indptr; fresh.indices = indices; fresh.values = values;
     const int rc = build_structures(&fresh, s);
     if (rc != NERVA_OK) return rc;  // the layer keeps its old pattern
     free_layer_buffers(layer);
     *layer = fresh;
+    return NERVA_OK;
+}
+
+int sparse_linear_enable_dense(nerva_layer *layer, void *stream)
+{
+    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
+    if (layer->dense_on) return NERVA_OK;
+    if (static_cast<int64_t>(layer->rows) * round_up(layer->cols, 32) >= (1ll << 31) ||
+        static_cast<int64_t>(layer->cols) * round_up(layer->rows, 32) >= (1ll << 31))
+        return fail(NERVA_ERR_SHAPE, "a %d x %d layer is too large for the dense route", layer->rows, layer->cols);
+    hipStream_t s = as_stream(stream);
+    hipError_t e = build_dense_copies(layer, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        (void)hipFree(layer->dense);
+        (void)hipFree(layer->dense_t);
+        (void)hipFree(layer->dense_scratch);
+        layer->dense = layer->dense_t = layer->dense_scratch = nullptr;
+        return hip_fail(e, "sparse_linear_enable_dense");
+    }
+    layer->dense_on = true;
+    return NERVA_OK;
+}
+
+int sparse_linear_sync_values(nerva_layer *layer, void *stream)
+{
+    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
+    hipStream_t s = as_stream(stream);
+    HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
+    if (layer->dense_on) HIP_TRY(refresh_dense_copies(layer, s));
     return NERVA_OK;
 }
 
@@ -573,6 +662,12 @@ int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
     if (rc == NERVA_OK) rc = check_batch(batch, ldy, "ldy");
     if (rc == NERVA_OK && batch > layer->max_batch) rc = fail(NERVA_ERR_SHAPE, "batch %d exceeds the layer's max_batch %d", batch, layer->max_batch);
     if (rc != NERVA_OK) return rc;
+    if (use_dense(layer, batch)) {
+        // a stand-alone call cannot know whether the caller has changed values[] since the last one
+        HIP_TRY(refresh_dense_copies(layer, as_stream(stream)));
+        HIP_TRY(dense_forward(layer, X, ldx, Y, ldy, batch, as_stream(stream)));
+        return NERVA_OK;
+    }
     SpmmArgs a{};
     a.blocks = layer->plan; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
     a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
@@ -597,7 +692,10 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
     if (rc == NERVA_OK && batch > layer->max_batch) rc = fail(NERVA_ERR_SHAPE, "batch %d exceeds the layer's max_batch %d", batch, layer->max_batch);
     if (rc != NERVA_OK) return rc;
     hipStream_t s = as_stream(stream);
-    if (dX) {
+    if (dX && use_dense(layer, batch) && !relu) {
+        HIP_TRY(refresh_dense_copies(layer, s));
+        HIP_TRY(dense_transposed(layer, dY, lddy, dX, lddx, nullptr, 0, batch, s));
+    } else if (dX) {
         HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
         SpmmArgs a{};
         a.blocks = layer->plan_t; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
@@ -799,7 +897,10 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
         a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
-        {
+        if (use_dense(ly, batch)) {
+            Timed tm(mlp->prof, s, "dense_forward", static_cast<int>(l));
+            HIP_TRY(dense_forward(ly, in, ldin, A, L.ld, batch, s));
+        } else {
             Timed tm(mlp->prof, s, "spmm_forward", static_cast<int>(l));
             HIP_TRY(launch_spmm(a, s));
         }
@@ -883,6 +984,7 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
+            if (ly->dense_on) { g.dense = ly->dense; g.dense_t = ly->dense_t; g.dense_ld = ly->dense_ld; g.dense_t_ld = ly->dense_t_ld; }
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
         } else {
             g.g = reinterpret_cast<float *>(ws + L.g[l]);
@@ -895,14 +997,26 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         // Launch order T_{n-1} | T_{n-2} + S_{n-1} | ... | T_1 + S_2 | S_1 + S_0: the fused
         // SDDMM+update S_l of a layer shares a grid with the transposed product of the layer
         // below, which no longer depends on it (S_l only needs dZ_l and must follow T_l).
+        // dZ_{l-1} through the dense copy of layer l's weights
+        auto dense_T = [&](int l) {
+            return dense_transposed(mlp->layers[l], dZ(l), L.ld, dZ(l - 1), L.ld, A(l - 1), L.ld, batch, s);
+        };
         if (n > 1 && !head) {
-            Timed tm(mlp->prof, s, "spmm_transposed", n - 1);
-            HIP_TRY(launch_spmm(make_T(n - 1), s));
+            if (use_dense(mlp->layers[n - 1], batch)) {
+                Timed tm(mlp->prof, s, "dense_transposed", n - 1);
+                HIP_TRY(dense_T(n - 1));
+            } else {
+                Timed tm(mlp->prof, s, "spmm_transposed", n - 1);
+                HIP_TRY(launch_spmm(make_T(n - 1), s));
+            }
         }
         for (int l = n - 1; l >= 2; --l) {
             const SpmmArgs t = make_T(l - 1);
             const SddmmArgs g = make_S(l);
-            if (can_pair(t, g)) {
+            if (use_dense(mlp->layers[l - 1], batch)) {
+                { Timed tm(mlp->prof, s, "dense_transposed", l - 1); HIP_TRY(dense_T(l - 1)); }
+                { Timed tm(mlp->prof, s, "sddmm_update", l); HIP_TRY(launch_sddmm(g, s)); }
+            } else if (can_pair(t, g)) {
                 Timed tm(mlp->prof, s, "spmm_transposed+sddmm_update", l - 1);
                 HIP_TRY(launch_pair(t, g, s));
             } else {
@@ -927,8 +1041,13 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         for (int l = n - 1; l >= 0; --l) {
             nerva_layer *ly = mlp->layers[l];
             if (l > 0 && !(head && l == n - 1)) {
-                Timed tm(mlp->prof, s, "spmm_transposed", l);
-                HIP_TRY(launch_spmm(make_T(l), s));
+                if (use_dense(ly, batch)) {
+                    Timed tm(mlp->prof, s, "dense_transposed", l);
+                    HIP_TRY(dense_transposed(ly, dZ(l), L.ld, dZ(l - 1), L.ld, A(l - 1), L.ld, batch, s));
+                } else {
+                    Timed tm(mlp->prof, s, "spmm_transposed", l);
+                    HIP_TRY(launch_spmm(make_T(l), s));
+                }
             }
             const SddmmArgs g = make_S(l);
             {
@@ -946,6 +1065,10 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
             if (l > 0) {
                 Timed tm(mlp->prof, s, "mirror_refresh", l);
                 HIP_TRY(launch_gather(ly->values_t, ly->values, ly->perm, ly->nnz, s));
+            }
+            if (ly->dense_on) {
+                Timed tm(mlp->prof, s, "dense_refresh", l);
+                HIP_TRY(refresh_dense_copies(ly, s));
             }
         }
     }

@@ -109,6 +109,10 @@ struct SddmmArgs {
     int64_t partial_db_at;    // >= nnz
     int32_t partial_tiles;    // tiles the buffer has room for
     int32_t nnz;
+    // dense copies of a layer on the dense route (or nullptr): the fused update stores every new
+    // weight there too, dense[row * dense_ld + col] and dense_t[col * dense_t_ld + row]
+    float *dense, *dense_t;
+    int64_t dense_ld, dense_t_ld;
 };
 // Column-tile width (in columns) the products use when their gathered operand has x_rows rows and
 // does not fit an L2; 0: no tiling.  Shared by the kernels' dispatch and by the sizing of the
@@ -130,6 +134,36 @@ hipError_t launch_gather(float *values_t, const float *values, const int32_t *pe
 hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels, int32_t classes,
                              int32_t batch, float *dZ, int64_t lddz, float *loss, hipStream_t s);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
+
+// Dense route of a layer whose density is high (the density-adaptive layer the paper plans in
+// "Discussion and Conclusion"): Y = epilogue(A^T X) as an fp32 MFMA product, with A stored K-major
+// -- AT[k * lda + i] = A[i][k], lda a multiple of 32, padding zero -- so that the lanes of a wave
+// read consecutive addresses of both operands.  The forward product uses the dense copy of W^T
+// (K = cols), the transposed product the dense copy of W (K = rows); both hold 0 off the pattern.
+struct DenseArgs {
+    const float *AT;     // (K, lda)
+    int64_t lda;
+    const float *X;      // (K, ldx)
+    int64_t ldx;
+    float *Y;            // (M, ldy)
+    int64_t ldy;
+    const float *bias;   // [M] or nullptr
+    const float *YM;     // optional (M, ldym): result is multiplied by [YM > 0]
+    int64_t ldym;
+    int32_t M, K, batch;
+    int32_t relu;
+    // K is also split over up to kDenseMaxSplits work-groups per tile when there are too few tiles
+    // to fill the chip; their partial tiles go to scratch[(split * M + row) * scratch_ld + column]
+    // and a second kernel adds them in split order and applies the epilogue.
+    float *scratch;      // room for kDenseMaxSplits * M * scratch_ld floats, or nullptr (then no split)
+    int64_t scratch_ld;  // >= batch
+};
+constexpr int32_t kDenseMaxSplits = 8;
+hipError_t launch_dense_gemm(const DenseArgs &a, hipStream_t s);
+// dense[i * ld + j] = dense_t[j * ld_t + i] = values[p] for every stored entry p = (i, j); the
+// rest of both arrays is not touched (zero since allocation)
+hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows,
+                                float *dense, int64_t ld, float *dense_t, int64_t ld_t, hipStream_t s);
 
 // The end of the forward pass and the start of the backward pass for a small output layer, in
 // one launch: logits Z = W X + b, softmax cross-entropy (loss and dZ = (softmax - onehot) / batch),

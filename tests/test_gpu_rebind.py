@@ -107,6 +107,29 @@ def test_layer_rebind(nb, torch_mod, oracle, rows, cols, density, new_density, b
     L.close()
 
 
+def test_mlp_forward_after_a_rebind_that_changes_nnz(nb, torch_mod, oracle):
+    """The workspace layout depends on every layer's nnz: after a rebind to a larger pattern the binding asks
+    for the layout (and the size) again, and the forward pass through all layers matches the oracle."""
+    torch = torch_mod
+    sizes, batch = (48, 64, 10), 32
+    mlp = wl.make_mlp(sizes, sparsity=0.4, bias_std=0.1, pattern_seed=61, value_seed=62)
+    X = np.random.default_rng(63).standard_normal((sizes[0], batch)).astype(np.float32)
+    M = nb.MLP(mlp, batch)
+    for density in (0.9, 0.1):
+        lay = mlp.layers[0]
+        new = layer_case(lay.rows, lay.cols, density, seed=64, relu=True)
+        M.rebind_layer(0, new.indptr, new.indices, new.values)
+        out = M.forward(nb.to_dense(X), batch).cpu().numpy()
+        torch.cuda.synchronize()
+        A0 = M.view("A", 0, batch).cpu().numpy()
+        ref0, S0 = oracle.spmm(lay.rows, lay.cols, new.indptr, new.indices, new.values, M.layers[0].bias.cpu().numpy(), X, True)
+        close(A0, ref0, S0, what="A[0]")
+        l1 = mlp.layers[1]
+        ref1, S1 = oracle.spmm(l1.rows, l1.cols, l1.indptr, l1.indices, l1.values, l1.bias, A0, False)
+        close(out, ref1, S1, what="logits")
+    M.close()
+
+
 def test_rebind_rejects_bad_pattern_and_keeps_the_old_one(nb, torch_mod, oracle):
     torch = torch_mod
     a = layer_case(40, 30, 0.3, seed=5, relu=False)
