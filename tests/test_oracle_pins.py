@@ -369,3 +369,37 @@ def test_nesterov_closed_forms(oracle):
     w2, v2, _, _ = oracle.momentum(w0, v0, g, 0.1, 0.9, dtype=np.float64, nesterov=False)
     w3, v3, _, _ = oracle.momentum(w0, v0, g, 0.1, 0.9, dtype=np.float64, nesterov=True)
     assert np.array_equal(v2, v3) and np.allclose(w3 - w2, 0.9 * v3 - 0.1 * g - v3, rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("nesterov", [False, True])
+def test_training_loop_matches_masked_dense_autograd(oracle, nesterov):
+    """The whole loop (feedforward, loss gradient / batch size, backpropagate from the step's initial weights,
+    optimize weights AND biases) against an independent implementation: a masked dense MLP in torch (CPU, fp64),
+    gradients by autograd, torch.optim.SGD with momentum -- the masked reference the paper compares with
+    (Section 5).  Constant learning rate, so torch's v = mu v + g ; w -= lr v is the same iteration."""
+    import torch
+    mlp = _tiny_mlp()
+    rng = np.random.default_rng(77)
+    B, steps, lr, mu = 5, 4, 0.1, 0.9
+    Xs = rng.standard_normal((steps, 7, B)); Ts = rng.integers(0, 3, size=(steps, B))
+    state = oracle.new_state(mlp.layers, np.float64)
+    Ws, Ms, bs = [], [], []
+    for lay in mlp.layers:
+        W, M = _dense(lay)
+        Ws.append(torch.nn.Parameter(torch.tensor(W))); Ms.append(torch.tensor(M)); bs.append(torch.nn.Parameter(torch.tensor(lay.bias, dtype=torch.float64)))
+    opt = torch.optim.SGD(Ws + bs, lr=lr, momentum=mu, nesterov=nesterov)
+    for t in range(steps):
+        out = oracle.mlp_step(state, Xs[t], Ts[t], lr, mu, np.float64, nesterov=nesterov)
+        a = torch.tensor(Xs[t])
+        for l in range(3):
+            a = (Ws[l] * Ms[l]) @ a + bs[l][:, None]
+            if l < 2:
+                a = torch.relu(a)
+        loss = torch.nn.functional.cross_entropy(a.T, torch.tensor(Ts[t]), reduction="mean")
+        opt.zero_grad(); loss.backward(); opt.step()
+        assert out["loss"] == pytest.approx(float(loss), rel=1e-12)
+        for l, lay in enumerate(mlp.layers):
+            W = Ws[l].detach().numpy()
+            got = np.array([W[i, lay.indices[p]] for i in range(lay.rows) for p in range(lay.indptr[i], lay.indptr[i + 1])])
+            np.testing.assert_allclose(state[l]["values"], got, rtol=1e-10, atol=1e-13, err_msg=f"values[{l}] after step {t}")
+            np.testing.assert_allclose(state[l]["bias"], bs[l].detach().numpy(), rtol=1e-10, atol=1e-13, err_msg=f"bias[{l}] after step {t}")
