@@ -163,3 +163,37 @@ def test_config5_kernels_sampled(nb, torch_mod, oracle, density, batch):
     torch.cuda.synchronize()
     assert torch.equal(Y2, Yd) and torch.equal(g2, g) and torch.equal(db2, db) and torch.equal(dX2, dXd)
     Lh.close()
+
+
+def test_operand_beyond_4gib(nb, torch_mod, oracle):
+    """A gathered operand that spans more than 4 GiB (2^20 + 5 rows with a leading dimension of 1024 floats):
+    the kernels that address the operand with 32-bit byte offsets must step aside for the ones with 64-bit row
+    bases.  The oracle works on the referenced operand rows only (same sums, compacted column indices)."""
+    torch = torch_mod
+    rows, cols, batch, ld, per_row = 64, (1 << 20) + 5, 100, 1024, 12
+    rng = np.random.default_rng(2024)
+    indptr = np.arange(0, rows * per_row + 1, per_row, dtype=np.int32)
+    indices = np.empty(rows * per_row, dtype=np.int32)
+    for i in range(rows):
+        c = rng.choice(cols - 1, size=per_row - 1, replace=False)
+        indices[i * per_row:(i + 1) * per_row] = np.sort(np.concatenate([c, [cols - 1]]))   # every row reaches the far end
+    values = rng.standard_normal(rows * per_row).astype(np.float32)
+    bias = rng.standard_normal(rows).astype(np.float32)
+    lay = wl.SparseLayerData(rows, cols, indptr, indices, values, bias, False)
+    L = nb.SparseLinear(lay, max_batch=batch)
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    Xd = torch.randn((cols, ld), generator=g, device="cuda", dtype=torch.float32)
+    assert Xd.numel() * 4 > (1 << 32)
+    dY = rng.standard_normal((rows, batch)).astype(np.float32)
+    Yd = nb.dense(rows, batch); dYd = nb.to_dense(dY)
+    gv = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)                      # the tensor's row stride (1024) is ldx
+    nb.sparse_linear_backward(L.handle, Xd, None, dYd, None, gv, db, batch)
+    torch.cuda.synchronize()
+    used, compact = np.unique(indices, return_inverse=True)
+    Xs = Xd[torch.as_tensor(used, dtype=torch.int64, device="cuda"), :batch].cpu().numpy()
+    Y, S = oracle.spmm(rows, len(used), indptr, compact.astype(np.int32), values, bias, Xs, False)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, len(used), indptr, compact.astype(np.int32), dY, Xs)
+    close(gv.cpu().numpy(), gr, Sg, what="dvalues"); close(db.cpu().numpy(), dbr, Sdb, what="dbias")
+    L.close()

@@ -309,3 +309,56 @@ def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
         gr, Sg, dbr, Sdb = oracle.sddmm(1024, 1024, z.indptr, z.indices, dY, X)
         close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
         L.close()
+
+
+def _random_case(k):
+    """Seeded draw of a layer shape, a row-length distribution, a batch and a leading dimension, spread over the
+    regimes that select different kernels (lanes across entries, grouped, wide, column tiles, packed short rows,
+    huge rows, scalar paths for odd leading dimensions)."""
+    rng = np.random.default_rng(9000 + k)
+    rows = int(rng.choice([1, 3, 17, 64, 200, 1000, 2500, 5000]))
+    cols = int(rng.choice([1, 5, 33, 128, 700, 3000, 9000]))
+    kind = rng.choice(["uniform", "zipf", "dense_rows", "empty_heavy"])
+    if kind == "uniform":
+        lens = rng.binomial(cols, rng.choice([0.002, 0.02, 0.2, 0.7]), size=rows)
+    elif kind == "zipf":
+        lens = np.minimum(cols, (cols * rng.permutation(np.arange(1, rows + 1)) ** -1.2).astype(np.int64))
+    elif kind == "dense_rows":
+        lens = np.where(rng.random(rows) < 0.05, cols, rng.integers(0, min(cols, 8) + 1, size=rows))
+    else:
+        lens = np.where(rng.random(rows) < 0.9, 0, rng.integers(0, min(cols, 300) + 1, size=rows))
+    if lens.sum() > 3_000_000:
+        lens = (lens * (3_000_000 / lens.sum())).astype(np.int64)
+    batch = int(rng.choice([1, 2, 4, 5, 16, 31, 64, 100, 128, 129, 256, 500, 1024]))
+    ld = None if rng.random() < 0.7 else batch + int(rng.integers(0, 9))
+    return rows, cols, lens.astype(np.int64), batch, ld, bool(rng.random() < 0.5)
+
+
+@pytest.mark.parametrize("k", range(48))
+def test_random_shapes_all_three_products(nb, torch_mod, oracle, k):
+    torch = torch_mod
+    rows, cols, lens, batch, ld, relu = _random_case(k)
+    indptr, indices = wl.pattern_from_row_nnz(lens, cols, seed=9100 + k)
+    rng = np.random.default_rng(9200 + k)
+    lay = wl.SparseLayerData(rows, cols, indptr, indices, rng.standard_normal(int(indptr[-1])).astype(np.float32),
+                             rng.standard_normal(rows).astype(np.float32), relu)
+    if lay.nnz * batch > 400_000_000:                        # keep the oracle's share of the run short
+        batch = max(1, 400_000_000 // max(lay.nnz, 1))
+        ld = None
+    X = rng.standard_normal((cols, batch)).astype(np.float32)
+    dY = rng.standard_normal((rows, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay, max_batch=batch)
+    Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld); dYd = nb.to_dense(dY, ld=ld); dXd = nb.dense(cols, batch, ld=ld)
+    g = torch.full((max(lay.nnz, 1),), float("nan"), device="cuda")[:lay.nnz]
+    db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(rows, cols, lay.indptr, lay.indices, lay.values, lay.bias, X, relu)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    dZ = oracle.relu_backward(dY, Yd.cpu().numpy()) if relu else dY
+    dX, SdX = oracle.spmm_t(rows, cols, lay.indptr, lay.indices, lay.values, dZ)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, lay.indptr, lay.indices, dZ, X)
+    close(g.cpu().numpy(), gr, Sg, what="dvalues"); close(db.cpu().numpy(), dbr, Sdb, what="dbias")
+    L.close()
