@@ -2,12 +2,16 @@
 //
 // Mapping shared by the sparse kernels: lanes of a 64-wide wavefront run along the batch
 // dimension, so every gather of a dense row is one contiguous, coalesced read (one example
-// per column, batch contiguous).  Row pointers, column indices and weights are wave-uniform
-// and travel through the scalar path.  Rows are handed to work-groups by a static partition
-// (RowBlocks) that gives long rows several waves, each with a contiguous share of the row's
-// stored entries; partial sums of one row meet in LDS and are added in a fixed order.  There
-// are no float atomics: every output element is produced by one lane in one order, so results
-// are bit-reproducible from run to run.
+// per column, batch contiguous).  Where a gather fills the whole wave (wide batches) row
+// pointers, column indices and weights are wave-uniform and travel through the scalar path;
+// for narrow batches and column tiles several stored entries share one gather instruction, their
+// indices loaded one per lane and handed round with ds_bpermute.  Rows are handed to work-groups
+// by a static partition (RowBlocks) that gives long rows several waves, each with a contiguous
+// share of the row's stored entries; partial sums of one row meet in LDS and are added in a
+// fixed order.  There are no float atomics: every output element is produced by one lane in one
+// order, so results are bit-reproducible from run to run.  (The exceptions to "along the batch":
+// spmv_kernel and head_kernel, whose lanes run across a row's entries, and the opt-in dense
+// route, an MFMA product.)
 #include "kernels.h"
 
 namespace nerva {
@@ -93,8 +97,7 @@ struct WaveTask {
 };
 // One 16-byte scalar load per wave: the partition table is spelled out per wave when the
 // pattern is bound, so nothing about the row has to be looked up before its entries are fetched.
-template <int GRAIN>
-__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, const int32_t *, int block)
+__device__ __forceinline__ WaveTask wave_task(const RowBlocks &b, int block)
 {
     const int4 d = b.waves[block * kWavesPerBlock + wave_in_block()];
     WaveTask t;
@@ -193,7 +196,7 @@ __device__ __forceinline__ void spmm_body(const SpmmArgs &a, const int block, co
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = wave_in_block();
-    const WaveTask task = wave_task<1>(a.blocks, a.indptr, block);
+    const WaveTask task = wave_task(a.blocks, block);
     const int col_base = col_tile * (kWave * VEC * NV);
 
     // Lanes whose columns lie beyond the batch re-read the tile's first columns and are never stored.
@@ -339,7 +342,7 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
     const int wv = wave_in_block();
     const int grp = lane / GS;
     const int lig = lane % GS;
-    const WaveTask task = wave_task<1>(a.blocks, a.indptr, block);
+    const WaveTask task = wave_task(a.blocks, block);
     const int col = col0 + lig * 4;
     const bool on = col < a.batch;
     const uint32_t off = static_cast<uint32_t>(on ? col : col0) * 4u;
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(kBlock) void spmv_kernel(const SpmmArgs a)
     __shared__ float red[kWavesPerBlock][NB];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = wave_in_block();
-    const WaveTask task = wave_task<1>(a.blocks, a.indptr, blockIdx.x);
+    const WaveTask task = wave_task(a.blocks, blockIdx.x);
     float acc[NB];
 #pragma unroll
     for (int c = 0; c < NB; ++c) acc[c] = 0.f;
@@ -736,7 +739,7 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
     constexpr int UI = NV >= 4 ? 2 : (NV == 2 ? 4 : 8);   // 32 registers of gathered data: two 16-wave work-groups fit a compute unit
     const int lane = threadIdx.x & (kWave - 1);
     mean_loss_task(a, block);
-    const WaveTask task = wave_task<NG>(a.blocks, a.indptr, block);
+    const WaveTask task = wave_task(a.blocks, block);
     if (task.row < 0) return;
     const int row = task.row;
     const int grp = lane / G;
@@ -934,7 +937,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     mean_loss_task(a, blockIdx.x);
-    const WaveTask task = wave_task<1>(a.blocks, a.indptr, blockIdx.x);
+    const WaveTask task = wave_task(a.blocks, blockIdx.x);
     if (task.row < 0) return;
     const int row = task.row;
     const float *zr = a.dZ + static_cast<int64_t>(row) * a.lddz;
