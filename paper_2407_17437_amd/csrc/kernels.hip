@@ -432,7 +432,7 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
 // the rows of a set have nearly the same length; a group whose row is exhausted repeats that
 // row's first entry with weight 0.
 template <int GS, bool XMASK>
-__device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int block, const int col0)
+__device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int block, const int col0, const int n_pack_blocks)
 {
     constexpr int NE = kWave / GS;
     const int lane = threadIdx.x & (kWave - 1);
@@ -448,9 +448,14 @@ __device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int bl
     const gmem_ptr Mg = as_gmem(a.XM);
     const int n_sets = (a.blocks.n_short + NE - 1) / NE;
     const int src0 = grp * GS * 4;  // byte address of the group's first lane
-    const int first_set = (block * kWavesPerBlock + wv) * kPackSets;
+    // The sets are sorted by length, so they are dealt to the waves round-robin: wave k of the
+    // launch's n_waves takes sets k, k + n_waves, k + 2 n_waves, ... and every wave gets its share
+    // of long and of short rows (consecutive sets per wave left the first work-groups 1.4x the work
+    // of the average on rows of 40..85 entries, and a launch is one round of work-groups).
+    const int n_waves = n_pack_blocks * kWavesPerBlock;
+    const int first_set = block * kWavesPerBlock + wv;
     if (first_set >= n_sets) return;  // wave-uniform
-    const int last_set = min(first_set + kPackSets, n_sets) - 1;
+    const int last_set = first_set + ((n_sets - 1 - first_set) / n_waves) * n_waves;  // <= first_set + (kPackSets - 1) * n_waves
 
     // Entry base+lig of the group's row: column index and weight (0 past the row's end, where the
     // row's first entry is repeated; an empty row reads entry 0 of the matrix and is zeroed below).
@@ -469,10 +474,10 @@ __device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int bl
     int cur_j;
     float cur_w;
     fetch(d.y, d.z, 0, cur_j, cur_w);
-    for (int set = first_set; set <= last_set; ++set) {
+    for (int set = first_set; set <= last_set; set += n_waves) {
         const int row = d.x, s0 = d.y, len = d.z;
         const int maxlen = __builtin_amdgcn_readfirstlane(len);  // group 0 holds the set's longest row
-        const int4 dn = a.blocks.short_rows[min(set + 1, last_set) * NE + grp];
+        const int4 dn = a.blocks.short_rows[min(set + n_waves, last_set) * NE + grp];
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         int base = 0;
         do {
@@ -544,7 +549,7 @@ __global__ __launch_bounds__(kBlock) void spmm_packed_kernel(const SpmmArgs a, c
     }
     if (tile >= n_tiles) return;
     if (rb < n_pack_blocks) {
-        spmm_body_packed<GS, XMASK>(a, rb, tile * GS * 4);
+        spmm_body_packed<GS, XMASK>(a, rb, tile * GS * 4, n_pack_blocks);
     } else {
         SpmmArgs al = a;
         al.blocks.waves = a.blocks.long_waves;
