@@ -213,6 +213,11 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
         for (int32_t i = 0; i < rows; ++i)
             if (lg_of[i] == lg) P.row_order.push_back(i);
         const int32_t end = static_cast<int32_t>(P.row_order.size());
+        // longest first inside the class (ties in row order): the rows of a work-group are alike,
+        // and the work-groups that take longest start first
+        std::stable_sort(P.row_order.begin() + begin, P.row_order.begin() + end, [&](int32_t x, int32_t y) {
+            return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
+        });
         const int32_t per_block = kWavesPerBlock >> lg;
         for (int32_t f = begin; f < end; f += per_block) {
             const int32_t n_rows = end - f < per_block ? end - f : per_block;

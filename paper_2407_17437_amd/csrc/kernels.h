@@ -25,7 +25,7 @@ struct RowBlocks {
     int32_t n_huge_blocks;
     // Optional second partition, built for matrices with many short rows (n_short > 0): rows of
     // at most kPackMaxLen entries are listed longest first and served one row per lane group,
-    // several rows per wave (spmm_packed_kernel); the remaining rows keep a partition of their
+    // 64/GS rows per wave (spmm_packed_kernel); the remaining rows keep a partition of their
     // own, huge work-groups first exactly as in `waves` (same scratch slots, same huge_rows).
     const int4 *short_rows;    // [n_short rounded up to a multiple of 64] {row or -1, first entry, entries, 0}
     const int4 *long_waves;    // [n_long_blocks * kWavesPerBlock], records as in `waves`
@@ -39,7 +39,7 @@ constexpr int32_t kHotRows = 1024;
 constexpr int32_t kHugeFlag = 0x40000000;
 constexpr int32_t kPackMaxLen = 128;     // longest row served by the packed path
 constexpr int32_t kPackMinRows = 2048;   // fewer short rows than this: no packed path
-constexpr int32_t kPackSets = 4;         // row sets (64/GS rows each) per wave
+constexpr int32_t kPackSets = 1;         // row sets (64/GS rows each) per wave; measured on the wide MLP: 1 / 2 / 4 / 8 sets give 500 / 504 / 527 / 548 us per step
 
 // Y = epilogue( W * gather(X) ) for a CSR matrix W (rows x cols); also used on the CSC
 // mirror, where "rows" are W's columns.

@@ -426,11 +426,12 @@ __device__ __forceinline__ void spmm_body_grouped(const SpmmArgs &a, const int b
 }
 
 // Packed SpMM for short rows: each group of GS lanes owns one row, so a gather instruction
-// fetches one entry of each of 64/GS rows and no sum across groups or waves is needed; a wave
-// serves kPackSets sets of rows one after the other, which spreads its start-up (descriptor and
-// index fetches) over several rows.  The rows come from RowBlocks::short_rows, longest first, so
-// the rows of a set have nearly the same length; a group whose row is exhausted repeats that
-// row's first entry with weight 0.
+// fetches one entry of each of 64/GS rows and no sum across groups or waves is needed.  The rows
+// come from RowBlocks::short_rows, longest first, so the rows of a set have nearly the same
+// length; a group whose row is exhausted repeats that row's first entry with weight 0.  A wave
+// can serve kPackSets sets one after the other, fetching the next set's rows and indices one
+// step ahead; measured, one set per wave is best (more, shorter work-groups balance better than
+// the saved start-up is worth).
 template <int GS, bool XMASK>
 __device__ __forceinline__ void spmm_body_packed(const SpmmArgs &a, const int block, const int col0, const int n_pack_blocks)
 {
