@@ -1031,9 +1031,9 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
         }
         if (n > 1) {
             const SddmmArgs g1 = make_S(1), g0 = make_S(0);
-            if (can_pair(g1, g0)) {
+            if (can_pair(g0, g1)) {
                 Timed tm(mlp->prof, s, "sddmm_update+sddmm_update", 0);
-                HIP_TRY(launch_pair(g1, g0, s));
+                HIP_TRY(launch_pair(g0, g1, s));  // the larger layer's work-groups start first
             } else {
                 { Timed tm(mlp->prof, s, "sddmm_update", 1); HIP_TRY(launch_sddmm(g1, s)); }
                 { Timed tm(mlp->prof, s, "sddmm_update", 0); HIP_TRY(launch_sddmm(g0, s)); }
