@@ -79,7 +79,8 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz,
  * take is "huge": it is cut into several work-groups whose partial results a second kernel adds
  * in order.  Outputs (any array may be NULL to get only the counts):
  *   counts_host[4]            {ordinary rows, work-groups, huge rows, huge work-groups}
- *   row_order_host[rows]      ordinary row ids in serving order
+ *   row_order_host[rows]      ordinary row ids in serving order: by lg descending, inside one lg by
+ *                             stored entries descending, ties by row id
  *   blocks_host[4*nb]         per work-group, huge ones first:
  *                               ordinary {lg | rows served << 8, first position of row_order, 0, 0}
  *                               huge     {NERVA_HUGE_FLAG | share index, row, first entry, end entry}

@@ -123,6 +123,10 @@ def _check_plan(nb, indptr, rows):
                 assert -(-k // (1 << (lg - 1))) > target           # and no more waves than needed
         covered += n
     assert covered == len(order)
+    # inside one class the rows come longest first, ties in row order
+    lg_of_slot = np.concatenate([np.full(info >> 8, info & 0xFF) for info in blocks[n_huge_blocks:, 0].tolist()] or [np.zeros(0, int)])
+    key = list(zip((-lg_of_slot).tolist(), (-row_nnz[order]).tolist(), order.tolist()))
+    assert key == sorted(key)
     return order, blocks, huge, n_huge_blocks
 
 
