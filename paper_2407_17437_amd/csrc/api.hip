@@ -78,6 +78,9 @@ struct nerva_layer {
     bool dense_on = false;
     float *dense = nullptr, *dense_t = nullptr;
     int64_t dense_ld = 0, dense_t_ld = 0;
+    // owned, only for a matrix that stores every entry and has at most kFullMaxRows rows
+    float *full_scratch = nullptr;   // slice partials of the streaming product, (slices * rows, full_scratch_ld)
+    int64_t full_scratch_ld = 0;
     float *dense_scratch = nullptr;  // partial tiles of a K-split product: kDenseMaxSplits x max(rows, cols) x dense_scratch_ld
     int64_t dense_scratch_ld = 0;
 };
@@ -347,6 +350,7 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->dense);
     (void)hipFree(l->dense_t);
     (void)hipFree(l->dense_scratch);
+    (void)hipFree(l->full_scratch);
     (void)hipFree(l->perm);
     (void)hipFree(l->pos_t);
 }
@@ -560,6 +564,11 @@ static int build_structures(nerva_layer *l, hipStream_t s)
         l->scratch_ld = round_up(max_batch, 64);
         if (slots > 0) e = hipMalloc(&l->scratch, static_cast<size_t>(slots) * l->scratch_ld * 4);
     }
+    if (e == hipSuccess && rows <= kFullMaxRows && static_cast<int64_t>(nnz) == static_cast<int64_t>(rows) * cols) {
+        l->full_scratch_ld = round_up(max_batch, 64);
+        const int64_t slices = (cols + kFullSlice - 1) / kFullSlice;
+        e = hipMalloc(&l->full_scratch, static_cast<size_t>(slices) * rows * l->full_scratch_ld * 4);
+    }
     if (e == hipSuccess) e = launch_gather(l->values_t, values, l->perm, nnz, s);
     if (e == hipSuccess && l->dense_on) e = build_dense_copies(l, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
@@ -678,6 +687,7 @@ int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
     a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
     a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
+    a.full_scratch = layer->full_scratch; a.full_scratch_ld = layer->full_scratch_ld;
     HIP_TRY(launch_spmm(a, as_stream(stream)));
     return NERVA_OK;
 }
@@ -902,6 +912,7 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
         a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
+        a.full_scratch = ly->full_scratch; a.full_scratch_ld = ly->full_scratch_ld;
         if (use_dense(ly, batch)) {
             Timed tm(mlp->prof, s, "dense_forward", static_cast<int>(l));
             HIP_TRY(dense_forward(ly, in, ldin, A, L.ld, batch, s));

@@ -64,7 +64,15 @@ struct SpmmArgs {
     int32_t nnz;             // length of indices/values
     float *scratch;          // partial rows of huge-row work-groups, (n_huge_blocks, scratch_ld)
     int64_t scratch_ld;
+    // Only for a matrix that stores every entry and has at most kFullMaxRows rows (a saturated
+    // output layer): values[] is then the row-major dense matrix, and the product streams the
+    // operand once for all rows instead of gathering it once per row.  Partial results of the
+    // kFullSlice-column slices of W: full_scratch[(slice * rows + row) * full_scratch_ld + column].
+    float *full_scratch;     // or nullptr: the matrix is not full, or has too many rows
+    int64_t full_scratch_ld;
 };
+constexpr int32_t kFullMaxRows = 16;
+constexpr int32_t kFullSlice = 128;   // columns of W (rows of the operand) per work-group
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s);
 
 // g[p] = <dZ[row(p),:], X[indices[p],:]>, db[i] = sum_c dZ[i,c]; optionally followed, inside

@@ -648,6 +648,92 @@ __global__ __launch_bounds__(kBlock) void spmv_kernel(const SpmmArgs a)
     a.Y[static_cast<int64_t>(task.row) * a.ldy + lane] = y;
 }
 
+// Product with a FULL matrix of few rows (every entry stored, rows <= kFullMaxRows): values[] is
+// the row-major dense matrix, so instead of gathering the operand once per row the kernel streams
+// it once for all rows.  A work-group of 4 waves owns kFullSlice consecutive operand rows and 256
+// batch columns (4 per lane); wave w walks the slice's operand rows w*32 .. w*32+31, eight 16-byte
+// loads in flight, weights through uniform loads, one accumulator per matrix row; the waves'
+// accumulators meet in LDS and are added in wave order.  The slice's partial result goes to
+// full_scratch; full_rows_finish_kernel adds the slices in order and applies the epilogue.
+constexpr int kFullWaves = 4;  // 4 waves x 16 rows x 1 KiB of LDS at most: 64 KiB
+__global__ __launch_bounds__(kFullWaves * kWave) void full_rows_kernel(const SpmmArgs a)
+{
+    extern __shared__ float4 full_red[];  // [kFullWaves][rows][kWave]
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int K = a.x_rows;
+    const int slice = blockIdx.x;
+    const int col = (blockIdx.y * kWave + lane) * 4;
+    const bool on = col < a.batch;
+    const int64_t xoff = on ? col : 0;
+    constexpr int KW = kFullSlice / kFullWaves;  // operand rows per wave: all requested before the first use
+    static_assert(KW == 32, "one weight per lane of a half wave");
+    const int k_begin = slice * kFullSlice + wv * KW;
+    float4 acc[kFullMaxRows];
+    float4 x[KW];
+#pragma unroll
+    for (int u = 0; u < KW; ++u) {
+        const int64_t k = k_begin + u < K ? k_begin + u : K - 1;  // rows past the end are re-read and get weight 0
+        x[u] = ld4(a.X + k * a.ldx + xoff);
+    }
+    // lane u (and u + 32) holds row r's weight of operand row k_begin + u
+    float wrow[kFullMaxRows];
+    const int kl = k_begin + (lane & (KW - 1));
+#pragma unroll
+    for (int r = 0; r < kFullMaxRows; ++r)
+        wrow[r] = (r < a.rows && kl < K) ? a.values[static_cast<int64_t>(r) * K + kl] : 0.f;
+#pragma unroll
+    for (int r = 0; r < kFullMaxRows; ++r) {
+        acc[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < a.rows) {  // uniform
+#pragma unroll
+            for (int u = 0; u < KW; ++u) {
+                const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wrow[r]), u));
+                acc[r].x = fmaf(w, x[u].x, acc[r].x);
+                acc[r].y = fmaf(w, x[u].y, acc[r].y);
+                acc[r].z = fmaf(w, x[u].z, acc[r].z);
+                acc[r].w = fmaf(w, x[u].w, acc[r].w);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kFullMaxRows; ++r)
+        if (r < a.rows) full_red[(wv * a.rows + r) * kWave + lane] = acc[r];
+    __syncthreads();
+    if (!on) return;
+    for (int r = wv; r < a.rows; r += kFullWaves) {
+        float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int w = 0; w < kFullWaves; ++w) {
+            const float4 p = full_red[(w * a.rows + r) * kWave + lane];
+            y.x += p.x; y.y += p.y; y.z += p.z; y.w += p.w;
+        }
+        st4(a.full_scratch + (static_cast<int64_t>(slice) * a.rows + r) * a.full_scratch_ld + col, y);
+    }
+}
+
+__global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmArgs a, const int n_slices)
+{
+    const int r = blockIdx.x;
+    const int c = blockIdx.y * kEwBlock + threadIdx.x;
+    if (c >= a.batch) return;
+    const float *p = a.full_scratch + static_cast<int64_t>(r) * a.full_scratch_ld + c;
+    const int64_t step = static_cast<int64_t>(a.rows) * a.full_scratch_ld;
+    float y = 0.f;
+    int q = 0;
+    for (; q + 8 <= n_slices; q += 8) {  // eight loads in flight, added in slice order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(q + u) * step];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) y += v[u];
+    }
+    for (; q < n_slices; ++q) y += p[q * step];
+    y += a.bias ? a.bias[r] : 0.f;
+    if (a.relu) y = y > 0.f ? y : 0.f;
+    if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(r) * a.ldym + c]);
+    a.Y[static_cast<int64_t>(r) * a.ldy + c] = y;
+}
+
 // Second pass for huge rows: adds the partial rows of a row's work-groups in share order, then
 // bias, ReLU and the optional output mask.  One thread per column.
 __global__ __launch_bounds__(256) void spmm_finish_kernel(const SpmmArgs a)
@@ -1587,6 +1673,14 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
             hipLaunchKernelGGL(spmv_kernel<4>, dim3(a.blocks.n_blocks), dim3(kBlock), 0, s, a);
         if (a.blocks.n_huge_rows > 0)
             hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, 1), dim3(256), 0, s, a);
+        return hipGetLastError();
+    }
+    if (a.full_scratch && !a.XM && a.batch >= 64 && a.rows <= kFullMaxRows && spmm_vec_ok(a) &&
+        a.full_scratch_ld % 4 == 0) {
+        const int n_slices = (a.x_rows + kFullSlice - 1) / kFullSlice;
+        hipLaunchKernelGGL(full_rows_kernel, dim3(n_slices, (a.batch + 255) / 256), dim3(kFullWaves * kWave),
+                           static_cast<size_t>(kFullWaves) * a.rows * kWave * sizeof(float4), s, a);
+        hipLaunchKernelGGL(full_rows_finish_kernel, dim3(a.rows, (a.batch + kEwBlock - 1) / kEwBlock), dim3(kEwBlock), 0, s, a, n_slices);
         return hipGetLastError();
     }
     if (spmm_vec_ok(a)) {

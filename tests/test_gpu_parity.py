@@ -97,6 +97,10 @@ SHAPES = [
     (2400, 1000, 0.125, 64, None),   # rows around the 128-entry limit: packed and ordinary rows in one grid
     (2200, 3000, 0.005, 300, None),  # operand beyond an L2: packed rows inside column tiles
     (300, 2500, 0.02, 100, None),    # short rows only in the mirror
+    # every entry stored and few rows: the operand is streamed once for all rows
+    (16, 700, 1.0, 300, None),       # 16 rows, ragged slices and columns
+    (3, 1000, 1.0, 64, None),
+    (10, 8192, 1.0, 256, None),      # the wide MLP's saturated output layer, a quarter of its batch
     # operands beyond an L2: column tiles in the products and per-tile partial sums in the SDDMM
     (300, 6000, 0.02, 200, None),    # 64-column tiles, ragged last tile
     (320, 12000, 0.02, 360, None),   # 32-column tiles (240 entries per row, a 17 MB operand)
