@@ -117,6 +117,28 @@ enum { NERVA_PACK_MAX_LEN = 128, NERVA_PACK_MIN_ROWS = 2048 };
 int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *short_rows_host,
                                int32_t *long_waves_host, int32_t *counts_host);
 
+/* The static part of the staged product (HOST arrays, needs no GPU).  For batches of at least
+ * NERVA_STAGE_MIN_BATCH columns and matrices with several stored entries per column and row
+ * range, Y = S X (and Y = S^T X on the mirror) copies NERVA_STAGE_ROWS rows of X at a time into a
+ * compute unit's local memory and serves from there every stored entry whose column falls into
+ * that block of rows, while the results of the work-group's rows wait in registers.  The rows
+ * are cut into ranges of consecutive rows, at most NERVA_STAGE_RANGE_ROWS each and of about equal
+ * work, one work-group per (range, tile of NERVA_STAGE_COLS batch columns); inside a range the
+ * rows are listed by stored entries descending (ties in row order), four consecutive list slots
+ * being served side by side; every row is cut into segments at the multiples of
+ * NERVA_STAGE_ROWS in its column indices.  Outputs (arrays may be NULL to get only the counts):
+ *   counts_host[2]      {ranges, column blocks nb}; both 0 when no product of this matrix at up
+ *                       to max_batch columns would be staged
+ *   slot_rows_host[ranges * NERVA_STAGE_RANGE_ROWS]
+ *                       row in each slot of each range, -1 in unused slots
+ *   ends_host[ranges * (nb + 1) * NERVA_STAGE_RANGE_ROWS]
+ *                       [(range * (nb + 1) + b) * NERVA_STAGE_RANGE_ROWS + slot] = position of the
+ *                       slot's first stored entry with column >= b * NERVA_STAGE_ROWS (b = nb: one
+ *                       past the row's last entry); 0 throughout for unused slots */
+enum { NERVA_STAGE_ROWS = 512, NERVA_STAGE_COLS = 64, NERVA_STAGE_MIN_BATCH = 128, NERVA_STAGE_RANGE_ROWS = 512 };
+int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_host, const int32_t *indices_host,
+                           int32_t max_batch, int32_t *slot_rows_host, int32_t *ends_host, int32_t *counts_host);
+
 /* ---- layer -------------------------------------------------------------------------
  * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays
  * (which must outlive the layer) and builds, once, what a static pattern allows to be

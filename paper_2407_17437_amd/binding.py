@@ -21,13 +21,14 @@ NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
 NERVA_PACK_MAX_LEN, NERVA_PACK_MIN_ROWS = 128, 2048
+NERVA_STAGE_ROWS, NERVA_STAGE_COLS, NERVA_STAGE_MIN_BATCH, NERVA_STAGE_RANGE_ROWS = 512, 64, 128, 512
 NERVA_PARTITION_BALANCED, NERVA_PARTITION_ROW_SPLIT = 0, 1
 NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV, NERVA_MLP_SEPARATE_HEAD = 0, 1, 2, 4
 NERVA_WAVES_PER_BLOCK = 16
 NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
-    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_set_partition_mode",
+    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_plan_staged_host", "nerva_set_partition_mode",
     "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_enable_dense", "sparse_linear_sync_values", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
@@ -55,6 +56,7 @@ def _load() -> ctypes.CDLL:
         "nerva_validate_csr_host": (ctypes.c_int, [i32, i32, i64, vp, vp]),
         "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp, vp]),
         "nerva_plan_short_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp]),
+        "nerva_plan_staged_host": (ctypes.c_int, [i32, i32, vp, vp, i32, vp, vp, vp]),
         "nerva_set_partition_mode": (ctypes.c_int, [i32]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
@@ -159,6 +161,22 @@ def nerva_plan_short_rows_host(rows: int, indptr):
     waves = np.empty((max(1, counts[1]), NERVA_WAVES_PER_BLOCK, 4), dtype=np.int32)
     _check(lib.nerva_plan_short_rows_host(rows, indptr.ctypes.data, short.ctypes.data, waves.ctypes.data, counts.ctypes.data))
     return short[:ns64], int(counts[0]), waves[:counts[1]], int(counts[2])
+
+
+def nerva_plan_staged_host(rows: int, cols: int, indptr, indices, max_batch: int):
+    """Returns (slot_rows[ranges, 512], ends[ranges, blocks + 1, 512]) as numpy int32 arrays; ranges == 0: not staged."""
+    import numpy as np
+    indptr = np.ascontiguousarray(indptr, dtype=np.int32)
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    counts = np.zeros(2, dtype=np.int32)
+    _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch, None, None, counts.ctypes.data))
+    ranges, blocks = int(counts[0]), int(counts[1])
+    slot_rows = np.zeros((ranges, NERVA_STAGE_RANGE_ROWS), dtype=np.int32)
+    ends = np.zeros((ranges, blocks + 1, NERVA_STAGE_RANGE_ROWS), dtype=np.int32)
+    if ranges:
+        _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch,
+                                          slot_rows.ctypes.data, ends.ctypes.data, counts.ctypes.data))
+    return slot_rows, ends
 
 
 # ---- entry points, same names as the C ABI ------------------------------------------------

@@ -301,10 +301,93 @@ float hot_row_share(int32_t other_rows, const int32_t *other_indptr)
     return static_cast<float>(static_cast<double>(top) / static_cast<double>(nnz));
 }
 
-hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t other_rows, const int32_t *other_indptr_host,
+// Row ranges, slot order and segment bounds of the staged product (RowBlocks::staged_*) for a
+// matrix whose products run at up to max_batch columns; empty when that product would never be chosen.
+struct StagedPlan {
+    std::vector<int32_t> rows;    // [ranges * kStageRangeRows]
+    std::vector<int32_t> ends;    // [ranges * (cblocks + 1) * kStageRangeRows]
+    std::vector<int32_t> groups;  // [ranges]
+    int32_t ranges = 0, cblocks = 0;
+};
+
+StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const int32_t *indices, int32_t max_batch)
+{
+    StagedPlan H;
+    const int64_t nnz = indptr[rows];
+    if (g_partition_mode.load() != NERVA_PARTITION_BALANCED || max_batch < kStageMinBatch || nnz == 0) return H;
+    const int32_t n_tiles = (max_batch + kStageCols - 1) / kStageCols;
+    int32_t want = kStageTargetGroups / n_tiles;
+    if (want > rows / 64) want = rows / 64;
+    // (ranges cut by cost are not equally long: leave an eighth of the slots as slack)
+    const int32_t at_least = (rows + kStageRangeRows * 7 / 8 - 1) / (kStageRangeRows * 7 / 8);
+    if (want < at_least) want = at_least;
+    // one work-group fits a compute unit at a time: fill the last round of the grid as well
+    if (static_cast<int64_t>(want) * n_tiles > kStageTargetGroups) {
+        const int64_t rounds = (static_cast<int64_t>(want) * n_tiles + kStageTargetGroups - 1) / kStageTargetGroups;
+        want = static_cast<int32_t>(rounds * kStageTargetGroups / n_tiles);
+    }
+    if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * want * cols) return H;
+    const int32_t cblocks = (cols + kStageRows - 1) / kStageRows;
+    if ((static_cast<int64_t>(want) + at_least) * (cblocks + 1) * kStageRangeRows > (1ll << 28)) return H;  // tables beyond 1 GiB
+    // ranges of about equal cost: a stored entry costs one gather, a segment about two more
+    auto cost = [&](int32_t r) {
+        const int64_t len = indptr[r + 1] - indptr[r];
+        return len + 2 * (len < cblocks ? len : cblocks) + 1;
+    };
+    int64_t total = 0;
+    for (int32_t r = 0; r < rows; ++r) total += cost(r);
+    std::vector<int32_t> first_row{0};
+    {
+        int32_t range = 0, in_range = 0;
+        int64_t done = 0;
+        for (int32_t r = 0; r < rows; ++r) {
+            const bool next = range + 1 < want && done * want >= total * (range + 1);
+            if ((next || in_range == kStageRangeRows) && in_range > 0) {
+                first_row.push_back(r);
+                in_range = 0;
+            }
+            if (next) ++range;
+            done += cost(r);
+            ++in_range;
+        }
+        first_row.push_back(rows);
+    }
+    const int32_t ranges = static_cast<int32_t>(first_row.size()) - 1;
+    H.ranges = ranges;
+    H.cblocks = cblocks;
+    H.rows.assign(static_cast<size_t>(ranges) * kStageRangeRows, -1);
+    H.ends.assign(static_cast<size_t>(ranges) * (cblocks + 1) * kStageRangeRows, 0);
+    H.groups.resize(ranges);
+    std::vector<int32_t> order;
+    for (int32_t q = 0; q < ranges; ++q) {
+        const int32_t r0 = first_row[q], n = first_row[q + 1] - r0;
+        H.groups[q] = (n + 63) / 64;
+        order.resize(n);
+        for (int32_t i = 0; i < n; ++i) order[i] = r0 + i;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
+        });
+        int32_t *e = H.ends.data() + static_cast<size_t>(q) * (cblocks + 1) * kStageRangeRows;
+        for (int32_t slot = 0; slot < n; ++slot) {
+            const int32_t r = order[slot];
+            H.rows[static_cast<size_t>(q) * kStageRangeRows + slot] = r;
+            const int32_t *lo = indices + indptr[r], *hi = indices + indptr[r + 1];
+            e[slot] = indptr[r];
+            for (int32_t b = 1; b <= cblocks; ++b) {
+                lo = std::lower_bound(lo, hi, b * kStageRows);
+                e[static_cast<size_t>(b) * kStageRangeRows + slot] = static_cast<int32_t>(lo - indices);
+            }
+        }
+    }
+    return H;
+}
+
+hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *indices_host, int32_t max_batch,
+                       int32_t other_rows, const int32_t *other_indptr_host,
                        int32_t **mem, RowBlocks *plan, hipStream_t s, std::vector<int32_t> &staging)
 {
     const RowPlan P = plan_rows(rows, indptr_host);
+    const StagedPlan H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch);
     int32_t n_short = 0;
     const std::vector<int32_t> short_rows = short_row_table(rows, indptr_host, &n_short);
     RowPlan Q;
@@ -313,12 +396,17 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t other_r
     staging = P.blocks;
     staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
     staging.insert(staging.end(), P.waves.begin(), P.waves.end());
+    const size_t staged_at = staging.size();
+    staging.insert(staging.end(), H.rows.begin(), H.rows.end());  // (multiples of kStageRangeRows: what follows stays 16-byte aligned)
+    staging.insert(staging.end(), H.ends.begin(), H.ends.end());
     const size_t long_at = staging.size();
     staging.insert(staging.end(), Q.waves.begin(), Q.waves.end());
     const size_t short_at = staging.size();
     staging.insert(staging.end(), short_rows.begin(), short_rows.end());
     const size_t order_at = staging.size();
     staging.insert(staging.end(), P.row_order.begin(), P.row_order.end());
+    const size_t groups_at = staging.size();
+    staging.insert(staging.end(), H.groups.begin(), H.groups.end());
     if (staging.empty()) staging.push_back(0);
     hipError_t e = hipMalloc(mem, staging.size() * 4);
     if (e != hipSuccess) return e;
@@ -335,6 +423,14 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, int32_t other_r
     plan->n_blocks = P.n_blocks();
     plan->n_huge_rows = P.n_huge_rows();
     plan->n_huge_blocks = P.n_huge_blocks;
+    plan->staged_rows = H.ranges ? *mem + staged_at : nullptr;
+    plan->staged_ends = H.ranges ? *mem + staged_at + H.rows.size() : nullptr;
+    plan->staged_groups = H.ranges ? *mem + groups_at : nullptr;
+    plan->staged_ranges = H.ranges;
+    plan->staged_cblocks = H.cblocks;
+    plan->staged_longest_row = 0;
+    for (int32_t r = 0; r < rows; ++r)
+        if (indptr_host[r + 1] - indptr_host[r] > plan->staged_longest_row) plan->staged_longest_row = indptr_host[r + 1] - indptr_host[r];
     return e;
 }
 
@@ -452,6 +548,21 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
     return NERVA_OK;
 }
 
+int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_host, const int32_t *indices_host,
+                           int32_t max_batch, int32_t *slot_rows_host, int32_t *ends_host, int32_t *counts_host)
+{
+    if (rows <= 0 || cols <= 0 || !indptr_host || !counts_host || (indptr_host[rows] > 0 && !indices_host))
+        return fail(NERVA_ERR_ARGUMENT, "bad argument");
+    static_assert(NERVA_STAGE_ROWS == kStageRows && NERVA_STAGE_COLS == kStageCols && NERVA_STAGE_MIN_BATCH == kStageMinBatch &&
+                  NERVA_STAGE_RANGE_ROWS == kStageRangeRows, "header and kernels disagree");
+    const StagedPlan H = plan_staged(rows, cols, indptr_host, indices_host, max_batch);
+    counts_host[0] = H.ranges;
+    counts_host[1] = H.cblocks;
+    if (slot_rows_host && !H.rows.empty()) memcpy(slot_rows_host, H.rows.data(), H.rows.size() * 4);
+    if (ends_host && !H.ends.empty()) memcpy(ends_host, H.ends.data(), H.ends.size() * 4);
+    return NERVA_OK;
+}
+
 // Dense copies for the dense route: allocated zero, then filled from the stored entries.
 static hipError_t build_dense_copies(nerva_layer *l, hipStream_t s)
 {
@@ -543,8 +654,8 @@ static int build_structures(nerva_layer *l, hipStream_t s)
     if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->perm, h_perm.data(), nb, hipMemcpyHostToDevice, s);
     if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->pos_t, h_pos_t.data(), nb, hipMemcpyHostToDevice, s);
     std::vector<int32_t> stage_a, stage_b;
-    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), cols, h_indptr_t.data(), &l->plan_mem, &l->plan, s, stage_a);
-    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), rows, h_indptr.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
+    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), h_indices.data(), max_batch, cols, h_indptr_t.data(), &l->plan_mem, &l->plan, s, stage_a);
+    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), h_indices_t.data(), max_batch, rows, h_indptr.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
     if (e == hipSuccess) {
         // room for the column-tiled SDDMM at max_batch columns, if that batch would be tiled
         const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false);

@@ -34,7 +34,29 @@ struct RowBlocks {
     // Share of the stored entries whose gathered operand row is one of the kHotRows most
     // referenced ones: when it is large the gathers hit in cache without any column tiling.
     float hot_share;
+    // Optional third form, for the staged product (spmm_staged_kernel; staged_rows != nullptr).
+    // The rows are cut into staged_ranges ranges of at most kStageRangeRows rows and about equal
+    // work; inside a range the rows are listed longest first (slot 0, 1, ...; unused slots hold
+    // -1).  Every row is cut into segments at the multiples of kStageRows in its column indices:
+    // staged_ends[(range * (staged_cblocks + 1) + b) * kStageRangeRows + slot] is the position of
+    // the slot's first stored entry with column >= b * kStageRows (b = 0: the row's first entry,
+    // b = staged_cblocks: one past its last; unused slots: 0 throughout).
+    const int32_t *staged_rows;    // [staged_ranges * kStageRangeRows]
+    const int32_t *staged_ends;
+    const int32_t *staged_groups;  // [staged_ranges] rows of the range / 64, rounded up
+    int32_t staged_ranges;
+    int32_t staged_cblocks;
+    int32_t staged_longest_row;    // stored entries of the longest row
 };
+constexpr int32_t kStageRows = 512;      // operand rows held in LDS at a time
+constexpr int32_t kStageCols = 64;       // columns of the operand (examples) per work-group
+constexpr int32_t kStageJ = 8;           // rows per row of 16 lanes
+constexpr int32_t kStageRangeRows = 512; // rows per work-group: 16 waves x 4 lane rows x kStageJ
+constexpr int32_t kStageMinBatch = 128;  // narrower batches never take the staged product
+constexpr int32_t kStageTargetGroups = 256;  // work-groups wanted at max_batch (one per compute unit)
+constexpr float kStageMinReuse = 2.f;    // stored entries per staged operand row and work-group, at least
+constexpr int32_t kStageLongSegment = 16;  // mean entries per segment from which staging pays whatever the operand's size
+constexpr int64_t kStageBigOperand = 48ll << 20;  // operand bytes no set of L2s holds: staging pays for short segments too
 constexpr int32_t kHotRows = 1024;
 constexpr int32_t kHugeFlag = 0x40000000;
 constexpr int32_t kPackMaxLen = 128;     // longest row served by the packed path

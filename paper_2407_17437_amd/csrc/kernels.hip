@@ -14,6 +14,8 @@
 // route, an MFMA product.)
 #include "kernels.h"
 
+#include <utility>
+
 namespace nerva {
 namespace {
 
@@ -732,6 +734,250 @@ __global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmAr
     if (a.relu) y = y > 0.f ? y : 0.f;
     if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(r) * a.ldym + c]);
     a.Y[static_cast<int64_t>(r) * a.ldy + c] = y;
+}
+
+// ---- staged product ----------------------------------------------------------------------
+// For wide batches and matrices with many entries per operand row the gathers are served from
+// LDS instead of the L2, and the results stay in registers until they are complete.  A
+// work-group of 16 waves owns a range of at most kStageRangeRows rows and kStageCols columns of
+// the batch; a row of 16 lanes owns up to kStageJ of those rows, a float4 of the batch per lane
+// and row.  The work-group walks the column blocks of the matrix in order: it copies the
+// block's kStageRows operand rows (128 KiB) into LDS, then every lane row serves, out of that
+// copy, the segment (row, block) of each of its rows.  A segment's (column, weight) pairs are
+// loaded one per lane, a block ahead, and reach the other lanes of the row through DPP row
+// broadcasts, so the only LDS traffic is the gather itself.  Bias, ReLU and the output mask are
+// applied when the rows are stored, once, after the last block.  Every output element is summed
+// by one lane in one order.
+constexpr int kStageWaves = kWavesPerBlock;
+static_assert(kStageRangeRows == kStageWaves * 4 * kStageJ && kStageJ <= 16, "a lane row owns kStageJ rows of the range");
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+
+// lane i of every row of 16 lanes receives the value of the row's lane I
+template <int I>
+__device__ __forceinline__ int row_lane(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x150 + I, 0xF, 0xF, false); }
+// lane i of every row of 16 lanes receives the value of the row's lane (i + K) % 16
+template <int K>
+__device__ __forceinline__ int row_rotate_down(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x120 + (16 - K), 0xF, 0xF, false); }
+
+template <int I>
+__device__ __forceinline__ void staged_step(const char *lds, int off, float w, float4 &acc)
+{
+    const int o = row_lane<I>(off);
+    const float wi = __builtin_bit_cast(float, row_lane<I>(__builtin_bit_cast(int, w)));
+    const float4 x = *reinterpret_cast<const float4 *>(lds + o);
+    acc.x = fmaf(wi, x.x, acc.x);
+    acc.y = fmaf(wi, x.y, acc.y);
+    acc.z = fmaf(wi, x.z, acc.z);
+    acc.w = fmaf(wi, x.w, acc.w);
+}
+// the first N entries of every lane row, in entry order; afterwards entry N sits in lane 0
+template <int N>
+__device__ __forceinline__ void staged_pass(const char *lds, int &off, float &w, float4 &acc)
+{
+    staged_step<0>(lds, off, w, acc);
+    if constexpr (N > 1) staged_step<1>(lds, off, w, acc);
+    if constexpr (N > 2) { staged_step<2>(lds, off, w, acc); staged_step<3>(lds, off, w, acc); }
+    if constexpr (N > 4) {
+        staged_step<4>(lds, off, w, acc); staged_step<5>(lds, off, w, acc);
+        staged_step<6>(lds, off, w, acc); staged_step<7>(lds, off, w, acc);
+    }
+    if constexpr (N > 8) {
+        staged_step<8>(lds, off, w, acc); staged_step<9>(lds, off, w, acc);
+        staged_step<10>(lds, off, w, acc); staged_step<11>(lds, off, w, acc);
+        staged_step<12>(lds, off, w, acc); staged_step<13>(lds, off, w, acc);
+        staged_step<14>(lds, off, w, acc); staged_step<15>(lds, off, w, acc);
+    }
+    if constexpr (N < 16) {
+        off = row_rotate_down<N>(off);
+        w = __builtin_bit_cast(float, row_rotate_down<N>(__builtin_bit_cast(int, w)));
+    }
+}
+
+// One segment per lane row: entries [p0, p0 + len) of one of the lane row's rows, the first 16
+// of them already in (off, w) as LDS byte offset and weight; adds the products to acc.
+__device__ __forceinline__ void staged_segment(const SpmmArgs &a, const char *lds, int cb0, int lig, int p0, int len,
+                                               int off, float w, float4 &acc)
+{
+    // the longest of the four segments sets the number of steps; shorter ones ride along with weight 0
+    const int l01 = max(__builtin_amdgcn_readlane(len, 0), __builtin_amdgcn_readlane(len, 16));
+    const int l23 = max(__builtin_amdgcn_readlane(len, 32), __builtin_amdgcn_readlane(len, 48));
+    const int longest = max(l01, l23);
+    auto passes = [&](int n) {
+        if (n >= 16) {
+            staged_pass<16>(lds, off, w, acc);
+        } else {
+            if (n & 8) staged_pass<8>(lds, off, w, acc);
+            if (n & 4) staged_pass<4>(lds, off, w, acc);
+            if (n & 2) staged_pass<2>(lds, off, w, acc);
+            if (n & 1) staged_pass<1>(lds, off, w, acc);
+        }
+    };
+    if (longest <= 16) {
+        // no load in this path, hence no wait: whatever the kernel has in flight stays in flight
+        passes(longest);
+        return;
+    }
+    // long segments: kStageDepth chunks of 16 entries are served while the next kStageDepth travel
+    constexpr int kStageDepth = 2;
+    int o[kStageDepth], o2[kStageDepth];
+    float ww[kStageDepth], w2[kStageDepth];
+    auto load_chunk = [&](int first, int &oo, float &wo) {
+        oo = 0;
+        wo = 0.f;
+        if (first < longest) {  // uniform
+            const int e = first + lig;
+            if (e < len) {
+                oo = (a.indices[p0 + e] - cb0) * (kStageCols * 4);
+                wo = a.values[p0 + e];
+            }
+        }
+    };
+    o[0] = off;
+    ww[0] = w;
+#pragma unroll
+    for (int k = 1; k < kStageDepth; ++k) load_chunk(16 * k, o[k], ww[k]);
+    for (int c = 0; c < longest; c += 16 * kStageDepth) {
+#pragma unroll
+        for (int k = 0; k < kStageDepth; ++k) load_chunk(c + 16 * (kStageDepth + k), o2[k], w2[k]);
+#pragma unroll
+        for (int k = 0; k < kStageDepth; ++k) {
+            const int n = longest - c - 16 * k;
+            if (n > 0) {
+                off = o[k];
+                w = ww[k];
+                passes(n);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kStageDepth; ++k) {
+            o[k] = o2[k];
+            ww[k] = w2[k];
+        }
+    }
+}
+
+// Work-group barrier that orders LDS accesses only: global loads issued before it stay in flight
+// across it (the staged kernel has no global data that one wave writes and another reads).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <bool XMASK>
+__global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const SpmmArgs a, const int n_tiles)
+{
+    __shared__ float4 stage[kStageRows * kStageCols / 4];
+    // Work-groups of one column tile stage the same operand rows: where there are eight tiles or
+    // more, each of eight tiles gets an XCD (consecutive work-groups go to consecutive XCDs) and
+    // its L2 to itself; left-over tiles are dealt out plainly.
+    const int n_ranges = a.blocks.staged_ranges;
+    const int aligned = (n_tiles >> 3) * 8 * n_ranges;
+    int range, tile;
+    if (static_cast<int>(blockIdx.x) < aligned) {
+        const int slot = blockIdx.x >> 3;
+        range = slot % n_ranges;
+        tile = (slot / n_ranges) * 8 + (blockIdx.x & 7);
+    } else {
+        const int rest = blockIdx.x - aligned, left = n_tiles & 7;
+        tile = (n_tiles >> 3) * 8 + rest % left;
+        range = rest / left;
+    }
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int lrow = lane >> 4, lig = lane & 15;
+    const int col = tile * kStageCols + lig * 4;
+    const bool col_on = col < a.batch;
+    const char *lds = reinterpret_cast<const char *>(stage) + lig * 16;
+    const int n_cb = a.blocks.staged_cblocks;
+    // The lane row's J-th row sits in slot (J * 16 + wave) * 4 + lrow of the range; lane J of the
+    // lane row keeps that slot's row id and, block after block, its segment bounds.
+    const int my_slot = ((lig & (kStageJ - 1)) * kStageWaves + wv) * 4 + lrow;
+    const int my_row = a.blocks.staged_rows[range * kStageRangeRows + my_slot];
+    const int n_j = a.blocks.staged_groups[range];  // rows of the range / 64, rounded up
+    const int32_t *ends = a.blocks.staged_ends + static_cast<int64_t>(range) * (n_cb + 1) * kStageRangeRows + my_slot;
+    constexpr auto all_j = std::make_integer_sequence<int, kStageJ>{};
+    float4 acc[kStageJ];
+    static_for(all_j, [&](auto jc) { acc[decltype(jc)::value] = make_float4(0.f, 0.f, 0.f, 0.f); });
+    // first 16 entries of the segments of column block blk; e_lo, e_hi: the lane's bounds blk and blk + 1
+    auto first_chunks = [&](int blk, int e_lo, int e_hi, int (&off)[kStageJ], float (&w)[kStageJ]) {
+        static_for(all_j, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            off[j] = 0;
+            w[j] = 0.f;
+            if (j < n_j) {
+                const int p0 = row_lane<j>(e_lo);
+                if (lig < row_lane<j>(e_hi) - p0) {
+                    off[j] = (a.indices[p0 + lig] - blk * kStageRows) * (kStageCols * 4);
+                    w[j] = a.values[p0 + lig];
+                }
+            }
+        });
+    };
+    int e0 = ends[0], e1 = ends[kStageRangeRows];
+    int e2 = n_cb >= 2 ? ends[2 * kStageRangeRows] : e1;
+    int off_cur[kStageJ];
+    float w_cur[kStageJ];
+    first_chunks(0, e0, e1, off_cur, w_cur);
+    for (int b = 0; b < n_cb; ++b) {
+        const int cb0 = b * kStageRows;
+        lds_barrier();  // the previous block's gathers are done
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            constexpr int kHalf = kStageRows / 128;
+            float4 v[kHalf];
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) {
+                const int k = cb0 + (h * kHalf + i) * 64 + static_cast<int>(threadIdx.x >> 4);
+                v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < a.x_rows && col_on) {
+                    v[i] = ld4(a.X + static_cast<int64_t>(k) * a.ldx + col);
+                    if constexpr (XMASK) v[i] = keep_where_positive(v[i], ld4(a.XM + static_cast<int64_t>(k) * a.ldxm + col));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) stage[((h * kHalf + i) * 64 + (threadIdx.x >> 4)) * 16 + lig] = v[i];
+        }
+        // the next block's first chunks travel while this block is served
+        int off_next[kStageJ];
+        float w_next[kStageJ];
+        int e3 = e2;
+        if (b + 1 < n_cb) {
+            first_chunks(b + 1, e1, e2, off_next, w_next);
+            if (b + 3 <= n_cb) e3 = ends[(b + 3) * kStageRangeRows];
+        } else {
+            static_for(all_j, [&](auto jc) { off_next[decltype(jc)::value] = 0; w_next[decltype(jc)::value] = 0.f; });
+        }
+        lds_barrier();
+        static_for(all_j, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            if (j < n_j) {
+                const int p0 = row_lane<j>(e0);
+                staged_segment(a, lds, cb0, lig, p0, row_lane<j>(e1) - p0, off_cur[j], w_cur[j], acc[j]);
+            }
+        });
+        static_for(all_j, [&](auto jc) { off_cur[decltype(jc)::value] = off_next[decltype(jc)::value]; w_cur[decltype(jc)::value] = w_next[decltype(jc)::value]; });
+        e0 = e1;
+        e1 = e2;
+        e2 = e3;
+    }
+    static_for(all_j, [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const int row = row_lane<j>(my_row);
+        if (j < n_j && row >= 0 && col_on) {
+            const float bb = a.bias ? a.bias[row] : 0.f;
+            float4 r = make_float4(acc[j].x + bb, acc[j].y + bb, acc[j].z + bb, acc[j].w + bb);
+            if (a.relu) r = make_float4(r.x > 0.f ? r.x : 0.f, r.y > 0.f ? r.y : 0.f, r.z > 0.f ? r.z : 0.f, r.w > 0.f ? r.w : 0.f);
+            if (a.YM) r = keep_where_positive(r, ld4(a.YM + static_cast<int64_t>(row) * a.ldym + col));
+            st4(a.Y + static_cast<int64_t>(row) * a.ldy + col, r);
+        }
+    });
 }
 
 // Second pass for huge rows: adds the partial rows of a row's work-groups in share order, then
@@ -1542,6 +1788,29 @@ hipError_t sddmm_go(const SddmmArgs &a, hipStream_t s)
 // The grouped kernels address the gathered operand with 32-bit byte offsets from its base.
 inline bool spans_below_4gib(int64_t rows, int64_t ld) { return rows * ld * 4 < (1ll << 32); }
 
+bool spmm_vec_ok(const SpmmArgs &a);
+
+// The staged product pays where a work-group finds several stored entries per operand row it
+// copies into LDS, fills its column tiles, and has enough siblings to occupy the chip; where the
+// segments are long (the gathers then dominate everything else) or the operand is beyond any
+// L2 and evenly used (the gathers of the other kernels then go to memory); and where no single row, which one row
+// of 16 lanes serves alone at about one entry per 60 ns, outlasts the rest of the matrix, which
+// the chip's 256 LDS serve at about one entry and tile per 3.3 ns each.
+bool spmm_staged_ok(const SpmmArgs &a)
+{
+    if (!a.blocks.staged_rows || a.batch < kStageMinBatch || a.batch % 4 != 0 || !spmm_vec_ok(a)) return false;
+    const int64_t n_tiles = (a.batch + kStageCols - 1) / kStageCols;
+    if (static_cast<int64_t>(a.batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
+    const int64_t groups = n_tiles * a.blocks.staged_ranges;
+    if (groups < kStageTargetGroups * 3 / 4 || groups >= (1ll << 31)) return false;
+    if (static_cast<double>(a.nnz) < static_cast<double>(kStageMinReuse) * a.blocks.staged_ranges * a.x_rows) return false;
+    if (static_cast<int64_t>(a.blocks.staged_longest_row) * 4096 > static_cast<int64_t>(a.nnz) * n_tiles) return false;
+    const bool long_segments = static_cast<int64_t>(a.nnz) >= static_cast<int64_t>(kStageLongSegment) * a.rows * a.blocks.staged_cblocks;
+    // (a few hot operand rows that take most gathers stay cached on the other paths)
+    const bool big_operand = static_cast<int64_t>(a.x_rows) * a.batch * 4 >= kStageBigOperand && a.blocks.hot_share < 0.5f;
+    return long_segments || big_operand;
+}
+
 bool spmm_offsets_ok(const SpmmArgs &a)
 {
     return spans_below_4gib(a.x_rows, a.ldx) && (!a.XM || spans_below_4gib(a.x_rows, a.ldxm));
@@ -1635,7 +1904,7 @@ bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && spmm_offsets_ok(a) &&
-           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && sddmm_tile_columns(b) == 0;
+           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && !spmm_staged_ok(a) && sddmm_tile_columns(b) == 0;
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
@@ -1681,6 +1950,15 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
         hipLaunchKernelGGL(full_rows_kernel, dim3(n_slices, (a.batch + 255) / 256), dim3(kFullWaves * kWave),
                            static_cast<size_t>(kFullWaves) * a.rows * kWave * sizeof(float4), s, a);
         hipLaunchKernelGGL(full_rows_finish_kernel, dim3(a.rows, (a.batch + kEwBlock - 1) / kEwBlock), dim3(kEwBlock), 0, s, a, n_slices);
+        return hipGetLastError();
+    }
+    if (spmm_staged_ok(a)) {
+        const int n_tiles = (a.batch + kStageCols - 1) / kStageCols;
+        const dim3 grid(n_tiles * a.blocks.staged_ranges), block(kStageWaves * kWave);
+        if (a.XM)
+            hipLaunchKernelGGL(spmm_staged_kernel<true>, grid, block, 0, s, a, n_tiles);
+        else
+            hipLaunchKernelGGL(spmm_staged_kernel<false>, grid, block, 0, s, a, n_tiles);
         return hipGetLastError();
     }
     if (spmm_vec_ok(a)) {

@@ -70,9 +70,9 @@ def main() -> int:
                                      np.zeros(n, np.float32), False)
         else:
             lay = wl.make_zipf_matrix(n, dens, seed=11)
-        L = nb.SparseLinear(lay)
         rn = np.diff(lay.indptr)
         for batch in args.batch:
+            L = nb.SparseLinear(lay, max_batch=batch)   # bound for this batch: the partition may depend on it
             rng = np.random.default_rng(batch)
             X = nb.to_dense(rng.standard_normal((n, batch), dtype=np.float32))
             dY = nb.to_dense(rng.standard_normal((n, batch), dtype=np.float32))
@@ -98,7 +98,7 @@ def main() -> int:
                     "gbs_cold": round(byt / cold / 1e3, 1), "frac_hbm_cold": round(byt / cold / 1e3 / HBM_PEAK_GBS, 4),
                     "gbs_back_to_back": round(byt / warm / 1e3, 1),
                     "tflops_back_to_back": round(2.0 * nnz * batch / warm / 1e6, 3)}), flush=True)
-        L.close()
+            L.close()
     return 0
 
 

@@ -102,6 +102,26 @@ def test_stage_parity_small(nb, torch_mod, oracle, sizes, kw, batch, steps, unfu
     M.close()
 
 
+def test_stage_parity_staged_products(nb, torch_mod, oracle):
+    """A batch of 512 on layers with ~200 entries per row: the forward products of both hidden layers and the
+    transposed product of the second (with the ReLU mask of the first applied as it is stored) take the
+    staged kernel; two steps, so that the second uses weights and mirror values the first one updated."""
+    torch = torch_mod
+    sizes, batch = (600, 2048, 2048, 10), 512
+    mlp = wl.make_mlp(sizes, sparsity=0.9, bias_std=0.1, pattern_seed=101, value_seed=201)
+    for l, (rows, cols) in enumerate([(2048, 600), (2048, 2048)]):
+        lay = mlp.layers[l]
+        assert nb.nerva_plan_staged_host(rows, cols, lay.indptr, lay.indices, batch)[0].shape[0] >= 32
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 2, seed=301)
+    M = nb.MLP(mlp, batch)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, False)
+    M.close()
+
+
 def _digest(*arrays):
     h = hashlib.sha256()
     for a in arrays:

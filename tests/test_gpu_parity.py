@@ -101,6 +101,12 @@ SHAPES = [
     (16, 700, 1.0, 300, None),       # 16 rows, ragged slices and columns
     (3, 1000, 1.0, 64, None),
     (10, 8192, 1.0, 256, None),      # the wide MLP's saturated output layer, a quarter of its batch
+    # wide batch, several entries per operand row and row range: operand blocks staged in LDS
+    (2048, 1100, 0.3, 512, None),    # segments of ~150 entries, ragged last column block; the mirror is not staged
+    (4096, 4200, 0.08, 256, None),   # both directions staged, 64 row ranges
+    (3072, 12300, 0.012, 1024, None),  # a 50 MB operand: staged although its segments are short (~6 entries)
+    (4096, 700, 0.1, 216, None),     # last tile ragged (24 of 64 columns)
+    (4096, 600, 0.1, 704, None),     # 11 tiles: eight XCD-aligned, three dealt plainly
     # operands beyond an L2: column tiles in the products and per-tile partial sums in the SDDMM
     (300, 6000, 0.02, 200, None),    # 64-column tiles, ragged last tile
     (320, 12000, 0.02, 360, None),   # 32-column tiles (240 entries per row, a 17 MB operand)
@@ -287,6 +293,38 @@ def test_zipf_matrix_packed_rows(nb, torch_mod, oracle):
         close(dXd.cpu().numpy(), dX, SdX, what="dX")
         gr, Sg, dbr, Sdb = oracle.sddmm(n, n, z.indptr, z.indices, dY, X)
         close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+        L.close()
+
+
+def test_zipf_matrix_staged_products(nb, torch_mod, oracle):
+    """Power-law rows on the staged products: full rows (a segment of 512 entries in every column block) next
+    to rows with a single entry and empty rows (bias only), in both directions, with and without ReLU mask."""
+    torch = torch_mod
+    n, batch = 4096, 1024
+    lens = wl.zipf_row_nnz(n, n, n * n // 10, 1.2, seed=19)
+    lens[np.arange(5, n, 37)] = 0                              # empty rows and rows with one entry, scattered
+    lens[np.arange(11, n, 41)] = 1
+    indptr, indices = wl.pattern_from_row_nnz(lens, n, seed=20)
+    prng = np.random.default_rng(21)
+    z = wl.SparseLayerData(n, n, indptr, indices, prng.standard_normal(int(indptr[-1])).astype(np.float32),
+                           (prng.standard_normal(n) * 0.5).astype(np.float32), False)
+    slot_rows, ends = nb.nerva_plan_staged_host(n, n, z.indptr, z.indices, batch)
+    assert ends.shape[0] >= 16 and ends.shape[1] == 9 and (lens == n).any()
+    rng = np.random.default_rng(batch)
+    X = rng.standard_normal((n, batch)).astype(np.float32)
+    dY = rng.standard_normal((n, batch)).astype(np.float32)
+    for relu in (False, True):
+        lay = wl.SparseLayerData(n, n, z.indptr, z.indices, z.values, z.bias, relu)
+        L = nb.SparseLinear(lay, max_batch=batch)
+        Xd = nb.to_dense(X); Yd = nb.dense(n, batch); dYd = nb.to_dense(dY); dXd = nb.dense(n, batch)
+        nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+        nb.sparse_linear_backward(L.handle, Xd, Yd if relu else None, dYd, dXd, None, None, batch)
+        torch.cuda.synchronize()
+        Y, S = oracle.spmm(n, n, z.indptr, z.indices, z.values, z.bias, X, relu)
+        close(Yd.cpu().numpy(), Y, S, what="Y")
+        dZ = oracle.relu_backward(dY, Y) if relu else dY
+        dX, SdX = oracle.spmm_t(n, n, z.indptr, z.indices, z.values, dZ)
+        close(dXd.cpu().numpy(), dX, SdX, what="dX")
         L.close()
 
 

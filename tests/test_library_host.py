@@ -191,6 +191,47 @@ def test_short_row_partition(nb):
     assert nb.nerva_plan_short_rows_host(4000, np.zeros(4001, dtype=np.int32))[1] == 0
 
 
+def test_staged_ranges_and_segment_bounds(nb):
+    """Third form: ranges of consecutive rows (at most 512 each), every row in exactly one slot, longest first
+    inside a range, and per slot the positions that cut its row at the multiples of 512 in the column indices."""
+    R, RR = nb.NERVA_STAGE_ROWS, nb.NERVA_STAGE_RANGE_ROWS
+    cases = [(700, 1300, wl.uniform_pattern(700, 1300, 700 * 1300 // 5, seed=3), 256),
+             (2048, 512, wl.uniform_pattern(2048, 512, 2048 * 512 // 10, seed=4), 1024),
+             (5000, 900, wl.uniform_pattern(5000, 900, 5000 * 900 // 4, seed=8), 2048),
+             (640, 2100, wl.pattern_from_row_nnz(wl.zipf_row_nnz(640, 2100, 640 * 2100 // 8, 1.2, seed=5), 2100, seed=6), 128)]
+    for rows, cols, (indptr, indices), max_batch in cases:
+        slot_rows, ends = nb.nerva_plan_staged_host(rows, cols, indptr, indices, max_batch)
+        ranges, nb1, _ = ends.shape
+        n_tiles = -(-max_batch // nb.NERVA_STAGE_COLS)
+        assert nb1 - 1 == -(-cols // R)
+        assert ranges >= max(-(-rows // RR), min(256 // n_tiles, rows // 64)) and ranges <= 256 // n_tiles + -(-rows // RR)
+        lens = np.diff(indptr)
+        seen = np.zeros(rows, dtype=np.int32)
+        first = []
+        for q in range(ranges):
+            used = slot_rows[q] >= 0
+            n = int(used.sum())
+            assert n >= 1 and used[:n].all() and (ends[q][:, ~used] == 0).all()
+            r = slot_rows[q, :n]
+            seen[r] += 1
+            assert r.max() - r.min() == n - 1                                  # consecutive rows
+            first.append(int(r.min()))
+            key = list(zip((-lens[r]).tolist(), r.tolist()))
+            assert key == sorted(key)                                           # longest first, ties in row order
+            e = ends[q][:, :n]
+            assert np.array_equal(e[0], indptr[r]) and np.array_equal(e[-1], indptr[r + 1]) and (np.diff(e, axis=0) >= 0).all()
+            for s in range(0, n, max(1, n // 7)):                               # the cut positions, on a sample of slots
+                row_cols = indices[indptr[r[s]]:indptr[r[s] + 1]]
+                want = indptr[r[s]] + np.searchsorted(row_cols, np.arange(nb1) * R)
+                assert np.array_equal(e[:, s], want)
+        assert (seen == 1).all() and first == sorted(first)
+    indptr, indices = cases[0][2]
+    assert nb.nerva_plan_staged_host(700, 1300, indptr, indices, 127)[0].shape[0] == 0      # batch too narrow
+    ip, ix = wl.uniform_pattern(700, 1300, 700 * 13, seed=7)
+    assert nb.nerva_plan_staged_host(700, 1300, ip, ix, 256)[0].shape[0] == 0                # too few entries per staged row
+    assert nb.nerva_plan_staged_host(50, 40, np.zeros(51, dtype=np.int32), np.zeros(0, dtype=np.int32), 256)[0].shape[0] == 0
+
+
 def test_row_plan_uniform_and_skewed(nb):
     mlp = wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9)
     for lay in mlp.layers:
