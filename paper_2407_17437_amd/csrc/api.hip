@@ -659,8 +659,10 @@ static int build_structures(nerva_layer *l, hipStream_t s)
     if (e == hipSuccess) {
         // room for the column-tiled SDDMM at max_batch columns, if that batch would be tiled
         const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false);
-        if (w > 0) {
-            l->partial_tiles = (max_batch + w - 1) / w;
+        int32_t tiles = w > 0 ? (max_batch + w - 1) / w : 0;
+        if (l->plan.staged_rows && (max_batch + kStageCols - 1) / kStageCols > tiles) tiles = (max_batch + kStageCols - 1) / kStageCols;
+        if (tiles > 0) {
+            l->partial_tiles = tiles;
             l->partial_db_at = round_up(nnz, 64);
             l->partial_stride = l->partial_db_at + round_up(rows, 64);
             const size_t bytes = static_cast<size_t>(l->partial_tiles) * l->partial_stride * 4;

@@ -870,16 +870,12 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool XMASK>
-__global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const SpmmArgs a, const int n_tiles)
+// Work-groups of one column tile stage the same operand rows: where there are eight tiles or
+// more, each of eight tiles gets an XCD (consecutive work-groups go to consecutive XCDs) and its
+// L2 to itself; left-over tiles are dealt out plainly.
+__device__ __forceinline__ void staged_ids(int n_ranges, int n_tiles, int &range, int &tile)
 {
-    __shared__ float4 stage[kStageRows * kStageCols / 4];
-    // Work-groups of one column tile stage the same operand rows: where there are eight tiles or
-    // more, each of eight tiles gets an XCD (consecutive work-groups go to consecutive XCDs) and
-    // its L2 to itself; left-over tiles are dealt out plainly.
-    const int n_ranges = a.blocks.staged_ranges;
     const int aligned = (n_tiles >> 3) * 8 * n_ranges;
-    int range, tile;
     if (static_cast<int>(blockIdx.x) < aligned) {
         const int slot = blockIdx.x >> 3;
         range = slot % n_ranges;
@@ -889,6 +885,15 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
         tile = (n_tiles >> 3) * 8 + rest % left;
         range = rest / left;
     }
+}
+
+template <bool XMASK>
+__global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const SpmmArgs a, const int n_tiles)
+{
+    __shared__ float4 stage[kStageRows * kStageCols / 4];
+    const int n_ranges = a.blocks.staged_ranges;
+    int range, tile;
+    staged_ids(n_ranges, n_tiles, range, tile);
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = wave_in_block();
     const int lrow = lane >> 4, lig = lane & 15;
@@ -1205,6 +1210,182 @@ __global__ __launch_bounds__(kBlock) void sddmm_tiled_kernel(const SddmmArgs a, 
     t.db = t.g + a.partial_db_at;
     if (tile != 0) t.loss_cols = nullptr;
     sddmm_body<G, NV, EXACT4>(t, rb);
+}
+
+// ---- staged SDDMM --------------------------------------------------------------------------
+// The SDDMM on the staged product's plan: same ranges, tiles, column blocks and LDS copy of the
+// operand; a lane row keeps the tile's 64 columns of dZ of its 8 rows in registers instead of
+// results.  An entry's product is a dot product over the lane row: each lane multiplies its four
+// columns, and 16 entries at a time are summed across the 16 lanes by a transposing butterfly
+// (45 instructions per 16 entries instead of 6 per entry), after which lane i holds entry i's sum
+// and the lane row stores 16 consecutive partial products.  Partial products and partial row
+// sums of dZ go to the tile's slice of the partial buffer; sddmm_finish_kernel adds the tiles.
+
+// d[i] is this lane's share of value i; returns, in lane i of every row of 16 lanes, the sum of
+// the 16 lanes' d[i].  Fixed pairing: lane l with l^8, l^7, l^2, l^1 in turn.
+__device__ __forceinline__ float row16_transpose_sum(const float (&d)[16], int lig)
+{
+    const bool b3 = lig & 8, b2 = lig & 4, b1 = lig & 2, b0 = lig & 1;
+    float e[8], f[4], g[2];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) e[k] = (b3 ? d[k + 8] : d[k]) + dpp<0x128>(b3 ? d[k] : d[k + 8]);  // row_ror:8
+#pragma unroll
+    for (int k = 0; k < 4; ++k) f[k] = (b2 ? e[k + 4] : e[k]) + dpp<0x141>(b2 ? e[k] : e[k + 4]);  // row_half_mirror
+#pragma unroll
+    for (int k = 0; k < 2; ++k) g[k] = (b1 ? f[k + 2] : f[k]) + dpp<0x4E>(b1 ? f[k] : f[k + 2]);   // quad_perm [2,3,0,1]
+    return (b0 ? g[1] : g[0]) + dpp<0xB1>(b0 ? g[0] : g[1]);                                      // quad_perm [1,0,3,2]
+}
+
+template <int I>
+__device__ __forceinline__ float staged_dot(const char *lds, int off, const float4 &z)
+{
+    const float4 x = *reinterpret_cast<const float4 *>(lds + row_lane<I>(off));
+    return fmaf(x.w, z.w, fmaf(x.z, z.z, fmaf(x.y, z.y, x.x * z.x)));
+}
+
+// Up to 16 entries of every lane row (n: the most any of the four has left, uniform): products of
+// the entries whose LDS byte offsets the lanes hold in off, stored by lane i for entry first + i.
+__device__ __forceinline__ void sddmm_staged_chunk(const char *lds, int off, const float4 &z, int n, int lig,
+                                                   int first, int end, float *gp)
+{
+    float d[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) d[i] = 0.f;
+    d[0] = staged_dot<0>(lds, off, z); d[1] = staged_dot<1>(lds, off, z);
+    d[2] = staged_dot<2>(lds, off, z); d[3] = staged_dot<3>(lds, off, z);
+    if (n > 4) {
+        d[4] = staged_dot<4>(lds, off, z); d[5] = staged_dot<5>(lds, off, z);
+        d[6] = staged_dot<6>(lds, off, z); d[7] = staged_dot<7>(lds, off, z);
+    }
+    if (n > 8) {
+        d[8] = staged_dot<8>(lds, off, z); d[9] = staged_dot<9>(lds, off, z);
+        d[10] = staged_dot<10>(lds, off, z); d[11] = staged_dot<11>(lds, off, z);
+    }
+    if (n > 12) {
+        d[12] = staged_dot<12>(lds, off, z); d[13] = staged_dot<13>(lds, off, z);
+        d[14] = staged_dot<14>(lds, off, z); d[15] = staged_dot<15>(lds, off, z);
+    }
+    const float sum = row16_transpose_sum(d, lig);
+    if (first + lig < end) gp[first + lig] = sum;
+}
+
+__device__ __forceinline__ void sddmm_staged_segment(const SddmmArgs &a, const char *lds, int cb0, int lig, int p0, int len,
+                                                     int off, const float4 &z, float *gp)
+{
+    const int l01 = max(__builtin_amdgcn_readlane(len, 0), __builtin_amdgcn_readlane(len, 16));
+    const int l23 = max(__builtin_amdgcn_readlane(len, 32), __builtin_amdgcn_readlane(len, 48));
+    const int longest = max(l01, l23);
+    if (longest <= 16) {
+        if (longest > 0) sddmm_staged_chunk(lds, off, z, longest, lig, p0, p0 + len, gp);
+        return;
+    }
+    constexpr int kDepth = 2;  // chunks of 16 entries served while the next kDepth travel
+    int o[kDepth], o2[kDepth];
+    auto load_chunk = [&](int first, int &oo) {
+        oo = 0;
+        if (first < longest && first + lig < len) oo = (a.indices[p0 + first + lig] - cb0) * (kStageCols * 4);
+    };
+    o[0] = off;
+#pragma unroll
+    for (int k = 1; k < kDepth; ++k) load_chunk(16 * k, o[k]);
+    for (int c = 0; c < longest; c += 16 * kDepth) {
+#pragma unroll
+        for (int k = 0; k < kDepth; ++k) load_chunk(c + 16 * (kDepth + k), o2[k]);
+#pragma unroll
+        for (int k = 0; k < kDepth; ++k) {
+            const int n = longest - c - 16 * k;
+            if (n > 0) sddmm_staged_chunk(lds, o[k], z, n, lig, p0 + c + 16 * k, p0 + len, gp);
+        }
+#pragma unroll
+        for (int k = 0; k < kDepth; ++k) o[k] = o2[k];
+    }
+}
+
+__global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const SddmmArgs a, const int n_tiles)
+{
+    __shared__ float4 stage[kStageRows * kStageCols / 4];
+    const int n_ranges = a.blocks.staged_ranges;
+    int range, tile;
+    staged_ids(n_ranges, n_tiles, range, tile);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int lrow = lane >> 4, lig = lane & 15;
+    const int col = tile * kStageCols + lig * 4;
+    const bool col_on = col < a.batch;
+    const char *lds = reinterpret_cast<const char *>(stage) + lig * 16;
+    const int n_cb = a.blocks.staged_cblocks;
+    const int my_slot = ((lig & (kStageJ - 1)) * kStageWaves + wv) * 4 + lrow;
+    const int my_row = a.blocks.staged_rows[range * kStageRangeRows + my_slot];
+    const int n_j = a.blocks.staged_groups[range];
+    const int32_t *ends = a.blocks.staged_ends + static_cast<int64_t>(range) * (n_cb + 1) * kStageRangeRows + my_slot;
+    float *gp = a.partial + static_cast<int64_t>(tile) * a.partial_stride;
+    constexpr auto all_j = std::make_integer_sequence<int, kStageJ>{};
+    // the tile's columns of dZ for the lane row's rows, and their sums (the tile's share of db)
+    float4 z[kStageJ];
+    static_for(all_j, [&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        z[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < n_j) {
+            const int row = row_lane<j>(my_row);
+            if (row >= 0 && col_on) {
+                z[j] = ld4(a.dZ + static_cast<int64_t>(row) * a.lddz + col);
+                if (a.ZM) z[j] = keep_where_positive(z[j], ld4(a.ZM + static_cast<int64_t>(row) * a.ldzm + col));
+            }
+            const float sum = row16_sum((z[j].x + z[j].y) + (z[j].z + z[j].w));
+            if (row >= 0 && lig == 0) gp[a.partial_db_at + row] = sum;
+        }
+    });
+    auto first_chunks = [&](int blk, int e_lo, int e_hi, int (&off)[kStageJ]) {
+        static_for(all_j, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            off[j] = 0;
+            if (j < n_j) {
+                const int p0 = row_lane<j>(e_lo);
+                if (lig < row_lane<j>(e_hi) - p0) off[j] = (a.indices[p0 + lig] - blk * kStageRows) * (kStageCols * 4);
+            }
+        });
+    };
+    int e0 = ends[0], e1 = ends[kStageRangeRows];
+    int e2 = n_cb >= 2 ? ends[2 * kStageRangeRows] : e1;
+    int off_cur[kStageJ];
+    first_chunks(0, e0, e1, off_cur);
+    for (int b = 0; b < n_cb; ++b) {
+        const int cb0 = b * kStageRows;
+        lds_barrier();  // the previous block's gathers are done
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            constexpr int kHalf = kStageRows / 128;
+            float4 v[kHalf];
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) {
+                const int k = cb0 + (h * kHalf + i) * 64 + static_cast<int>(threadIdx.x >> 4);
+                v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < a.x_rows && col_on) v[i] = ld4(a.X + static_cast<int64_t>(k) * a.ldx + col);
+            }
+#pragma unroll
+            for (int i = 0; i < kHalf; ++i) stage[((h * kHalf + i) * 64 + (threadIdx.x >> 4)) * 16 + lig] = v[i];
+        }
+        int off_next[kStageJ];
+        int e3 = e2;
+        if (b + 1 < n_cb) {
+            first_chunks(b + 1, e1, e2, off_next);
+            if (b + 3 <= n_cb) e3 = ends[(b + 3) * kStageRangeRows];
+        } else {
+            static_for(all_j, [&](auto jc) { off_next[decltype(jc)::value] = 0; });
+        }
+        lds_barrier();
+        static_for(all_j, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            if (j < n_j) {
+                const int p0 = row_lane<j>(e0);
+                sddmm_staged_segment(a, lds, cb0, lig, p0, row_lane<j>(e1) - p0, off_cur[j], z[j], gp);
+            }
+        });
+        static_for(all_j, [&](auto jc) { off_cur[decltype(jc)::value] = off_next[decltype(jc)::value]; });
+        e0 = e1;
+        e1 = e2;
+        e2 = e3;
+    }
 }
 
 // Second pass of the tiled SDDMM: adds the tiles' partial products in tile order, then stores the
@@ -1796,19 +1977,31 @@ bool spmm_vec_ok(const SpmmArgs &a);
 // L2 and evenly used (the gathers of the other kernels then go to memory); and where no single row, which one row
 // of 16 lanes serves alone at about one entry per 60 ns, outlasts the rest of the matrix, which
 // the chip's 256 LDS serve at about one entry and tile per 3.3 ns each.
-bool spmm_staged_ok(const SpmmArgs &a)
+bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t batch, int64_t nnz)
 {
-    if (!a.blocks.staged_rows || a.batch < kStageMinBatch || a.batch % 4 != 0 || !spmm_vec_ok(a)) return false;
-    const int64_t n_tiles = (a.batch + kStageCols - 1) / kStageCols;
-    if (static_cast<int64_t>(a.batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
-    const int64_t groups = n_tiles * a.blocks.staged_ranges;
+    if (!blocks.staged_rows || batch < kStageMinBatch || batch % 4 != 0) return false;
+    const int64_t n_tiles = (batch + kStageCols - 1) / kStageCols;
+    if (static_cast<int64_t>(batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
+    const int64_t groups = n_tiles * blocks.staged_ranges;
     if (groups < kStageTargetGroups * 3 / 4 || groups >= (1ll << 31)) return false;
-    if (static_cast<double>(a.nnz) < static_cast<double>(kStageMinReuse) * a.blocks.staged_ranges * a.x_rows) return false;
-    if (static_cast<int64_t>(a.blocks.staged_longest_row) * 4096 > static_cast<int64_t>(a.nnz) * n_tiles) return false;
-    const bool long_segments = static_cast<int64_t>(a.nnz) >= static_cast<int64_t>(kStageLongSegment) * a.rows * a.blocks.staged_cblocks;
+    if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
+    if (static_cast<int64_t>(blocks.staged_longest_row) * 4096 > nnz * n_tiles) return false;
+    const bool long_segments = nnz >= static_cast<int64_t>(kStageLongSegment) * rows * blocks.staged_cblocks;
     // (a few hot operand rows that take most gathers stay cached on the other paths)
-    const bool big_operand = static_cast<int64_t>(a.x_rows) * a.batch * 4 >= kStageBigOperand && a.blocks.hot_share < 0.5f;
+    const bool big_operand = static_cast<int64_t>(x_rows) * batch * 4 >= kStageBigOperand && blocks.hot_share < 0.5f;
     return long_segments || big_operand;
+}
+
+bool spmm_staged_ok(const SpmmArgs &a) { return spmm_vec_ok(a) && staged_pays(a.blocks, a.rows, a.x_rows, a.batch, a.nnz); }
+
+bool sddmm_vec_ok(const SddmmArgs &a);
+
+// the staged SDDMM needs room for one slice of partial products per 64-column tile
+bool sddmm_staged_ok(const SddmmArgs &a)
+{
+    if (!a.partial || a.skip_products || a.dense || a.loss_cols || !sddmm_vec_ok(a)) return false;
+    if ((a.batch + kStageCols - 1) / kStageCols > a.partial_tiles) return false;
+    return staged_pays(a.blocks, a.rows, a.x_rows, a.batch, a.nnz);
 }
 
 bool spmm_offsets_ok(const SpmmArgs &a)
@@ -1904,14 +2097,14 @@ bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && spmm_offsets_ok(a) &&
-           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && !spmm_staged_ok(a) && sddmm_tile_columns(b) == 0;
+           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && !spmm_staged_ok(a) && sddmm_tile_columns(b) == 0 && !sddmm_staged_ok(b);
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && sddmm_vec_ok(a) && sddmm_vec_ok(b) &&
-           sddmm_tile_columns(a) == 0 && sddmm_tile_columns(b) == 0;
+           sddmm_tile_columns(a) == 0 && sddmm_tile_columns(b) == 0 && !sddmm_staged_ok(a) && !sddmm_staged_ok(b);
 }
 
 hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
@@ -2007,6 +2200,13 @@ int sddmm_tile_columns(const SddmmArgs &a)
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    if (sddmm_staged_ok(a)) {
+        const int n_tiles = (a.batch + kStageCols - 1) / kStageCols;
+        hipLaunchKernelGGL(sddmm_staged_kernel, dim3(n_tiles * a.blocks.staged_ranges), dim3(kStageWaves * kWave), 0, s, a, n_tiles);
+        const int64_t work = a.nnz > a.rows ? a.nnz : a.rows;
+        hipLaunchKernelGGL(sddmm_finish_kernel, dim3(elementwise_blocks(work)), dim3(kEwBlock), 0, s, a, n_tiles);
+        return hipGetLastError();
+    }
     switch (sddmm_tile_columns(a)) {
         case 128: return sddmm_tiled_go<16, 2>(a, s);
         case 64: return sddmm_tiled_go<16, 1>(a, s);

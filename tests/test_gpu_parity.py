@@ -297,7 +297,7 @@ def test_zipf_matrix_packed_rows(nb, torch_mod, oracle):
 
 
 def test_zipf_matrix_staged_products(nb, torch_mod, oracle):
-    """Power-law rows on the staged products: full rows (a segment of 512 entries in every column block) next
+    """Power-law rows on the staged products and the staged SDDMM: full rows (a segment of 512 entries in every column block) next
     to rows with a single entry and empty rows (bias only), in both directions, with and without ReLU mask."""
     torch = torch_mod
     n, batch = 4096, 1024
@@ -317,14 +317,17 @@ def test_zipf_matrix_staged_products(nb, torch_mod, oracle):
         lay = wl.SparseLayerData(n, n, z.indptr, z.indices, z.values, z.bias, relu)
         L = nb.SparseLinear(lay, max_batch=batch)
         Xd = nb.to_dense(X); Yd = nb.dense(n, batch); dYd = nb.to_dense(dY); dXd = nb.dense(n, batch)
+        g = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((n,), float("nan"), device="cuda")
         nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
-        nb.sparse_linear_backward(L.handle, Xd, Yd if relu else None, dYd, dXd, None, None, batch)
+        nb.sparse_linear_backward(L.handle, Xd, Yd if relu else None, dYd, dXd, g, db, batch)
         torch.cuda.synchronize()
         Y, S = oracle.spmm(n, n, z.indptr, z.indices, z.values, z.bias, X, relu)
         close(Yd.cpu().numpy(), Y, S, what="Y")
         dZ = oracle.relu_backward(dY, Y) if relu else dY
         dX, SdX = oracle.spmm_t(n, n, z.indptr, z.indices, z.values, dZ)
         close(dXd.cpu().numpy(), dX, SdX, what="dX")
+        gr, Sg, dbr, Sdb = oracle.sddmm(n, n, z.indptr, z.indices, dZ, X)
+        close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
         L.close()
 
 
