@@ -125,6 +125,8 @@ def main() -> int:
                     help="layers of at least this density take the dense MFMA route for their two products (default: none)")
     ap.add_argument("--separate-head", action="store_true",
                     help="keep the output layer's forward product, loss and transposed product as three launches")
+    ap.add_argument("--prefer-staged", action="store_true",
+                    help="measurement aid: staged (LDS) products and SDDMM wherever they can run, not only where the library expects them to pay")
     ap.add_argument("--inference", action="store_true",
                     help="instead of training steps: forward passes on ONE example (batch 1), microseconds per example")
     args = ap.parse_args()
@@ -149,6 +151,8 @@ def main() -> int:
     Xd = torch.zeros((pool, sizes[0], ld), dtype=torch.float32, device="cuda")
     Xd[:, :, :batch] = torch.as_tensor(Xs).cuda()
     Td = torch.as_tensor(Ts).cuda()
+    if args.prefer_staged:
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
     M = nb.MLP(mlp, batch, (nb.NERVA_MLP_UNFUSED if args.unfused else 0) |
                (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0), dense_from_density=args.dense_from_density)
     x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4

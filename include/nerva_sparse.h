@@ -99,8 +99,12 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
  * nerva_plan_*_host calls build (process-wide; layers already bound keep theirs).
  * NERVA_PARTITION_BALANCED (default): the partition described above.  NERVA_PARTITION_ROW_SPLIT:
  * plain row splitting -- one wave per row whatever its length, no huge rows, no packed short
- * rows -- so that the balanced partition can be timed against it on the same matrix. */
-enum { NERVA_PARTITION_BALANCED = 0, NERVA_PARTITION_ROW_SPLIT = 1 };
+ * rows, no staged products -- so that the balanced partition can be timed against it on the same
+ * matrix.  NERVA_PARTITION_PREFER_STAGED: the balanced partition, but the staged products and the
+ * staged SDDMM (see nerva_plan_staged_host) run wherever they can (batch of at least
+ * NERVA_STAGE_MIN_BATCH columns, a multiple of 4), also where the library's own rule expects them
+ * to be slower. */
+enum { NERVA_PARTITION_BALANCED = 0, NERVA_PARTITION_ROW_SPLIT = 1, NERVA_PARTITION_PREFER_STAGED = 2 };
 int nerva_set_partition_mode(int32_t mode);
 
 /* The second partition, which the products Y = S X and Y = S^T X use on matrices with many short

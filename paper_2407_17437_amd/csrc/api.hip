@@ -314,7 +314,8 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
 {
     StagedPlan H;
     const int64_t nnz = indptr[rows];
-    if (g_partition_mode.load() != NERVA_PARTITION_BALANCED || max_batch < kStageMinBatch || nnz == 0) return H;
+    const bool preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
+    if (g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT || max_batch < kStageMinBatch || nnz == 0) return H;
     const int32_t n_tiles = (max_batch + kStageCols - 1) / kStageCols;
     int32_t want = kStageTargetGroups / n_tiles;
     if (want > rows / 64) want = rows / 64;
@@ -326,7 +327,7 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
         const int64_t rounds = (static_cast<int64_t>(want) * n_tiles + kStageTargetGroups - 1) / kStageTargetGroups;
         want = static_cast<int32_t>(rounds * kStageTargetGroups / n_tiles);
     }
-    if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * want * cols) return H;
+    if (!preferred && static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * want * cols) return H;
     const int32_t cblocks = (cols + kStageRows - 1) / kStageRows;
     if ((static_cast<int64_t>(want) + at_least) * (cblocks + 1) * kStageRangeRows > (1ll << 28)) return H;  // tables beyond 1 GiB
     // ranges of about equal cost: a stored entry costs one gather, a segment about two more
@@ -428,6 +429,7 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *
     plan->staged_groups = H.ranges ? *mem + groups_at : nullptr;
     plan->staged_ranges = H.ranges;
     plan->staged_cblocks = H.cblocks;
+    plan->staged_preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
     plan->staged_longest_row = 0;
     for (int32_t r = 0; r < rows; ++r)
         if (indptr_host[r + 1] - indptr_host[r] > plan->staged_longest_row) plan->staged_longest_row = indptr_host[r + 1] - indptr_host[r];
@@ -511,7 +513,7 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz, const int32
 
 int nerva_set_partition_mode(int32_t mode)
 {
-    if (mode != NERVA_PARTITION_BALANCED && mode != NERVA_PARTITION_ROW_SPLIT) return fail(NERVA_ERR_ARGUMENT, "unknown partition mode %d", mode);
+    if (mode != NERVA_PARTITION_BALANCED && mode != NERVA_PARTITION_ROW_SPLIT && mode != NERVA_PARTITION_PREFER_STAGED) return fail(NERVA_ERR_ARGUMENT, "unknown partition mode %d", mode);
     g_partition_mode.store(mode);
     return NERVA_OK;
 }

@@ -47,6 +47,7 @@ struct RowBlocks {
     int32_t staged_ranges;
     int32_t staged_cblocks;
     int32_t staged_longest_row;    // stored entries of the longest row
+    int32_t staged_preferred;      // measurement aid: take the staged kernels wherever they can run
 };
 constexpr int32_t kStageRows = 512;      // operand rows held in LDS at a time
 constexpr int32_t kStageCols = 64;       // columns of the operand (examples) per work-group

@@ -759,10 +759,10 @@ __device__ __forceinline__ void static_for(std::integer_sequence<int, I...>, F &
 
 // lane i of every row of 16 lanes receives the value of the row's lane I
 template <int I>
-__device__ __forceinline__ int row_lane(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x150 + I, 0xF, 0xF, false); }
+__device__ __forceinline__ int row_lane(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x150 + I, 0xF, 0xF, true); }
 // lane i of every row of 16 lanes receives the value of the row's lane (i + K) % 16
 template <int K>
-__device__ __forceinline__ int row_rotate_down(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x120 + (16 - K), 0xF, 0xF, false); }
+__device__ __forceinline__ int row_rotate_down(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x120 + (16 - K), 0xF, 0xF, true); }
 
 template <int I>
 __device__ __forceinline__ void staged_step(const char *lds, int off, float w, float4 &acc)
@@ -1225,15 +1225,23 @@ __global__ __launch_bounds__(kBlock) void sddmm_tiled_kernel(const SddmmArgs a, 
 // the 16 lanes' d[i].  Fixed pairing: lane l with l^8, l^7, l^2, l^1 in turn.
 __device__ __forceinline__ float row16_transpose_sum(const float (&d)[16], int lig)
 {
+    // every lane has a partner in these four moves: no lane keeps the old value
+    auto from = [](auto ctrl, float x) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    using ror8 = std::integral_constant<int, 0x128>;         // row_ror:8
+    using half_mirror = std::integral_constant<int, 0x141>;  // row_half_mirror
+    using xor2 = std::integral_constant<int, 0x4E>;          // quad_perm [2,3,0,1]
+    using xor1 = std::integral_constant<int, 0xB1>;          // quad_perm [1,0,3,2]
     const bool b3 = lig & 8, b2 = lig & 4, b1 = lig & 2, b0 = lig & 1;
     float e[8], f[4], g[2];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) e[k] = (b3 ? d[k + 8] : d[k]) + dpp<0x128>(b3 ? d[k] : d[k + 8]);  // row_ror:8
+    for (int k = 0; k < 8; ++k) e[k] = (b3 ? d[k + 8] : d[k]) + from(ror8{}, b3 ? d[k] : d[k + 8]);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) f[k] = (b2 ? e[k + 4] : e[k]) + dpp<0x141>(b2 ? e[k] : e[k + 4]);  // row_half_mirror
+    for (int k = 0; k < 4; ++k) f[k] = (b2 ? e[k + 4] : e[k]) + from(half_mirror{}, b2 ? e[k] : e[k + 4]);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) g[k] = (b1 ? f[k + 2] : f[k]) + dpp<0x4E>(b1 ? f[k] : f[k + 2]);   // quad_perm [2,3,0,1]
-    return (b0 ? g[1] : g[0]) + dpp<0xB1>(b0 ? g[0] : g[1]);                                      // quad_perm [1,0,3,2]
+    for (int k = 0; k < 2; ++k) g[k] = (b1 ? f[k + 2] : f[k]) + from(xor2{}, b1 ? f[k] : f[k + 2]);
+    return (b0 ? g[1] : g[0]) + from(xor1{}, b0 ? g[0] : g[1]);
 }
 
 template <int I>
@@ -1981,9 +1989,11 @@ bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t 
 {
     if (!blocks.staged_rows || batch < kStageMinBatch || batch % 4 != 0) return false;
     const int64_t n_tiles = (batch + kStageCols - 1) / kStageCols;
-    if (static_cast<int64_t>(batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
+    if (!blocks.staged_preferred && static_cast<int64_t>(batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
     const int64_t groups = n_tiles * blocks.staged_ranges;
-    if (groups < kStageTargetGroups * 3 / 4 || groups >= (1ll << 31)) return false;
+    if (groups >= (1ll << 31)) return false;
+    if (blocks.staged_preferred) return true;
+    if (groups < kStageTargetGroups * 3 / 4) return false;
     if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
     if (static_cast<int64_t>(blocks.staged_longest_row) * 4096 > nnz * n_tiles) return false;
     const bool long_segments = nnz >= static_cast<int64_t>(kStageLongSegment) * rows * blocks.staged_cblocks;
