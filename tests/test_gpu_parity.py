@@ -331,6 +331,58 @@ def test_zipf_matrix_staged_products(nb, torch_mod, oracle):
         L.close()
 
 
+@pytest.mark.parametrize("rows,cols,lens_kind,batch", [
+    (7, 5, "uniform", 128),          # fewer rows than one group of four, one column block, one range
+    (33, 65, "uniform", 132),        # third tile holds 4 of 64 columns
+    (130, 1025, "uniform", 256),     # a column block of a single operand row
+    (64, 96, "full", 128),           # every entry stored
+    (50, 700, "empty_heavy", 128),   # most rows empty
+    (1300, 40, "uniform", 192),      # several ranges, rows cut by the 512-row limit
+    (600, 3000, "zipf", 320),        # full rows next to empty ones: segments of 512 entries and of none side by side
+])
+def test_staged_kernels_on_awkward_shapes(nb, torch_mod, oracle, rows, cols, lens_kind, batch):
+    """The staged products and the staged SDDMM where the library would not choose them: the partition mode that
+    prefers them runs them on any matrix at batches of 128 or more, which reaches their edge cases (few rows,
+    ragged tiles and blocks, empty rows and segments, very long segments)."""
+    torch = torch_mod
+    rng = np.random.default_rng(rows * 7 + cols)
+    if lens_kind == "uniform":
+        lens = rng.binomial(cols, 0.2, size=rows)
+    elif lens_kind == "full":
+        lens = np.full(rows, cols)
+    elif lens_kind == "empty_heavy":
+        lens = np.where(rng.random(rows) < 0.8, 0, rng.integers(1, cols + 1, size=rows))
+    else:
+        lens = np.minimum(cols, (cols * rng.permutation(np.arange(1, rows + 1)) ** -1.2).astype(np.int64))
+    indptr, indices = wl.pattern_from_row_nnz(lens.astype(np.int64), cols, seed=rows + cols)
+    nnz = int(indptr[-1])
+    lay = wl.SparseLayerData(rows, cols, indptr, indices, rng.standard_normal(nnz).astype(np.float32),
+                             (rng.standard_normal(rows) * 0.5).astype(np.float32), True)
+    X = rng.standard_normal((cols, batch)).astype(np.float32)
+    dY = rng.standard_normal((rows, batch)).astype(np.float32)
+    nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
+    try:
+        assert nb.nerva_plan_staged_host(rows, cols, indptr, indices, batch)[0].shape[0] >= 1
+        L = nb.SparseLinear(lay, max_batch=batch)
+    finally:
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_BALANCED)
+    Xd = nb.to_dense(X); Yd = nb.dense(rows, batch); dYd = nb.to_dense(dY); dXd = nb.dense(cols, batch)
+    g = torch.full((max(nnz, 1),), float("nan"), device="cuda")[:nnz]; db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(rows, cols, indptr, indices, lay.values, lay.bias, X, True)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    dZ = oracle.relu_backward(dY, Yd.cpu().numpy())
+    dX, SdX = oracle.spmm_t(rows, cols, indptr, indices, lay.values, dZ)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, indptr, indices, dZ, X)
+    close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+    full = Yd._base if Yd._base is not None else Yd
+    assert torch.isnan(full.view(rows, -1)[:, batch:]).all()     # padding columns of the output were not written
+    L.close()
+
+
 def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
     """Power-law rows (one full row, many empty ones): every share count of the row partition."""
     torch = torch_mod

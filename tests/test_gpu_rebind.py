@@ -91,6 +91,7 @@ def check_layer(nb, torch, oracle, L, lay, batch):
     (2500, 300, 0.02, 0.03, 100),     # packed short rows before and after
     (12, 4096, 0.9, 0.1, 100),        # huge rows become ordinary ones
     (50, 40, 0.3, 0.0, 8),            # everything pruned
+    (4096, 700, 0.1, 0.15, 256),      # staged products and staged SDDMM before and after
 ])
 def test_layer_rebind(nb, torch_mod, oracle, rows, cols, density, new_density, batch):
     torch = torch_mod
