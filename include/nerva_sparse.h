@@ -130,16 +130,21 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
  * work, one work-group per (range, tile of NERVA_STAGE_COLS batch columns); inside a range the
  * rows are listed by stored entries descending (ties in row order), four consecutive list slots
  * being served side by side; every row is cut into segments at the multiples of
- * NERVA_STAGE_ROWS in its column indices.  Outputs (arrays may be NULL to get only the counts):
+ * NERVA_STAGE_ROWS in its column indices.  A row with at least max(256, total work / ranges / 32)
+ * stored entries takes four slots, from a multiple of 4 on, each marked NERVA_STAGE_QUAD: the four
+ * serve a quarter of each of its segments each, so that no single row outlasts its range.
+ * Outputs (arrays may be NULL to get only the counts):
  *   counts_host[2]      {ranges, column blocks nb}; both 0 when no product of this matrix at up
  *                       to max_batch columns would be staged
  *   slot_rows_host[ranges * NERVA_STAGE_RANGE_ROWS]
- *                       row in each slot of each range, -1 in unused slots
+ *                       row in each slot of each range (| NERVA_STAGE_QUAD in the four slots of a
+ *                       split row), -1 in unused slots
  *   ends_host[ranges * (nb + 1) * NERVA_STAGE_RANGE_ROWS]
  *                       [(range * (nb + 1) + b) * NERVA_STAGE_RANGE_ROWS + slot] = position of the
  *                       slot's first stored entry with column >= b * NERVA_STAGE_ROWS (b = nb: one
  *                       past the row's last entry); 0 throughout for unused slots */
-enum { NERVA_STAGE_ROWS = 512, NERVA_STAGE_COLS = 64, NERVA_STAGE_MIN_BATCH = 128, NERVA_STAGE_RANGE_ROWS = 512 };
+enum { NERVA_STAGE_ROWS = 512, NERVA_STAGE_COLS = 64, NERVA_STAGE_MIN_BATCH = 128, NERVA_STAGE_RANGE_ROWS = 512,
+       NERVA_STAGE_QUAD = 1 << 30 };
 int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_host, const int32_t *indices_host,
                            int32_t max_batch, int32_t *slot_rows_host, int32_t *ends_host, int32_t *counts_host);
 

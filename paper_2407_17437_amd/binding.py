@@ -21,7 +21,7 @@ NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5
 NERVA_ACT_NONE, NERVA_ACT_RELU = 0, 1
 NERVA_PACK_MAX_LEN, NERVA_PACK_MIN_ROWS = 128, 2048
-NERVA_STAGE_ROWS, NERVA_STAGE_COLS, NERVA_STAGE_MIN_BATCH, NERVA_STAGE_RANGE_ROWS = 512, 64, 128, 512
+NERVA_STAGE_ROWS, NERVA_STAGE_COLS, NERVA_STAGE_MIN_BATCH, NERVA_STAGE_RANGE_ROWS, NERVA_STAGE_QUAD = 512, 64, 128, 512, 1 << 30
 NERVA_PARTITION_BALANCED, NERVA_PARTITION_ROW_SPLIT, NERVA_PARTITION_PREFER_STAGED = 0, 1, 2
 NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV, NERVA_MLP_SEPARATE_HEAD = 0, 1, 2, 4
 NERVA_WAVES_PER_BLOCK = 16

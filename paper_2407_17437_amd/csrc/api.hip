@@ -308,6 +308,7 @@ struct StagedPlan {
     std::vector<int32_t> ends;    // [ranges * (cblocks + 1) * kStageRangeRows]
     std::vector<int32_t> groups;  // [ranges]
     int32_t ranges = 0, cblocks = 0;
+    int32_t longest_share = 0;    // most entries any one slot serves
 };
 
 StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const int32_t *indices, int32_t max_batch)
@@ -337,19 +338,24 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     };
     int64_t total = 0;
     for (int32_t r = 0; r < rows; ++r) total += cost(r);
+    // A row of 16 lanes serves a row alone.  A row much longer than a wave's fair share of its range
+    // would make that wave the range's critical path: it gets the four lane rows of a wave instead, each a
+    // quarter of every segment ("quad": four slots, group-aligned).
+    const int64_t quad_len = std::max<int64_t>(256, total / want / 32);
+    auto slots_of = [&](int32_t r) { return indptr[r + 1] - indptr[r] >= quad_len ? 4 : 1; };
     std::vector<int32_t> first_row{0};
     {
         int32_t range = 0, in_range = 0;
         int64_t done = 0;
         for (int32_t r = 0; r < rows; ++r) {
             const bool next = range + 1 < want && done * want >= total * (range + 1);
-            if ((next || in_range == kStageRangeRows) && in_range > 0) {
+            if ((next || in_range + slots_of(r) > kStageRangeRows) && in_range > 0) {
                 first_row.push_back(r);
                 in_range = 0;
             }
             if (next) ++range;
             done += cost(r);
-            ++in_range;
+            in_range += slots_of(r);
         }
         first_row.push_back(rows);
     }
@@ -362,23 +368,29 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     std::vector<int32_t> order;
     for (int32_t q = 0; q < ranges; ++q) {
         const int32_t r0 = first_row[q], n = first_row[q + 1] - r0;
-        H.groups[q] = (n + 63) / 64;
         order.resize(n);
         for (int32_t i = 0; i < n; ++i) order[i] = r0 + i;
         std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
             return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
         });
         int32_t *e = H.ends.data() + static_cast<size_t>(q) * (cblocks + 1) * kStageRangeRows;
-        for (int32_t slot = 0; slot < n; ++slot) {
-            const int32_t r = order[slot];
-            H.rows[static_cast<size_t>(q) * kStageRangeRows + slot] = r;
+        int32_t slot = 0;  // quads come first (longest rows), so they start at multiples of 4
+        for (int32_t i = 0; i < n; ++i) {
+            const int32_t r = order[i], copies = slots_of(r);
+            const int32_t len = indptr[r + 1] - indptr[r];
+            const int32_t share = copies == 4 ? (len + 3) / 4 : len;
+            if (share > H.longest_share) H.longest_share = share;
             const int32_t *lo = indices + indptr[r], *hi = indices + indptr[r + 1];
-            e[slot] = indptr[r];
-            for (int32_t b = 1; b <= cblocks; ++b) {
-                lo = std::lower_bound(lo, hi, b * kStageRows);
-                e[static_cast<size_t>(b) * kStageRangeRows + slot] = static_cast<int32_t>(lo - indices);
+            for (int32_t b = 0; b <= cblocks; ++b) {
+                if (b > 0) lo = std::lower_bound(lo, hi, b * kStageRows);
+                for (int32_t c = 0; c < copies; ++c)
+                    e[static_cast<size_t>(b) * kStageRangeRows + slot + c] = static_cast<int32_t>(lo - indices);
             }
+            for (int32_t c = 0; c < copies; ++c)
+                H.rows[static_cast<size_t>(q) * kStageRangeRows + slot + c] = copies == 4 ? (r | kStageQuad) : r;
+            slot += copies;
         }
+        H.groups[q] = (slot + 63) / 64;
     }
     return H;
 }
@@ -430,9 +442,9 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *
     plan->staged_ranges = H.ranges;
     plan->staged_cblocks = H.cblocks;
     plan->staged_preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
+    plan->staged_longest_share = H.longest_share;
     plan->staged_longest_row = 0;
-    for (int32_t r = 0; r < rows; ++r)
-        if (indptr_host[r + 1] - indptr_host[r] > plan->staged_longest_row) plan->staged_longest_row = indptr_host[r + 1] - indptr_host[r];
+    for (int32_t r = 0; r < rows; ++r) plan->staged_longest_row = std::max(plan->staged_longest_row, indptr_host[r + 1] - indptr_host[r]);
     return e;
 }
 
@@ -556,7 +568,7 @@ int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_hos
     if (rows <= 0 || cols <= 0 || !indptr_host || !counts_host || (indptr_host[rows] > 0 && !indices_host))
         return fail(NERVA_ERR_ARGUMENT, "bad argument");
     static_assert(NERVA_STAGE_ROWS == kStageRows && NERVA_STAGE_COLS == kStageCols && NERVA_STAGE_MIN_BATCH == kStageMinBatch &&
-                  NERVA_STAGE_RANGE_ROWS == kStageRangeRows, "header and kernels disagree");
+                  NERVA_STAGE_RANGE_ROWS == kStageRangeRows && NERVA_STAGE_QUAD == kStageQuad, "header and kernels disagree");
     const StagedPlan H = plan_staged(rows, cols, indptr_host, indices_host, max_batch);
     counts_host[0] = H.ranges;
     counts_host[1] = H.cblocks;

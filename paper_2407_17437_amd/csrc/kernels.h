@@ -37,7 +37,9 @@ struct RowBlocks {
     // Optional third form, for the staged product (spmm_staged_kernel; staged_rows != nullptr).
     // The rows are cut into staged_ranges ranges of at most kStageRangeRows rows and about equal
     // work; inside a range the rows are listed longest first (slot 0, 1, ...; unused slots hold
-    // -1).  Every row is cut into segments at the multiples of kStageRows in its column indices:
+    // -1).  A row much longer than its range's mean takes four slots, a multiple of 4 onwards, marked
+    // kStageQuad: the four lane rows of one wave then serve a quarter of each of its segments each
+    // and their results are added at the end.  Every row is cut into segments at the multiples of kStageRows in its column indices:
     // staged_ends[(range * (staged_cblocks + 1) + b) * kStageRangeRows + slot] is the position of
     // the slot's first stored entry with column >= b * kStageRows (b = 0: the row's first entry,
     // b = staged_cblocks: one past its last; unused slots: 0 throughout).
@@ -46,12 +48,14 @@ struct RowBlocks {
     const int32_t *staged_groups;  // [staged_ranges] rows of the range / 64, rounded up
     int32_t staged_ranges;
     int32_t staged_cblocks;
+    int32_t staged_longest_share;  // most stored entries any one lane row serves
     int32_t staged_longest_row;    // stored entries of the longest row
     int32_t staged_preferred;      // measurement aid: take the staged kernels wherever they can run
 };
 constexpr int32_t kStageRows = 512;      // operand rows held in LDS at a time
 constexpr int32_t kStageCols = 64;       // columns of the operand (examples) per work-group
 constexpr int32_t kStageJ = 8;           // rows per row of 16 lanes
+constexpr int32_t kStageQuad = 1 << 30;  // flag in staged_rows: the slot is one of the four of a split row
 constexpr int32_t kStageRangeRows = 512; // rows per work-group: 16 waves x 4 lane rows x kStageJ
 constexpr int32_t kStageMinBatch = 128;  // narrower batches never take the staged product
 constexpr int32_t kStageTargetGroups = 256;  // work-groups wanted at max_batch (one per compute unit)

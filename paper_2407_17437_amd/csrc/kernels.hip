@@ -911,14 +911,27 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
     float4 acc[kStageJ];
     static_for(all_j, [&](auto jc) { acc[decltype(jc)::value] = make_float4(0.f, 0.f, 0.f, 0.f); });
     // first 16 entries of the segments of column block blk; e_lo, e_hi: the lane's bounds blk and blk + 1
+    // the lane row's J-th segment in a block whose bounds lane J holds in e_lo, e_hi: the slot's
+    // entries, or this lane row's quarter of them where the four lane rows share a long row
+    auto segment = [&](auto jc, int e_lo, int e_hi, int &p0, int &len) {
+        constexpr int j = decltype(jc)::value;
+        p0 = row_lane<j>(e_lo);
+        len = row_lane<j>(e_hi) - p0;
+        if (row_lane<j>(my_row) & kStageQuad) {
+            const int from = (len * lrow) >> 2;
+            p0 += from;
+            len = ((len * (lrow + 1)) >> 2) - from;
+        }
+    };
     auto first_chunks = [&](int blk, int e_lo, int e_hi, int (&off)[kStageJ], float (&w)[kStageJ]) {
         static_for(all_j, [&](auto jc) {
             constexpr int j = decltype(jc)::value;
             off[j] = 0;
             w[j] = 0.f;
             if (j < n_j) {
-                const int p0 = row_lane<j>(e_lo);
-                if (lig < row_lane<j>(e_hi) - p0) {
+                int p0, len;
+                segment(jc, e_lo, e_hi, p0, len);
+                if (lig < len) {
                     off[j] = (a.indices[p0 + lig] - blk * kStageRows) * (kStageCols * 4);
                     w[j] = a.values[p0 + lig];
                 }
@@ -963,8 +976,9 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
         static_for(all_j, [&](auto jc) {
             constexpr int j = decltype(jc)::value;
             if (j < n_j) {
-                const int p0 = row_lane<j>(e0);
-                staged_segment(a, lds, cb0, lig, p0, row_lane<j>(e1) - p0, off_cur[j], w_cur[j], acc[j]);
+                int p0, len;
+                segment(jc, e0, e1, p0, len);
+                staged_segment(a, lds, cb0, lig, p0, len, off_cur[j], w_cur[j], acc[j]);
             }
         });
         static_for(all_j, [&](auto jc) { off_cur[decltype(jc)::value] = off_next[decltype(jc)::value]; w_cur[decltype(jc)::value] = w_next[decltype(jc)::value]; });
@@ -974,8 +988,17 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
     }
     static_for(all_j, [&](auto jc) {
         constexpr int j = decltype(jc)::value;
-        const int row = row_lane<j>(my_row);
-        if (j < n_j && row >= 0 && col_on) {
+        const int slot_row = row_lane<j>(my_row);
+        const bool quad = slot_row >= 0 && (slot_row & kStageQuad);
+        const int row = slot_row < 0 ? -1 : (slot_row & ~kStageQuad);
+        if (j < n_j && __builtin_amdgcn_readfirstlane(quad)) {
+            // the four lane rows hold a quarter of the row's sum each: (0 + 1) + (2 + 3), in every lane row
+            acc[j].x += __shfl_xor(acc[j].x, 16); acc[j].y += __shfl_xor(acc[j].y, 16);
+            acc[j].z += __shfl_xor(acc[j].z, 16); acc[j].w += __shfl_xor(acc[j].w, 16);
+            acc[j].x += __shfl_xor(acc[j].x, 32); acc[j].y += __shfl_xor(acc[j].y, 32);
+            acc[j].z += __shfl_xor(acc[j].z, 32); acc[j].w += __shfl_xor(acc[j].w, 32);
+        }
+        if (j < n_j && row >= 0 && col_on && (!quad || lrow == 0)) {
             const float bb = a.bias ? a.bias[row] : 0.f;
             float4 r = make_float4(acc[j].x + bb, acc[j].y + bb, acc[j].z + bb, acc[j].w + bb);
             if (a.relu) r = make_float4(r.x > 0.f ? r.x : 0.f, r.y > 0.f ? r.y : 0.f, r.z > 0.f ? r.z : 0.f, r.w > 0.f ? r.w : 0.f);
@@ -1334,22 +1357,35 @@ __global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const
         constexpr int j = decltype(jc)::value;
         z[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (j < n_j) {
-            const int row = row_lane<j>(my_row);
+            const int slot_row = row_lane<j>(my_row);
+            const int row = slot_row < 0 ? -1 : (slot_row & ~kStageQuad);
             if (row >= 0 && col_on) {
                 z[j] = ld4(a.dZ + static_cast<int64_t>(row) * a.lddz + col);
                 if (a.ZM) z[j] = keep_where_positive(z[j], ld4(a.ZM + static_cast<int64_t>(row) * a.ldzm + col));
             }
             const float sum = row16_sum((z[j].x + z[j].y) + (z[j].z + z[j].w));
-            if (row >= 0 && lig == 0) gp[a.partial_db_at + row] = sum;
+            // (the four lane rows of a split row hold the same dZ: the first one reports it)
+            if (row >= 0 && lig == 0 && (!(slot_row & kStageQuad) || lrow == 0)) gp[a.partial_db_at + row] = sum;
         }
     });
+    auto segment = [&](auto jc, int e_lo, int e_hi, int &p0, int &len) {  // as in spmm_staged_kernel
+        constexpr int j = decltype(jc)::value;
+        p0 = row_lane<j>(e_lo);
+        len = row_lane<j>(e_hi) - p0;
+        if (row_lane<j>(my_row) & kStageQuad) {
+            const int from = (len * lrow) >> 2;
+            p0 += from;
+            len = ((len * (lrow + 1)) >> 2) - from;
+        }
+    };
     auto first_chunks = [&](int blk, int e_lo, int e_hi, int (&off)[kStageJ]) {
         static_for(all_j, [&](auto jc) {
             constexpr int j = decltype(jc)::value;
             off[j] = 0;
             if (j < n_j) {
-                const int p0 = row_lane<j>(e_lo);
-                if (lig < row_lane<j>(e_hi) - p0) off[j] = (a.indices[p0 + lig] - blk * kStageRows) * (kStageCols * 4);
+                int p0, len;
+                segment(jc, e_lo, e_hi, p0, len);
+                if (lig < len) off[j] = (a.indices[p0 + lig] - blk * kStageRows) * (kStageCols * 4);
             }
         });
     };
@@ -1385,8 +1421,9 @@ __global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const
         static_for(all_j, [&](auto jc) {
             constexpr int j = decltype(jc)::value;
             if (j < n_j) {
-                const int p0 = row_lane<j>(e0);
-                sddmm_staged_segment(a, lds, cb0, lig, p0, row_lane<j>(e1) - p0, off_cur[j], z[j], gp);
+                int p0, len;
+                segment(jc, e0, e1, p0, len);
+                sddmm_staged_segment(a, lds, cb0, lig, p0, len, off_cur[j], z[j], gp);
             }
         });
         static_for(all_j, [&](auto jc) { off_cur[decltype(jc)::value] = off_next[decltype(jc)::value]; });
@@ -1982,8 +2019,8 @@ bool spmm_vec_ok(const SpmmArgs &a);
 // The staged product pays where a work-group finds several stored entries per operand row it
 // copies into LDS, fills its column tiles, and has enough siblings to occupy the chip; where the
 // segments are long (the gathers then dominate everything else) or the operand is beyond any
-// L2 and evenly used (the gathers of the other kernels then go to memory); and where no single row, which one row
-// of 16 lanes serves alone at about one entry per 60 ns, outlasts the rest of the matrix, which
+// L2 and evenly used (the gathers of the other kernels then go to memory); and where no single lane row's share,
+// served at about one entry per 60 ns, outlasts the rest of the matrix, which
 // the chip's 256 LDS serve at about one entry and tile per 3.3 ns each.
 bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t batch, int64_t nnz)
 {
@@ -1995,10 +2032,14 @@ bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t 
     if (blocks.staged_preferred) return true;
     if (groups < kStageTargetGroups * 3 / 4) return false;
     if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
-    if (static_cast<int64_t>(blocks.staged_longest_row) * 4096 > nnz * n_tiles) return false;
+    if (static_cast<int64_t>(blocks.staged_longest_share) * 4096 > nnz * n_tiles) return false;
     const bool long_segments = nnz >= static_cast<int64_t>(kStageLongSegment) * rows * blocks.staged_cblocks;
     // (a few hot operand rows that take most gathers stay cached on the other paths)
-    const bool big_operand = static_cast<int64_t>(x_rows) * batch * 4 >= kStageBigOperand && blocks.hot_share < 0.5f;
+    // ... and short segments only pay on rows of similar length: on a power-law matrix most (row, block)
+    // pairs hold one entry or none and cost a visit all the same (measured: 1 % power-law at batch 1024,
+    // forward 1.00 -> 1.06 ms, SDDMM 0.99 -> 1.33 ms; 1 % uniform, 1.18 -> 0.76 ms)
+    const bool big_operand = static_cast<int64_t>(x_rows) * batch * 4 >= kStageBigOperand && blocks.hot_share < 0.5f &&
+                             static_cast<int64_t>(blocks.staged_longest_row) * rows <= 4 * nnz;
     return long_segments || big_operand;
 }
 

@@ -208,22 +208,33 @@ def test_staged_ranges_and_segment_bounds(nb):
         lens = np.diff(indptr)
         seen = np.zeros(rows, dtype=np.int32)
         first = []
+        n_quads = 0
         for q in range(ranges):
             used = slot_rows[q] >= 0
             n = int(used.sum())
             assert n >= 1 and used[:n].all() and (ends[q][:, ~used] == 0).all()
-            r = slot_rows[q, :n]
+            quad = (slot_rows[q, :n] & nb.NERVA_STAGE_QUAD) != 0
+            r = slot_rows[q, :n] & ~nb.NERVA_STAGE_QUAD
+            nq = int(quad.sum())
+            assert nq % 4 == 0 and quad[:nq].all()                              # split rows first, four slots each
+            assert (r[:nq].reshape(-1, 4) == r[:nq:4, None]).all()
+            n_quads += nq // 4
+            e = ends[q][:, :n]
+            assert (e[:, :nq].reshape(nb1, -1, 4) == e[:, :nq:4, None]).all()    # ... holding the same bounds
+            keep = np.ones(n, dtype=bool); keep[:nq] = (np.arange(nq) % 4 == 0)
+            r, e = r[keep], e[:, keep]
             seen[r] += 1
-            assert r.max() - r.min() == n - 1                                  # consecutive rows
+            assert r.max() - r.min() == len(r) - 1                              # consecutive rows
             first.append(int(r.min()))
             key = list(zip((-lens[r]).tolist(), r.tolist()))
             assert key == sorted(key)                                           # longest first, ties in row order
-            e = ends[q][:, :n]
+            assert (lens[r[:nq // 4]] >= 256).all()
             assert np.array_equal(e[0], indptr[r]) and np.array_equal(e[-1], indptr[r + 1]) and (np.diff(e, axis=0) >= 0).all()
-            for s in range(0, n, max(1, n // 7)):                               # the cut positions, on a sample of slots
+            for s in range(0, len(r), max(1, len(r) // 7)):                     # the cut positions, on a sample of slots
                 row_cols = indices[indptr[r[s]]:indptr[r[s] + 1]]
                 want = indptr[r[s]] + np.searchsorted(row_cols, np.arange(nb1) * R)
                 assert np.array_equal(e[:, s], want)
+        assert (n_quads > 0) == (rows == 640)                                    # only the power-law case has rows that long
         assert (seen == 1).all() and first == sorted(first)
     indptr, indices = cases[0][2]
     assert nb.nerva_plan_staged_host(700, 1300, indptr, indices, 127)[0].shape[0] == 0      # batch too narrow
