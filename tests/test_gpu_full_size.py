@@ -124,11 +124,28 @@ def test_config4_step_sampled(nb, torch_mod, oracle):
 def test_config5_kernels_sampled(nb, torch_mod, oracle, density, batch):
     """16384 x 16384 with power-law row lengths (rank^-1.2): forward, transposed and sampled products
     alone, checked on sampled rows / columns / entries, the heaviest rows included."""
-    torch = torch_mod
-    n = 16384
-    z = wl.make_zipf_matrix(n, density, seed=11)
+    z = wl.make_zipf_matrix(16384, density, seed=11)
     rn = np.diff(z.indptr)
-    assert rn.max() == n and rn.sum() == z.nnz                   # full rows exist: the huge-row path is exercised
+    assert rn.max() == 16384 and rn.sum() == z.nnz               # full rows exist: the huge-row path is exercised
+    _config5_case(nb, torch_mod, oracle, z, batch)
+
+
+def test_config5_uniform_rows_sampled(nb, torch_mod, oracle):
+    """The same size with uniform rows at 1 % and batch 1024: a 64 MiB operand and short segments, the case in which
+    the products and the SDDMM are staged through LDS because of the operand's size."""
+    n = 16384
+    nnz = wl.round_half_up(0.01 * n * n)
+    indptr, indices = wl.uniform_pattern(n, n, nnz, seed=11)
+    prng = np.random.default_rng(12)
+    z = wl.SparseLayerData(n, n, indptr, indices, prng.standard_normal(nnz, dtype=np.float32),
+                           (prng.standard_normal(n) * 0.5).astype(np.float32), False)
+    assert nb.nerva_plan_staged_host(n, n, indptr, indices, 1024)[0].shape[0] >= 32
+    _config5_case(nb, torch_mod, oracle, z, 1024)
+
+
+def _config5_case(nb, torch, oracle, z, batch):
+    n = z.rows
+    rn = np.diff(z.indptr)
     rng = np.random.default_rng(batch)
     X = rng.standard_normal((n, batch), dtype=np.float32)
     dY = rng.standard_normal((n, batch), dtype=np.float32)
@@ -151,7 +168,7 @@ def test_config5_kernels_sampled(nb, torch_mod, oracle, density, batch):
     close(dbh[sel], dbr, Sdb, what="dbias sampled rows")
     empty = np.nonzero(rn == 0)[0]
     if len(empty):
-        assert np.all(Y[empty] == 0.0)                            # bias is zero here: empty rows give exactly zero
+        assert np.array_equal(Y[empty], np.broadcast_to(z.bias[empty, None], Y[empty].shape))   # empty rows give exactly the bias
     csel = np.sort(rng.choice(n, size=24, replace=False))
     tp, tx, tpos = sub_cols_transposed(z, csel)
     dXr, SdX = oracle.spmm(len(csel), n, tp, tx, z.values[tpos], None, dY, False)
