@@ -749,6 +749,7 @@ __global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmAr
 // applied when the rows are stored, once, after the last block.  Every output element is summed
 // by one lane in one order.
 constexpr int kStageWaves = kWavesPerBlock;
+constexpr int kStageRounds = 2;  // rounds in which a block is copied into LDS (8 / kStageRounds float4 per thread and round)
 static_assert(kStageRangeRows == kStageWaves * 4 * kStageJ && kStageJ <= 16, "a lane row owns kStageJ rows of the range");
 
 template <int... I, typename F>
@@ -947,8 +948,8 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
         const int cb0 = b * kStageRows;
         lds_barrier();  // the previous block's gathers are done
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            constexpr int kHalf = kStageRows / 128;
+        for (int h = 0; h < kStageRounds; ++h) {
+            constexpr int kHalf = kStageRows / (64 * kStageRounds);
             float4 v[kHalf];
 #pragma unroll
             for (int i = 0; i < kHalf; ++i) {
@@ -1397,8 +1398,8 @@ __global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const
         const int cb0 = b * kStageRows;
         lds_barrier();  // the previous block's gathers are done
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            constexpr int kHalf = kStageRows / 128;
+        for (int h = 0; h < kStageRounds; ++h) {
+            constexpr int kHalf = kStageRows / (64 * kStageRounds);
             float4 v[kHalf];
 #pragma unroll
             for (int i = 0; i < kHalf; ++i) {
