@@ -34,11 +34,12 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def build_microbench(verbose: bool = False) -> str:
-    """The stand-alone gather-rate measurement (not part of the library)."""
-    exe = os.path.join(PKG, "microbench_gather")
+def build_microbench(verbose: bool = False, name: str = "microbench_gather") -> str:
+    """A stand-alone gather-rate measurement (not part of the library): microbench_gather (L2 and LDS
+    gathers with per-lane index loads) or microbench_lds_gather (LDS gathers with DPP row broadcasts)."""
+    exe = os.path.join(PKG, name)
     cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, "microbench_gather.hip"), "-o", exe]
+           os.path.join(CSRC, name + ".hip"), "-o", exe]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
@@ -51,3 +52,4 @@ def build_microbench(verbose: bool = False) -> str:
 if __name__ == "__main__":
     print(build_library(verbose=True))
     print(build_microbench(verbose=True))
+    print(build_microbench(verbose=True, name="microbench_lds_gather"))
