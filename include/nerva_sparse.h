@@ -74,8 +74,10 @@ int nerva_validate_csr_host(int32_t rows, int32_t cols, int64_t nnz,
 
 /* The static work partition the kernels use, computed on HOST arrays (needs no GPU; exposed so
  * that it can be checked).  A work-group has NERVA_WAVES_PER_BLOCK waves.  Ordinary rows are
- * grouped by lg = log2(waves that share one row); a work-group serves
- * NERVA_WAVES_PER_BLOCK >> lg of them.  A row with more stored entries than one work-group should
+ * grouped by lg = log2(waves that share one row), the smallest lg that keeps a wave's share at or
+ * below the target; a work-group serves NERVA_WAVES_PER_BLOCK >> lg of them, and a class whose
+ * rows do not fill its last work-group hands that work-group's rows, its longest, to class lg + 1
+ * where that class's own last work-group has room for them (one work-group fewer).  A row with more stored entries than one work-group should
  * take is "huge": it is cut into several work-groups whose partial results a second kernel adds
  * in order.  Outputs (any array may be NULL to get only the counts):
  *   counts_host[4]            {ordinary rows, work-groups, huge rows, huge work-groups}

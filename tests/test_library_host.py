@@ -111,6 +111,8 @@ def _check_plan(nb, indptr, rows):
         assert parts == -(-int(row_nnz[r]) // (2 * cap))
     covered = 0
     prev_lg = 99
+    max_lg = W.bit_length() - 1
+    rows_in_class, promoted = [0] * (max_lg + 1), [0] * (max_lg + 1)
     for info, f, _, _ in blocks[n_huge_blocks:].tolist():
         lg, n = info & 0xFF, info >> 8
         assert 1 <= n <= (W >> lg) and f == covered
@@ -119,10 +121,23 @@ def _check_plan(nb, indptr, rows):
         for r in order[f:f + n]:
             k = int(row_nnz[r])
             assert -(-k // (1 << lg)) <= (target if (1 << lg) < W else 4 * target)   # a full work-group may run 4x over
-            if lg > 0:
-                assert -(-k // (1 << (lg - 1))) > target           # and no more waves than needed
+            rows_in_class[lg] += 1
+            if lg > 0 and -(-k // (1 << (lg - 1))) <= target:     # more waves than its length asks for:
+                promoted[lg] += 1                                  # handed up by a class that could not fill a work-group
         covered += n
     assert covered == len(order)
+    natural = [0] * (max_lg + 1)                                   # the classes by length alone
+    for r in order.tolist():
+        k, lg = int(row_nnz[r]), 0
+        while lg < max_lg and -(-k // (1 << lg)) > target:
+            lg += 1
+        natural[lg] += 1
+    assert len(blocks) - n_huge_blocks <= sum(-(-natural[lg] // (W >> lg)) for lg in range(max_lg + 1))
+    for lg in range(max_lg):
+        assert promoted[lg + 1] <= sum((W >> l) - 1 for l in range(lg + 1))
+        if promoted[lg + 1]:                                       # a class hands up a whole left-over work-group or nothing
+            assert rows_in_class[lg] % (W >> lg) == 0
+    assert promoted[0] == 0
     # inside one class the rows come longest first, ties in row order
     lg_of_slot = np.concatenate([np.full(info >> 8, info & 0xFF) for info in blocks[n_huge_blocks:, 0].tolist()] or [np.zeros(0, int)])
     key = list(zip((-lg_of_slot).tolist(), (-row_nnz[order]).tolist(), order.tolist()))
