@@ -1434,6 +1434,78 @@ __global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const
     }
 }
 
+// SDDMM of a full matrix of few rows (every entry stored, rows <= kFullMaxRows): dZ, a few rows,
+// is copied into LDS once per work-group and X is streamed once, a wave per row of X: the lane
+// multiplies its columns of the X row with the same columns of every dZ row, the row's `rows`
+// products are summed over the wave by the transposing butterfly, and lane i stores (or applies the
+// momentum step to) entry (i, row of X).  The first work-group also sums the rows of dZ for db.
+__global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, const int n_chunks)
+{
+    extern __shared__ float4 dz_s[];  // [rows][n_chunks][kWave]
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int R = a.rows, K = a.x_rows;
+    for (int idx = threadIdx.x; idx < R * n_chunks * kWave; idx += kBlock) {
+        const int i = idx / (n_chunks * kWave), c4 = idx % (n_chunks * kWave);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c4 * 4 < a.batch) {
+            v = ld4(a.dZ + static_cast<int64_t>(i) * a.lddz + c4 * 4);
+            if (a.ZM) v = keep_where_positive(v, ld4(a.ZM + static_cast<int64_t>(i) * a.ldzm + c4 * 4));
+        }
+        dz_s[idx] = v;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && wv < R && (a.db || (a.fused && a.bias))) {
+        float sum = 0.f;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const float4 z = dz_s[(wv * n_chunks + ch) * kWave + lane];
+            sum += (z.x + z.y) + (z.z + z.w);
+        }
+        sum = group_sum<kWave>(sum);
+        if (lane == 0) {
+            if (a.db) a.db[wv] = sum;
+            if (a.fused && a.bias) {
+                float w = a.bias[wv], v = a.bias_velocity[wv];
+                momentum_step(w, v, sum, a.lr, a.momentum, a.nesterov);
+                a.bias[wv] = w;
+                a.bias_velocity[wv] = v;
+            }
+        }
+    }
+    for (int j = blockIdx.x * kWavesPerBlock + wv; j < K; j += gridDim.x * kWavesPerBlock) {
+        float d[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) d[i] = 0.f;
+        const float *xr = a.X + static_cast<int64_t>(j) * a.ldx;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const int col = (ch * kWave + lane) * 4;
+            const float4 x = col < a.batch ? ld4(xr + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int i = 0; i < kFullMaxRows; ++i) {
+                if (i < R) {  // uniform
+                    const float4 z = dz_s[(i * n_chunks + ch) * kWave + lane];
+                    d[i] = fmaf(x.w, z.w, fmaf(x.z, z.z, fmaf(x.y, z.y, fmaf(x.x, z.x, d[i]))));
+                }
+            }
+        }
+        // lane i of each row of 16 lanes gets that row's sum of product i; then the four rows: (0 + 1) + (2 + 3)
+        float g = row16_transpose_sum(d, lane & 15);
+        g += __shfl_xor(g, 16);
+        g += __shfl_xor(g, 32);
+        if (lane < R) {
+            const int64_t p = static_cast<int64_t>(lane) * K + j;
+            if (a.g) a.g[p] = g;
+            if (a.fused) {
+                float w = a.values[p], v = a.velocity[p];
+                momentum_step(w, v, g, a.lr, a.momentum, a.nesterov);
+                a.values[p] = w;
+                a.velocity[p] = v;
+                if (a.values_t) a.values_t[a.pos_t[p]] = w;
+            }
+        }
+    }
+}
+
 // Second pass of the tiled SDDMM: adds the tiles' partial products in tile order, then stores the
 // gradient or applies the fused momentum step (and the mirror scatter); the same for the biases.
 __global__ __launch_bounds__(kEwBlock) void sddmm_finish_kernel(const SddmmArgs a, const int n_tiles)
@@ -2048,6 +2120,14 @@ bool spmm_staged_ok(const SpmmArgs &a) { return spmm_vec_ok(a) && staged_pays(a.
 
 bool sddmm_vec_ok(const SddmmArgs &a);
 
+// a full matrix of few rows whose dZ fits in 64 KiB of LDS
+bool sddmm_full_ok(const SddmmArgs &a)
+{
+    if (a.rows > kFullMaxRows || a.x_rows < 256 || static_cast<int64_t>(a.nnz) != static_cast<int64_t>(a.rows) * a.x_rows) return false;
+    if (a.batch < 64 || a.batch % 4 != 0 || a.skip_products || a.dense || a.loss_cols || !sddmm_vec_ok(a)) return false;
+    return static_cast<int64_t>(a.rows) * ((a.batch + 255) / 256) <= 64;
+}
+
 // the staged SDDMM needs room for one slice of partial products per 64-column tile
 bool sddmm_staged_ok(const SddmmArgs &a)
 {
@@ -2149,14 +2229,16 @@ bool can_pair(const SpmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 4 && a.batch <= 1024 && !a.XM && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && spmm_vec_ok(a) && spmm_offsets_ok(a) &&
-           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && !spmm_staged_ok(a) && sddmm_tile_columns(b) == 0 && !sddmm_staged_ok(b);
+           sddmm_vec_ok(b) && spmm_tile_group(a) == 0 && !spmm_staged_ok(a) && sddmm_tile_columns(b) == 0 &&
+           !sddmm_staged_ok(b) && !sddmm_full_ok(b);
 }
 
 bool can_pair(const SddmmArgs &a, const SddmmArgs &b)
 {
     return a.batch == b.batch && a.batch > 0 && a.batch <= 1024 && a.rows > 0 && b.rows > 0 &&
            a.blocks.n_blocks > 0 && b.blocks.n_blocks > 0 && sddmm_vec_ok(a) && sddmm_vec_ok(b) &&
-           sddmm_tile_columns(a) == 0 && sddmm_tile_columns(b) == 0 && !sddmm_staged_ok(a) && !sddmm_staged_ok(b);
+           sddmm_tile_columns(a) == 0 && sddmm_tile_columns(b) == 0 && !sddmm_staged_ok(a) && !sddmm_staged_ok(b) &&
+           !sddmm_full_ok(a) && !sddmm_full_ok(b);
 }
 
 hipError_t launch_pair(const SpmmArgs &a, const SddmmArgs &b, hipStream_t s)
@@ -2252,6 +2334,13 @@ int sddmm_tile_columns(const SddmmArgs &a)
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
+    if (sddmm_full_ok(a)) {
+        const int n_chunks = (a.batch + 255) / 256;
+        const int groups = (a.x_rows + kWavesPerBlock - 1) / kWavesPerBlock;  // one row of X per wave, up to two rounds of work-groups
+        hipLaunchKernelGGL(full_sddmm_kernel, dim3(groups < 1024 ? groups : 1024), dim3(kBlock),
+                           static_cast<size_t>(a.rows) * n_chunks * kWave * sizeof(float4), s, a, n_chunks);
+        return hipGetLastError();
+    }
     if (sddmm_staged_ok(a)) {
         const int n_tiles = (a.batch + kStageCols - 1) / kStageCols;
         hipLaunchKernelGGL(sddmm_staged_kernel, dim3(n_tiles * a.blocks.staged_ranges), dim3(kStageWaves * kWave), 0, s, a, n_tiles);

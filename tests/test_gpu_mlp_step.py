@@ -79,6 +79,7 @@ CASES = [
     ((64, 40, 10), dict(sparsity=0.5), 260, 2),
     ((40, 30, 20, 10), dict(sparsity=0.999), 16, 2),          # almost every row empty
     ((6000, 300, 10), dict(sparsity=0.98, bias_std=0.1), 200, 2),  # first layer's input beyond an L2: tiled SDDMM + update
+    ((100, 300, 10), dict(layer_nnz=(6000, 3000), bias_std=0.1), 64, 2),  # output layer stores every entry: streaming kernels, fused update
 ]
 
 
