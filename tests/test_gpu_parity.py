@@ -383,6 +383,33 @@ def test_staged_kernels_on_awkward_shapes(nb, torch_mod, oracle, rows, cols, len
     L.close()
 
 
+def test_staged_layer_at_smaller_batches(nb, torch_mod, oracle):
+    """A layer bound for batch 1024 (row ranges chosen for 16 column tiles) run at smaller batches: 512 and 320 still
+    take the staged kernels with fewer tiles, 128 and 100 fall back to the other kernels; same results to the bar."""
+    torch = torch_mod
+    rows, cols = 4096, 2100
+    lay = layer_case(rows, cols, 0.06, seed=77, relu=True)
+    assert nb.nerva_plan_staged_host(rows, cols, lay.indptr, lay.indices, 1024)[0].shape[0] >= 16
+    L = nb.SparseLinear(lay, max_batch=1024)
+    for batch in (1024, 512, 320, 128, 100):
+        rng = np.random.default_rng(batch)
+        X = rng.standard_normal((cols, batch)).astype(np.float32)
+        dY = rng.standard_normal((rows, batch)).astype(np.float32)
+        Xd = nb.to_dense(X); Yd = nb.dense(rows, batch); dYd = nb.to_dense(dY); dXd = nb.dense(cols, batch)
+        g = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((rows,), float("nan"), device="cuda")
+        nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+        nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+        torch.cuda.synchronize()
+        Y, S = oracle.spmm(rows, cols, lay.indptr, lay.indices, lay.values, lay.bias, X, True)
+        close(Yd.cpu().numpy(), Y, S, what=f"Y at batch {batch}")
+        dZ = oracle.relu_backward(dY, Yd.cpu().numpy())
+        dX, SdX = oracle.spmm_t(rows, cols, lay.indptr, lay.indices, lay.values, dZ)
+        close(dXd.cpu().numpy(), dX, SdX, what=f"dX at batch {batch}")
+        gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, lay.indptr, lay.indices, dZ, X)
+        close(g.cpu().numpy(), gr, Sg, what=f"g at batch {batch}"); close(db.cpu().numpy(), dbr, Sdb, what=f"db at batch {batch}")
+    L.close()
+
+
 def test_zipf_matrix_all_row_classes(nb, torch_mod, oracle):
     """Power-law rows (one full row, many empty ones): every share count of the row partition."""
     torch = torch_mod
