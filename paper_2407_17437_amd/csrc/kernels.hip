@@ -669,7 +669,7 @@ __global__ __launch_bounds__(kFullWaves * kWave) void full_rows_kernel(const Spm
     const bool on = col < a.batch;
     const int64_t xoff = on ? col : 0;
     constexpr int KW = kFullSlice / kFullWaves;  // operand rows per wave: all requested before the first use
-    static_assert(KW == 32, "one weight per lane of a half wave");
+    static_assert(KW <= 64 && (KW & (KW - 1)) == 0, "one weight per lane");
     const int k_begin = slice * kFullSlice + wv * KW;
     float4 acc[kFullMaxRows];
     float4 x[KW];
