@@ -135,6 +135,10 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
  * NERVA_STAGE_ROWS in its column indices.  A row with at least max(256, total work / ranges / 32)
  * stored entries takes four slots, from a multiple of 4 on, each marked NERVA_STAGE_QUAD: the four
  * serve a quarter of each of its segments each, so that no single row outlasts its range.
+ * Rows with fewer than min_entries stored entries are left out of the plan (0: every row is in).
+ * A layer whose rows differ widely in length (longest row > 4 x the mean) and which has the second
+ * partition above is bound with min_entries = NERVA_PACK_MAX_LEN + 1: its long rows are staged, its
+ * short rows take the packed path in a second launch.
  * Outputs (arrays may be NULL to get only the counts):
  *   counts_host[2]      {ranges, column blocks nb}; both 0 when no product of this matrix at up
  *                       to max_batch columns would be staged
@@ -148,7 +152,8 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
 enum { NERVA_STAGE_ROWS = 512, NERVA_STAGE_COLS = 64, NERVA_STAGE_MIN_BATCH = 128, NERVA_STAGE_RANGE_ROWS = 512,
        NERVA_STAGE_QUAD = 1 << 30 };
 int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_host, const int32_t *indices_host,
-                           int32_t max_batch, int32_t *slot_rows_host, int32_t *ends_host, int32_t *counts_host);
+                           int32_t max_batch, int32_t min_entries, int32_t *slot_rows_host, int32_t *ends_host,
+                           int32_t *counts_host);
 
 /* ---- layer -------------------------------------------------------------------------
  * sparse_linear_create binds a layer to the caller's pattern, values and bias arrays

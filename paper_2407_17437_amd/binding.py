@@ -56,7 +56,7 @@ def _load() -> ctypes.CDLL:
         "nerva_validate_csr_host": (ctypes.c_int, [i32, i32, i64, vp, vp]),
         "nerva_plan_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp, vp, vp]),
         "nerva_plan_short_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp]),
-        "nerva_plan_staged_host": (ctypes.c_int, [i32, i32, vp, vp, i32, vp, vp, vp]),
+        "nerva_plan_staged_host": (ctypes.c_int, [i32, i32, vp, vp, i32, i32, vp, vp, vp]),
         "nerva_set_partition_mode": (ctypes.c_int, [i32]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
@@ -163,18 +163,18 @@ def nerva_plan_short_rows_host(rows: int, indptr):
     return short[:ns64], int(counts[0]), waves[:counts[1]], int(counts[2])
 
 
-def nerva_plan_staged_host(rows: int, cols: int, indptr, indices, max_batch: int):
+def nerva_plan_staged_host(rows: int, cols: int, indptr, indices, max_batch: int, min_entries: int = 0):
     """Returns (slot_rows[ranges, 512], ends[ranges, blocks + 1, 512]) as numpy int32 arrays; ranges == 0: not staged."""
     import numpy as np
     indptr = np.ascontiguousarray(indptr, dtype=np.int32)
     indices = np.ascontiguousarray(indices, dtype=np.int32)
     counts = np.zeros(2, dtype=np.int32)
-    _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch, None, None, counts.ctypes.data))
+    _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch, min_entries, None, None, counts.ctypes.data))
     ranges, blocks = int(counts[0]), int(counts[1])
     slot_rows = np.zeros((ranges, NERVA_STAGE_RANGE_ROWS), dtype=np.int32)
     ends = np.zeros((ranges, blocks + 1, NERVA_STAGE_RANGE_ROWS), dtype=np.int32)
     if ranges:
-        _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch,
+        _check(lib.nerva_plan_staged_host(rows, cols, indptr.ctypes.data, indices.ctypes.data, max_batch, min_entries,
                                           slot_rows.ctypes.data, ends.ctypes.data, counts.ctypes.data))
     return slot_rows, ends
 

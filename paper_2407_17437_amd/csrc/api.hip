@@ -8,6 +8,7 @@
 #include <new>
 #include <string>
 #include <algorithm>
+#include <climits>
 #include <atomic>
 #include <functional>
 #include <vector>
@@ -161,8 +162,9 @@ struct RowPlan {
     int32_t n_huge_rows() const { return static_cast<int32_t>(huge_rows.size() / 4); }
 };
 
-// skip_upto >= 0: rows with at most that many entries are left out (they go to the packed path).
-RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
+// skip_upto >= 0: rows with at most that many entries are left out (they go to the packed path);
+// only_upto: rows with more entries than that are left out (they go to the staged kernels).
+RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, int32_t only_upto = INT32_MAX)
 {
     RowPlan P;
     const int64_t nnz = indptr[rows];
@@ -182,7 +184,7 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
     const bool row_split_only = g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT;
     for (int32_t i = 0; i < rows; ++i) {
         const int64_t n = indptr[i + 1] - indptr[i];
-        if (n <= skip_upto) {
+        if (n <= skip_upto || n > only_upto) {
             lg_of[i] = -2;
             continue;
         }
@@ -215,7 +217,7 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1)
     // them: one work-group fewer to schedule.  (The 1024 x 3072
     // layer of the paper's MLP at 90 % sparsity has 1023 rows of one class and 1 of the next: 513
     // work-groups on a chip that holds 512 at a time.)
-    if (!row_split_only && skip_upto < 0) {
+    if (!row_split_only && skip_upto < 0 && only_upto == INT32_MAX) {
         std::vector<int32_t> by_len;
         for (int lg = 0; lg < max_lg; ++lg) {
             const int32_t left_over = count[lg] % (kWavesPerBlock >> lg), above = kWavesPerBlock >> (lg + 1);
@@ -331,12 +333,23 @@ struct StagedPlan {
     std::vector<int32_t> groups;  // [ranges]
     int32_t ranges = 0, cblocks = 0;
     int32_t longest_share = 0;    // most entries any one slot serves
+    int32_t n_rows = 0;           // rows the plan covers
+    int64_t nnz = 0;              // and their stored entries
 };
 
-StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const int32_t *indices, int32_t max_batch)
+StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const int32_t *indices, int32_t max_batch,
+                       int32_t min_len = 0)
 {
     StagedPlan H;
-    const int64_t nnz = indptr[rows];
+    // the rows the plan covers: all of them, or those of at least min_len stored entries
+    std::vector<int32_t> covered;
+    int64_t nnz = 0;
+    for (int32_t r = 0; r < rows; ++r)
+        if (indptr[r + 1] - indptr[r] >= min_len) {
+            covered.push_back(r);
+            nnz += indptr[r + 1] - indptr[r];
+        }
+    rows = static_cast<int32_t>(covered.size());  // from here on: rows of the plan, covered[k] their ids
     const bool preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
     if (g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT || max_batch < kStageMinBatch || nnz == 0) return H;
     const int32_t n_tiles = (max_batch + kStageCols - 1) / kStageCols;
@@ -359,7 +372,7 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
         return len + 2 * (len < cblocks ? len : cblocks) + 1;
     };
     int64_t total = 0;
-    for (int32_t r = 0; r < rows; ++r) total += cost(r);
+    for (int32_t k = 0; k < rows; ++k) total += cost(covered[k]);
     // A row of 16 lanes serves a row alone.  A row much longer than a wave's fair share of its range
     // would make that wave the range's critical path: it gets the four lane rows of a wave instead, each a
     // quarter of every segment ("quad": four slots, group-aligned).
@@ -369,10 +382,11 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     {
         int32_t range = 0, in_range = 0;
         int64_t done = 0;
-        for (int32_t r = 0; r < rows; ++r) {
+        for (int32_t k = 0; k < rows; ++k) {
+            const int32_t r = covered[k];
             const bool next = range + 1 < want && done * want >= total * (range + 1);
             if ((next || in_range + slots_of(r) > kStageRangeRows) && in_range > 0) {
-                first_row.push_back(r);
+                first_row.push_back(k);
                 in_range = 0;
             }
             if (next) ++range;
@@ -384,6 +398,8 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     const int32_t ranges = static_cast<int32_t>(first_row.size()) - 1;
     H.ranges = ranges;
     H.cblocks = cblocks;
+    H.n_rows = rows;
+    H.nnz = nnz;
     H.rows.assign(static_cast<size_t>(ranges) * kStageRangeRows, -1);
     H.ends.assign(static_cast<size_t>(ranges) * (cblocks + 1) * kStageRangeRows, 0);
     H.groups.resize(ranges);
@@ -391,7 +407,7 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     for (int32_t q = 0; q < ranges; ++q) {
         const int32_t r0 = first_row[q], n = first_row[q + 1] - r0;
         order.resize(n);
-        for (int32_t i = 0; i < n; ++i) order[i] = r0 + i;
+        for (int32_t i = 0; i < n; ++i) order[i] = covered[r0 + i];
         std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
             return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
         });
@@ -422,11 +438,23 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *
                        int32_t **mem, RowBlocks *plan, hipStream_t s, std::vector<int32_t> &staging)
 {
     const RowPlan P = plan_rows(rows, indptr_host);
-    const StagedPlan H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch);
     int32_t n_short = 0;
     const std::vector<int32_t> short_rows = short_row_table(rows, indptr_host, &n_short);
-    RowPlan Q;
+    int32_t longest_row = 0;
+    for (int32_t r = 0; r < rows; ++r) longest_row = std::max(longest_row, indptr_host[r + 1] - indptr_host[r]);
+    // The staged product serves all rows, or, where the rows differ widely in length and the short
+    // ones have the packed path to go to, the rows beyond that path's length limit only.
+    StagedPlan H;
+    bool staged_partial = false;
+    if (n_short > 0 && n_short < rows && g_partition_mode.load() == NERVA_PARTITION_BALANCED &&
+        static_cast<int64_t>(longest_row) * rows > 4 * static_cast<int64_t>(indptr_host[rows])) {
+        H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch, kPackMaxLen + 1);
+        staged_partial = H.ranges > 0;
+    }
+    if (!staged_partial) H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch);
+    RowPlan Q, Z;
     if (n_short > 0) Q = plan_rows(rows, indptr_host, kPackMaxLen);
+    if (staged_partial) Z = plan_rows(rows, indptr_host, -1, kPackMaxLen);  // the short rows' partition for the SDDMM
     // 16-byte records first so that they stay 16-byte aligned
     staging = P.blocks;
     staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
@@ -436,6 +464,8 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *
     staging.insert(staging.end(), H.ends.begin(), H.ends.end());
     const size_t long_at = staging.size();
     staging.insert(staging.end(), Q.waves.begin(), Q.waves.end());
+    const size_t rest_at = staging.size();
+    staging.insert(staging.end(), Z.waves.begin(), Z.waves.end());
     const size_t short_at = staging.size();
     staging.insert(staging.end(), short_rows.begin(), short_rows.end());
     const size_t order_at = staging.size();
@@ -465,8 +495,12 @@ hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *
     plan->staged_cblocks = H.cblocks;
     plan->staged_preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
     plan->staged_longest_share = H.longest_share;
-    plan->staged_longest_row = 0;
-    for (int32_t r = 0; r < rows; ++r) plan->staged_longest_row = std::max(plan->staged_longest_row, indptr_host[r + 1] - indptr_host[r]);
+    plan->staged_longest_row = longest_row;
+    plan->staged_partial = staged_partial;
+    plan->rest_waves = reinterpret_cast<const int4 *>(*mem + rest_at);
+    plan->n_rest_blocks = Z.n_blocks();
+    plan->staged_row_count = H.n_rows;
+    plan->staged_nnz = static_cast<int32_t>(H.nnz);
     return e;
 }
 
@@ -585,13 +619,14 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
 }
 
 int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_host, const int32_t *indices_host,
-                           int32_t max_batch, int32_t *slot_rows_host, int32_t *ends_host, int32_t *counts_host)
+                           int32_t max_batch, int32_t min_entries, int32_t *slot_rows_host, int32_t *ends_host,
+                           int32_t *counts_host)
 {
-    if (rows <= 0 || cols <= 0 || !indptr_host || !counts_host || (indptr_host[rows] > 0 && !indices_host))
+    if (rows <= 0 || cols <= 0 || min_entries < 0 || !indptr_host || !counts_host || (indptr_host[rows] > 0 && !indices_host))
         return fail(NERVA_ERR_ARGUMENT, "bad argument");
     static_assert(NERVA_STAGE_ROWS == kStageRows && NERVA_STAGE_COLS == kStageCols && NERVA_STAGE_MIN_BATCH == kStageMinBatch &&
                   NERVA_STAGE_RANGE_ROWS == kStageRangeRows && NERVA_STAGE_QUAD == kStageQuad, "header and kernels disagree");
-    const StagedPlan H = plan_staged(rows, cols, indptr_host, indices_host, max_batch);
+    const StagedPlan H = plan_staged(rows, cols, indptr_host, indices_host, max_batch, min_entries);
     counts_host[0] = H.ranges;
     counts_host[1] = H.cblocks;
     if (slot_rows_host && !H.rows.empty()) memcpy(slot_rows_host, H.rows.data(), H.rows.size() * 4);

@@ -50,6 +50,12 @@ struct RowBlocks {
     int32_t staged_cblocks;
     int32_t staged_longest_share;  // most stored entries any one lane row serves
     int32_t staged_longest_row;    // stored entries of the longest row
+    int32_t staged_partial;        // the plan covers the rows of more than kPackMaxLen entries only: the others are
+                                   // short_rows and take the packed kernel
+    int32_t staged_row_count;      // rows the plan covers
+    const int4 *rest_waves;        // with staged_partial: partition of the rows it leaves out, records as in `waves`
+    int32_t n_rest_blocks;         //   (the SDDMM's; the products serve those rows through short_rows)
+    int32_t staged_nnz;            // and their stored entries
     int32_t staged_preferred;      // measurement aid: take the staged kernels wherever they can run
 };
 constexpr int32_t kStageRows = 512;      // operand rows held in LDS at a time

@@ -2095,9 +2095,10 @@ bool spmm_vec_ok(const SpmmArgs &a);
 // L2 and evenly used (the gathers of the other kernels then go to memory); and where no single lane row's share,
 // served at about one entry per 60 ns, outlasts the rest of the matrix, which
 // the chip's 256 LDS serve at about one entry and tile per 3.3 ns each.
-bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t batch, int64_t nnz)
+bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch)
 {
     if (!blocks.staged_rows || batch < kStageMinBatch || batch % 4 != 0) return false;
+    const int64_t rows = blocks.staged_row_count, nnz = blocks.staged_nnz;  // what the plan covers
     const int64_t n_tiles = (batch + kStageCols - 1) / kStageCols;
     if (!blocks.staged_preferred && static_cast<int64_t>(batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
     const int64_t groups = n_tiles * blocks.staged_ranges;
@@ -2116,7 +2117,18 @@ bool staged_pays(const RowBlocks &blocks, int32_t rows, int32_t x_rows, int32_t 
     return long_segments || big_operand;
 }
 
-bool spmm_staged_ok(const SpmmArgs &a) { return spmm_vec_ok(a) && staged_pays(a.blocks, a.rows, a.x_rows, a.batch, a.nnz); }
+int spmm_tile_group(const SpmmArgs &a);
+bool spmm_offsets_ok(const SpmmArgs &a);
+
+bool spmm_staged_ok(const SpmmArgs &a)
+{
+    if (!spmm_vec_ok(a) || !staged_pays(a.blocks, a.x_rows, a.batch)) return false;
+    if (!a.blocks.staged_partial) return true;
+    // the rows the plan leaves out take the packed kernel, which runs inside column tiles
+    const int tg = spmm_tile_group(a);
+    return a.blocks.n_short > 0 && tg != 0 && spmm_offsets_ok(a) &&
+           static_cast<int64_t>(a.blocks.n_short / 64 + 1) * ((a.batch + 31) / 32 + 8) < (1ll << 31);
+}
 
 bool sddmm_vec_ok(const SddmmArgs &a);
 
@@ -2133,7 +2145,7 @@ bool sddmm_staged_ok(const SddmmArgs &a)
 {
     if (!a.partial || a.skip_products || a.dense || a.loss_cols || !sddmm_vec_ok(a)) return false;
     if ((a.batch + kStageCols - 1) / kStageCols > a.partial_tiles) return false;
-    return staged_pays(a.blocks, a.rows, a.x_rows, a.batch, a.nnz);
+    return staged_pays(a.blocks, a.x_rows, a.batch) && (!a.blocks.staged_partial || a.blocks.n_rest_blocks > 0);
 }
 
 bool spmm_offsets_ok(const SpmmArgs &a)
@@ -2286,6 +2298,16 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
             hipLaunchKernelGGL(spmm_staged_kernel<true>, grid, block, 0, s, a, n_tiles);
         else
             hipLaunchKernelGGL(spmm_staged_kernel<false>, grid, block, 0, s, a, n_tiles);
+        if (a.blocks.staged_partial) {  // the short rows: packed, and nothing else in that grid
+            SpmmArgs rest = a;
+            rest.blocks.n_long_blocks = 0;
+            rest.blocks.n_huge_rows = 0;
+            switch (spmm_tile_group(a)) {
+                case 32: return spmm_packed_go<32>(rest, s);
+                case 16: return spmm_packed_go<16>(rest, s);
+                default: return spmm_packed_go<8>(rest, s);
+            }
+        }
         return hipGetLastError();
     }
     if (spmm_vec_ok(a)) {
@@ -2344,6 +2366,15 @@ hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
     if (sddmm_staged_ok(a)) {
         const int n_tiles = (a.batch + kStageCols - 1) / kStageCols;
         hipLaunchKernelGGL(sddmm_staged_kernel, dim3(n_tiles * a.blocks.staged_ranges), dim3(kStageWaves * kWave), 0, s, a, n_tiles);
+        if (a.blocks.staged_partial) {
+            // the rows the plan leaves out: the column-tiled SDDMM on their own partition, same tiles, same partial buffer
+            SddmmArgs rest = a;
+            rest.blocks.waves = a.blocks.rest_waves;
+            rest.blocks.n_blocks = a.blocks.n_rest_blocks;
+            const int spread = n_tiles >= 8;
+            const int64_t ids = (spread ? static_cast<int64_t>((n_tiles + 7) / 8) * 8 : n_tiles) * rest.blocks.n_blocks;
+            hipLaunchKernelGGL((sddmm_tiled_kernel<16, 1, true>), dim3(static_cast<unsigned>(ids)), dim3(kBlock), 0, s, rest, n_tiles, spread);
+        }
         const int64_t work = a.nnz > a.rows ? a.nnz : a.rows;
         hipLaunchKernelGGL(sddmm_finish_kernel, dim3(elementwise_blocks(work)), dim3(kEwBlock), 0, s, a, n_tiles);
         return hipGetLastError();

@@ -383,6 +383,39 @@ def test_staged_kernels_on_awkward_shapes(nb, torch_mod, oracle, rows, cols, len
     L.close()
 
 
+def test_power_law_rows_staged_and_packed_together(nb, torch_mod, oracle):
+    """Power-law rows with thousands of short rows next to a thousand long ones: the forward product stages the
+    rows of more than 128 entries through LDS and serves the others with the packed kernel, two launches writing
+    disjoint rows; with bias, ReLU, empty rows, and the operand mask of the stand-alone backward pass."""
+    torch = torch_mod
+    n, batch = 6144, 1024
+    lens = wl.zipf_row_nnz(n, n, n * n * 3 // 100, 1.2, seed=19)
+    lens[np.arange(7, n, 53)] = 0
+    indptr, indices = wl.pattern_from_row_nnz(lens, n, seed=20)
+    short, ns, _, _ = nb.nerva_plan_short_rows_host(n, indptr)
+    assert ns >= nb.NERVA_PACK_MIN_ROWS and (lens > nb.NERVA_PACK_MAX_LEN).sum() >= 1000
+    assert nb.nerva_plan_staged_host(n, n, indptr, indices, batch, nb.NERVA_PACK_MAX_LEN + 1)[0].shape[0] == 16
+    prng = np.random.default_rng(21)
+    lay = wl.SparseLayerData(n, n, indptr, indices, prng.standard_normal(int(indptr[-1])).astype(np.float32),
+                             (prng.standard_normal(n) * 0.5).astype(np.float32), True)
+    X = prng.standard_normal((n, batch)).astype(np.float32)
+    dY = prng.standard_normal((n, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay, max_batch=batch)
+    Xd = nb.to_dense(X); Yd = nb.dense(n, batch); dYd = nb.to_dense(dY); dXd = nb.dense(n, batch)
+    g = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((n,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(n, n, indptr, indices, lay.values, lay.bias, X, True)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    dZ = oracle.relu_backward(dY, Yd.cpu().numpy())
+    dX, SdX = oracle.spmm_t(n, n, indptr, indices, lay.values, dZ)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    gr, Sg, dbr, Sdb = oracle.sddmm(n, n, indptr, indices, dZ, X)
+    close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+    L.close()
+
+
 def test_staged_layer_at_smaller_batches(nb, torch_mod, oracle):
     """A layer bound for batch 1024 (row ranges chosen for 16 column tiles) run at smaller batches: 512 and 320 still
     take the staged kernels with fewer tiles, 128 and 100 fall back to the other kernels; same results to the bar."""

@@ -258,6 +258,26 @@ def test_staged_ranges_and_segment_bounds(nb):
     assert nb.nerva_plan_staged_host(50, 40, np.zeros(51, dtype=np.int32), np.zeros(0, dtype=np.int32), 256)[0].shape[0] == 0
 
 
+def test_staged_plan_of_the_long_rows_only(nb):
+    """With min_entries the plan covers exactly the rows that long, each once, ranges still in row order."""
+    rows = cols = 6144
+    lens = wl.zipf_row_nnz(rows, cols, rows * cols * 3 // 100, 1.2, seed=19)
+    indptr, indices = wl.pattern_from_row_nnz(lens, cols, seed=20)
+    m = nb.NERVA_PACK_MAX_LEN + 1
+    slot_rows, ends = nb.nerva_plan_staged_host(rows, cols, indptr, indices, 1024, m)
+    assert slot_rows.shape[0] == 16                                              # 256 work-groups at 16 column tiles
+    got = slot_rows[slot_rows >= 0] & ~nb.NERVA_STAGE_QUAD
+    quad = (slot_rows[slot_rows >= 0] & nb.NERVA_STAGE_QUAD) != 0
+    want = np.nonzero(lens >= m)[0]
+    assert np.array_equal(np.unique(got), want) and len(got) == len(want) + 3 * int(quad.sum()) // 4
+    lo = [int((r[r >= 0] & ~nb.NERVA_STAGE_QUAD).min()) for r in slot_rows]
+    hi = [int((r[r >= 0] & ~nb.NERVA_STAGE_QUAD).max()) for r in slot_rows]
+    assert all(h < l for h, l in zip(hi[:-1], lo[1:]))                           # ranges are runs of the covered rows
+    for q, s in [(0, 0), (7, 3), (15, 1)]:
+        r = int(slot_rows[q, s] & ~nb.NERVA_STAGE_QUAD)
+        assert ends[q, 0, s] == indptr[r] and ends[q, -1, s] == indptr[r + 1]
+
+
 def test_row_plan_uniform_and_skewed(nb):
     mlp = wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9)
     for lay in mlp.layers:
