@@ -746,8 +746,11 @@ __global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmAr
 // copy, the segment (row, block) of each of its rows.  A segment's (column, weight) pairs are
 // loaded one per lane, a block ahead, and reach the other lanes of the row through DPP row
 // broadcasts, so the only LDS traffic is the gather itself.  Bias, ReLU and the output mask are
-// applied when the rows are stored, once, after the last block.  Every output element is summed
-// by one lane in one order.
+// applied when the rows are stored, once, after the last block.  A row marked kStageQuad is
+// shared by the four lane rows of a wave, a quarter of each segment each, and their four results
+// are added in a fixed order before the store.  Every output element is summed in one order.
+// With a partial plan (RowBlocks::staged_partial) the kernel serves the long rows only and a
+// second launch, the packed kernel, the others.
 constexpr int kStageWaves = kWavesPerBlock;
 constexpr int kStageRounds = 2;  // rounds in which a block is copied into LDS (8 / kStageRounds float4 per thread and round)
 static_assert(kStageRangeRows == kStageWaves * 4 * kStageJ && kStageJ <= 16, "a lane row owns kStageJ rows of the range");
