@@ -493,8 +493,22 @@ def _random_case(k):
 
 @pytest.mark.parametrize("k", range(48))
 def test_random_shapes_all_three_products(nb, torch_mod, oracle, k):
+    _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged=False)
+
+
+@pytest.mark.parametrize("k", range(100, 124))
+def test_random_shapes_staged_kernels(nb, torch_mod, oracle, k):
+    """The same draw at batches the staged kernels accept, bound in the partition mode that prefers them: whatever
+    the shape and the row lengths, the staged products and the staged SDDMM (or, for an empty matrix, the others)."""
+    _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged=True)
+
+
+def _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged):
     torch = torch_mod
     rows, cols, lens, batch, ld, relu = _random_case(k)
+    if prefer_staged:
+        batch = int(np.random.default_rng(k).choice([128, 132, 192, 256, 320, 1024]))
+        ld = None
     indptr, indices = wl.pattern_from_row_nnz(lens, cols, seed=9100 + k)
     rng = np.random.default_rng(9200 + k)
     lay = wl.SparseLayerData(rows, cols, indptr, indices, rng.standard_normal(int(indptr[-1])).astype(np.float32),
@@ -504,7 +518,14 @@ def test_random_shapes_all_three_products(nb, torch_mod, oracle, k):
         ld = None
     X = rng.standard_normal((cols, batch)).astype(np.float32)
     dY = rng.standard_normal((rows, batch)).astype(np.float32)
-    L = nb.SparseLinear(lay, max_batch=batch)
+    if prefer_staged:
+        batch -= batch % 4                                     # (a cut batch must stay a multiple of 4)
+        X, dY = X[:, :batch], dY[:, :batch]
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
+    try:
+        L = nb.SparseLinear(lay, max_batch=batch)
+    finally:
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_BALANCED)
     Xd = nb.to_dense(X, ld=ld); Yd = nb.dense(rows, batch, ld=ld); dYd = nb.to_dense(dY, ld=ld); dXd = nb.dense(cols, batch, ld=ld)
     g = torch.full((max(lay.nnz, 1),), float("nan"), device="cuda")[:lay.nnz]
     db = torch.full((rows,), float("nan"), device="cuda")
