@@ -123,6 +123,29 @@ def test_stage_parity_staged_products(nb, torch_mod, oracle):
     M.close()
 
 
+def test_stage_parity_power_law_layer(nb, torch_mod, oracle):
+    """A hidden layer with power-law rows at batch 1024: its forward product and its SDDMM + update stage the long
+    rows through LDS and serve the thousands of short rows with the other kernels, in the training step's own
+    launches (fused update in the common finish pass); two steps, every stage against the oracle."""
+    torch = torch_mod
+    n, batch = 6144, 1024
+    mlp = wl.make_mlp((n, n, 10), sparsity=0.97, bias_std=0.1, pattern_seed=102, value_seed=202)
+    lens = wl.zipf_row_nnz(n, n, n * n * 3 // 100, 1.2, seed=19)
+    indptr, indices = wl.pattern_from_row_nnz(lens, n, seed=20)
+    prng = np.random.default_rng(21)
+    mlp.layers[0] = wl.SparseLayerData(n, n, indptr, indices, (prng.standard_normal(int(indptr[-1])) * 0.02).astype(np.float32),
+                                       (prng.standard_normal(n) * 0.1).astype(np.float32), True)
+    assert nb.nerva_plan_staged_host(n, n, indptr, indices, batch, nb.NERVA_PACK_MAX_LEN + 1)[0].shape[0] == 16
+    Xs, Ts = wl.make_batches(n, 10, batch, 2, seed=302)
+    M = nb.MLP(mlp, batch)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, False)
+    M.close()
+
+
 def _digest(*arrays):
     h = hashlib.sha256()
     for a in arrays:
