@@ -165,8 +165,13 @@ int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_hos
  * host to validate it (NERVA_ERR_CSR if not canonical), allocates device memory and
  * synchronises `stream`.  activation: NERVA_ACT_RELU for hidden layers, NERVA_ACT_NONE
  * for the output layer (Section 5.1). `bias` may be NULL (no bias).  max_batch bounds the
- * batch of later calls on this layer (it sizes the scratch rows of huge-row work-groups; a
- * later call with a larger batch returns NERVA_ERR_SHAPE).  */
+ * batch of later calls on this layer (a later call with a larger batch returns
+ * NERVA_ERR_SHAPE) and is the batch the static tables are laid out for: the scratch rows of
+ * huge-row work-groups, the row ranges of the staged products (nerva_plan_staged_host; a much
+ * smaller batch falls back to the other kernels), and, where the SDDMM would run in column
+ * tiles at that batch, a buffer of per-tile partial products: tiles x (nnz + rows) floats, at
+ * most 4 GiB (beyond that the SDDMM stays untiled).  Device memory owned by the layer besides
+ * that buffer: about 20 bytes per stored entry and 16 per row.  */
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz,
                          const int32_t *indptr, const int32_t *indices,
                          float *values, float *bias, int32_t activation, int32_t max_batch,
