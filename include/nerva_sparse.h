@@ -171,7 +171,9 @@ int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_hos
  * smaller batch falls back to the other kernels), and, where the SDDMM would run in column
  * tiles at that batch, a buffer of per-tile partial products: tiles x (nnz + rows) floats, at
  * most 4 GiB (beyond that the SDDMM stays untiled).  Device memory owned by the layer besides
- * that buffer: about 20 bytes per stored entry and 16 per row.  */
+ * that buffer: 16 bytes per stored entry (mirror and position maps) and the partition tables (a
+ * 16-byte record per wave of each partition; with a staged plan 4 bytes per row and block of 512
+ * columns, for the matrix and for its mirror).  */
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz,
                          const int32_t *indptr, const int32_t *indices,
                          float *values, float *bias, int32_t activation, int32_t max_batch,
