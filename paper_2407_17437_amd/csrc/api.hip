@@ -729,7 +729,7 @@ static int build_structures(nerva_layer *l, hipStream_t s)
     if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), h_indices_t.data(), max_batch, rows, h_indptr.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
     if (e == hipSuccess) {
         // room for the column-tiled SDDMM at max_batch columns, if that batch would be tiled
-        const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false);
+        const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false, true);
         int32_t tiles = w > 0 ? (max_batch + w - 1) / w : 0;
         if (l->plan.staged_rows && (max_batch + kStageCols - 1) / kStageCols > tiles) tiles = (max_batch + kStageCols - 1) / kStageCols;
         if (tiles > 0) {

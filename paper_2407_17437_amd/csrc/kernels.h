@@ -158,7 +158,7 @@ struct SddmmArgs {
 // Column-tile width (in columns) the products use when their gathered operand has x_rows rows and
 // does not fit an L2; 0: no tiling.  Shared by the kernels' dispatch and by the sizing of the
 // SDDMM partial buffer when a layer is created.
-int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked);
+int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked, bool for_sddmm = false);
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
 
 // Two independent launches in one grid (both on the 16-byte path, batch <= 1024, one column tile).

@@ -2219,7 +2219,7 @@ hipError_t sddmm_pair_go(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
 
 int sddmm_tile_columns(const SddmmArgs &a);
 
-int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked)
+int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked, bool for_sddmm)
 {
     const int64_t budget = (masked ? 5 : 10) * (1 << 18);  // 2.5 MiB (half of it with a mask operand)
     const int64_t row_bytes = static_cast<int64_t>(x_rows) * 4;
@@ -2227,7 +2227,9 @@ int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float
     // A matrix of few rows is in flight as a whole: its rows gather the same operand rows at about
     // the same time, which serves them from cache without tiling (measured on a dense 10 x 8192 layer).
     if (rows <= 256) return 0;
-    if (row_bytes * 128 <= budget && batch > 128) return 128;
+    // (the SDDMM, whose second operand is a row per matrix row and not a gather, still gains from 128-column
+    // tiles when they fill a whole L2: config 4's 8192-row operand, 120 -> 113 us, where the product loses 7 %)
+    if (row_bytes * 128 <= (for_sddmm ? (4ll << 20) : budget) && batch > 128) return 128;
     if (row_bytes * 64 <= budget && batch > 64) return 64;
     // Narrower tiles multiply the per-wave set-up (one pass over the row partition per tile) by 32 or
     // more.  Measured on 16384^2 matrices at batch 1024: they pay from about 128 entries per row on
@@ -2348,7 +2350,7 @@ int sddmm_tile_columns(const SddmmArgs &a)
     if (!a.partial || a.skip_products || a.dense || !sddmm_vec_ok(a)) return 0;  // (the finish pass does not know an entry's row)
     // the operand rows an entry gathers are named by its column index: the matrix's own partition
     // carries the share of the most referenced ones
-    const int w = tile_columns(a.x_rows, a.batch, a.nnz, a.rows, a.blocks.hot_share, false);
+    const int w = tile_columns(a.x_rows, a.batch, a.nnz, a.rows, a.blocks.hot_share, false, true);
     if (w == 0) return 0;
     const int n_tiles = (a.batch + w - 1) / w;
     if (n_tiles > a.partial_tiles) return 0;
