@@ -66,7 +66,9 @@ constexpr int32_t kStageRangeRows = 512; // rows per work-group: 16 waves x 4 la
 constexpr int32_t kStageMinBatch = 128;  // narrower batches never take the staged product
 constexpr int32_t kStageTargetGroups = 256;  // work-groups wanted at max_batch (one per compute unit)
 constexpr float kStageMinReuse = 2.f;    // stored entries per staged operand row and work-group, at least
-constexpr int32_t kStageLongSegment = 16;  // mean entries per segment from which staging pays whatever the operand's size
+constexpr int32_t kStageLongSegment = 10;       // mean entries per segment from which staging pays whatever the operand's size: products
+constexpr int32_t kStageLongSegmentSddmm = 20;  // ... and the SDDMM (measured on 8192 x 8192 uniform at batch 1024, 1 / 2 / 3 / 5 % density:
+                                                // products 142 / 301 / 407 / - us against 235 / 278 / 349 / 442 staged, SDDMM 162 / 289 / 407 / - against 317 / 369 / 460 / 584)
 constexpr int64_t kStageBigOperand = 48ll << 20;  // operand bytes no set of L2s holds: staging pays for short segments too
 constexpr int32_t kHotRows = 1024;
 constexpr int32_t kHugeFlag = 0x40000000;

@@ -2098,9 +2098,11 @@ bool spmm_vec_ok(const SpmmArgs &a);
 // L2 and evenly used (the gathers of the other kernels then go to memory); and where no single lane row's share,
 // served at about one entry per 60 ns, outlasts the rest of the matrix, which
 // the chip's 256 LDS serve at about one entry and tile per 3.3 ns each.
-bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch)
+bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch, int32_t long_segment)
 {
     if (!blocks.staged_rows || batch < kStageMinBatch || batch % 4 != 0) return false;
+    // (an operand of a few rows is in cache wherever it is gathered from: config 4's 8192 x 10 mirror, 21 against 28 us)
+    if (x_rows < kStageRows / 2 && !blocks.staged_preferred) return false;
     const int64_t rows = blocks.staged_row_count, nnz = blocks.staged_nnz;  // what the plan covers
     const int64_t n_tiles = (batch + kStageCols - 1) / kStageCols;
     if (!blocks.staged_preferred && static_cast<int64_t>(batch) * 5 < n_tiles * kStageCols * 4) return false;  // a fifth or more of the tiles' columns idle
@@ -2110,7 +2112,7 @@ bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch)
     if (groups < kStageTargetGroups * 3 / 4) return false;
     if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
     if (static_cast<int64_t>(blocks.staged_longest_share) * 4096 > nnz * n_tiles) return false;
-    const bool long_segments = nnz >= static_cast<int64_t>(kStageLongSegment) * rows * blocks.staged_cblocks;
+    const bool long_segments = nnz >= static_cast<int64_t>(long_segment) * rows * blocks.staged_cblocks;
     // (a few hot operand rows that take most gathers stay cached on the other paths)
     // ... and short segments only pay on rows of similar length: on a power-law matrix most (row, block)
     // pairs hold one entry or none and cost a visit all the same (measured: 1 % power-law at batch 1024,
@@ -2125,7 +2127,7 @@ bool spmm_offsets_ok(const SpmmArgs &a);
 
 bool spmm_staged_ok(const SpmmArgs &a)
 {
-    if (!spmm_vec_ok(a) || !staged_pays(a.blocks, a.x_rows, a.batch)) return false;
+    if (!spmm_vec_ok(a) || !staged_pays(a.blocks, a.x_rows, a.batch, kStageLongSegment)) return false;
     if (!a.blocks.staged_partial) return true;
     // the rows the plan leaves out take the packed kernel, which runs inside column tiles
     const int tg = spmm_tile_group(a);
@@ -2148,7 +2150,7 @@ bool sddmm_staged_ok(const SddmmArgs &a)
 {
     if (!a.partial || a.skip_products || a.dense || a.loss_cols || !sddmm_vec_ok(a)) return false;
     if ((a.batch + kStageCols - 1) / kStageCols > a.partial_tiles) return false;
-    return staged_pays(a.blocks, a.x_rows, a.batch) && (!a.blocks.staged_partial || a.blocks.n_rest_blocks > 0);
+    return staged_pays(a.blocks, a.x_rows, a.batch, kStageLongSegmentSddmm) && (!a.blocks.staged_partial || a.blocks.n_rest_blocks > 0);
 }
 
 bool spmm_offsets_ok(const SpmmArgs &a)

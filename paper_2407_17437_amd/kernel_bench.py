@@ -30,6 +30,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, nargs="+", default=[128, 1024])
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--uniform", action="store_true", help="uniform random pattern instead of power-law rows")
+    ap.add_argument("--prefer-staged", action="store_true",
+                    help="measurement aid: staged (LDS) kernels wherever they can run, not only where the library expects them to pay")
     ap.add_argument("--row-split", action="store_true",
                     help="build the layers with plain row splitting (one wave per row) instead of the balanced partition")
     args = ap.parse_args()
@@ -42,6 +44,8 @@ def main() -> int:
     assert torch.cuda.is_available()
     if args.row_split:
         nb.nerva_set_partition_mode(nb.NERVA_PARTITION_ROW_SPLIT)
+    if args.prefer_staged:
+        nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
     n = args.n
     flush = torch.empty(768 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")   # larger than every cache
 
@@ -92,7 +96,7 @@ def main() -> int:
                 print(json.dumps({
                     "kernel": name, "n": n, "density": dens, "nnz": nnz, "batch": batch,
                     "rows": "uniform" if args.uniform else "zipf1.2",
-                    "partition": "row-split" if args.row_split else "balanced", "max_row": int(rn.max()), "median_row": float(np.median(rn)),
+                    "partition": "row-split" if args.row_split else ("prefer-staged" if args.prefer_staged else "balanced"), "max_row": int(rn.max()), "median_row": float(np.median(rn)),
                     "us_cold": round(cold, 2), "us_back_to_back": round(warm, 2), "algorithmic_MB": round(byt / 1e6, 2),
                     "gflop": round(2.0 * nnz * batch / 1e9, 3),
                     "gbs_cold": round(byt / cold / 1e3, 1), "frac_hbm_cold": round(byt / cold / 1e3 / HBM_PEAK_GBS, 4),
