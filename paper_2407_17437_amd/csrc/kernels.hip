@@ -2109,7 +2109,9 @@ bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch, int32_t
     const int64_t groups = n_tiles * blocks.staged_ranges;
     if (groups >= (1ll << 31)) return false;
     if (blocks.staged_preferred) return true;
-    if (groups < kStageTargetGroups * 3 / 4) return false;
+    // (three quarters of the compute units busy at least; half where the plan covers a matrix's long rows only,
+    // whose alternative is gathering from memory: 580 long rows of the 0.3 % power-law matrix make 144 work-groups)
+    if (groups < (blocks.staged_partial ? kStageTargetGroups / 2 : kStageTargetGroups * 3 / 4)) return false;
     if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
     if (static_cast<int64_t>(blocks.staged_longest_share) * 4096 > nnz * n_tiles) return false;
     const bool long_segments = nnz >= static_cast<int64_t>(long_segment) * rows * blocks.staged_cblocks;
@@ -2128,9 +2130,12 @@ bool spmm_offsets_ok(const SpmmArgs &a);
 bool spmm_staged_ok(const SpmmArgs &a)
 {
     if (!spmm_vec_ok(a) || !staged_pays(a.blocks, a.x_rows, a.batch, kStageLongSegment)) return false;
-    if (!a.blocks.staged_partial) return true;
-    // the rows the plan leaves out take the packed kernel, which runs inside column tiles
-    const int tg = spmm_tile_group(a);
+    return !a.blocks.staged_partial || a.blocks.n_rest_blocks > 0;  // (the rows the plan leaves out need a partition of their own)
+}
+
+// whether the rows a partial plan leaves out take the packed kernel, which runs inside column tiles only
+bool staged_rest_packed(const SpmmArgs &a, int tg)
+{
     return a.blocks.n_short > 0 && tg != 0 && spmm_offsets_ok(a) &&
            static_cast<int64_t>(a.blocks.n_short / 64 + 1) * ((a.batch + 31) / 32 + 8) < (1ll << 31);
 }
@@ -2305,15 +2310,25 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
             hipLaunchKernelGGL(spmm_staged_kernel<true>, grid, block, 0, s, a, n_tiles);
         else
             hipLaunchKernelGGL(spmm_staged_kernel<false>, grid, block, 0, s, a, n_tiles);
-        if (a.blocks.staged_partial) {  // the short rows: packed, and nothing else in that grid
+        if (a.blocks.staged_partial) {
+            // the short rows: packed where that path runs (inside column tiles), and nothing else in that grid;
+            // otherwise whatever kernel the batch asks for, on the short rows' own partition
             SpmmArgs rest = a;
-            rest.blocks.n_long_blocks = 0;
             rest.blocks.n_huge_rows = 0;
-            switch (spmm_tile_group(a)) {
-                case 32: return spmm_packed_go<32>(rest, s);
-                case 16: return spmm_packed_go<16>(rest, s);
-                default: return spmm_packed_go<8>(rest, s);
+            const int tg = spmm_tile_group(a);
+            if (staged_rest_packed(a, tg)) {
+                rest.blocks.n_long_blocks = 0;
+                switch (tg) {
+                    case 32: return spmm_packed_go<32>(rest, s);
+                    case 16: return spmm_packed_go<16>(rest, s);
+                    default: return spmm_packed_go<8>(rest, s);
+                }
             }
+            rest.blocks.staged_rows = nullptr;
+            rest.blocks.n_short = 0;
+            rest.blocks.waves = a.blocks.rest_waves;
+            rest.blocks.n_blocks = a.blocks.n_rest_blocks;
+            return launch_spmm(rest, s);
         }
         return hipGetLastError();
     }

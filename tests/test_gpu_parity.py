@@ -383,6 +383,38 @@ def test_staged_kernels_on_awkward_shapes(nb, torch_mod, oracle, rows, cols, len
     L.close()
 
 
+def test_power_law_rows_staged_and_ordinary_kernels_together(nb, torch_mod, oracle):
+    """The same split on an operand small enough to stay untiled (600 rows x 1024 columns): without column tiles the
+    packed path does not run, so the short rows of the forward product go through the wide kernel on a partition of
+    their own, next to the staged long rows; the SDDMM splits likewise; the mirror (600 long rows) is not staged."""
+    torch = torch_mod
+    rows, cols, batch = 8192, 600, 1024
+    lens = wl.zipf_row_nnz(rows, cols, rows * cols * 12 // 100, 1.2, seed=31)
+    lens[np.arange(3, rows, 61)] = 0
+    indptr, indices = wl.pattern_from_row_nnz(lens, cols, seed=32)
+    assert (lens <= nb.NERVA_PACK_MAX_LEN).sum() >= nb.NERVA_PACK_MIN_ROWS
+    assert nb.nerva_plan_staged_host(rows, cols, indptr, indices, batch, nb.NERVA_PACK_MAX_LEN + 1)[0].shape[0] >= 8
+    prng = np.random.default_rng(33)
+    lay = wl.SparseLayerData(rows, cols, indptr, indices, prng.standard_normal(int(indptr[-1])).astype(np.float32),
+                             (prng.standard_normal(rows) * 0.5).astype(np.float32), True)
+    X = prng.standard_normal((cols, batch)).astype(np.float32)
+    dY = prng.standard_normal((rows, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay, max_batch=batch)
+    Xd = nb.to_dense(X); Yd = nb.dense(rows, batch); dYd = nb.to_dense(dY); dXd = nb.dense(cols, batch)
+    g = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, Yd, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(rows, cols, indptr, indices, lay.values, lay.bias, X, True)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    dZ = oracle.relu_backward(dY, Yd.cpu().numpy())
+    dX, SdX = oracle.spmm_t(rows, cols, indptr, indices, lay.values, dZ)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, indptr, indices, dZ, X)
+    close(g.cpu().numpy(), gr, Sg, what="g"); close(db.cpu().numpy(), dbr, Sdb, what="db")
+    L.close()
+
+
 def test_power_law_rows_staged_and_packed_together(nb, torch_mod, oracle):
     """Power-law rows with thousands of short rows next to a thousand long ones: the forward product stages the
     rows of more than 128 entries through LDS and serves the others with the packed kernel, two launches writing
