@@ -138,7 +138,9 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
  * Rows with fewer than min_entries stored entries are left out of the plan (0: every row is in).
  * A layer whose rows differ widely in length (longest row > 4 x the mean) and which has the second
  * partition above is bound with min_entries = NERVA_PACK_MAX_LEN + 1: its long rows are staged, its
- * short rows take the packed path in a second launch.
+ * short rows take the packed path (the other kernels on a partition of their own where the
+ * operand is not column-tiled; likewise the SDDMM) in a second launch.  With min_entries > 0 the
+ * ranges are runs of consecutive covered rows.  The SDDMM S = A B^T uses the same plan of S.
  * Outputs (arrays may be NULL to get only the counts):
  *   counts_host[2]      {ranges, column blocks nb}; both 0 when no product of this matrix at up
  *                       to max_batch columns would be staged
