@@ -49,6 +49,25 @@ MUTATIONS = [
      "dZ[l] = relu_backward(dA[l], A[l], dtype)", "dZ[l] = np.asarray(dA[l], dtype=dtype)"),
     ("weight gradient from the layer's output instead of its input", INIT,
      "inp = X if l == 0 else A[l - 1]", "inp = X if l == 0 else A[l - 1] * 0 + 1"),
+    # normalisers (the sums of |terms| that set the parity tolerances)
+    ("normaliser of the update drops |lr|", INC,
+     "double sg = fabs(lr) * (Sg ? Sg[p] : fabs((double)g[p]));", "double sg = (Sg ? Sg[p] : fabs((double)g[p]));"),
+    ("normaliser of the velocity taken from the new velocity", INC,
+     "double sv = fabs(mu * (double)v[p]) + sg;", "double sv = fabs(vn) + sg;"),
+    ("normaliser of the velocity drops the momentum term", INC,
+     "double sv = fabs(mu * (double)v[p]) + sg;", "double sv = sg;"),
+    ("Nesterov weight normaliser drops the momentum factor", INC,
+     "sw = fabs((double)w[p]) + fabs(mu) * sv + sg;", "sw = fabs((double)w[p]) + sv + sg;"),
+    ("weight normaliser drops |w|", INC,
+     "sw = fabs((double)w[p]) + sv;", "sw = sv;"),
+    ("loss normaliser doubled", INC, "out[1] = sloss / (double)batch;", "out[1] = 2.0 * sloss / (double)batch;"),
+    ("loss normaliser not averaged over the batch", INC, "out[1] = sloss / (double)batch;", "out[1] = sloss;"),
+    ("loss normaliser is |lse - z_t|", INC, "sloss += fabs(lse) + fabs(zt);", "sloss += fabs(lse - zt);"),
+    ("gradient normaliser of dZ_L subtracts the one-hot term", INC,
+     "SdZ[(int64_t)i * batch + c] = (pr + hot) / (double)batch;", "SdZ[(int64_t)i * batch + c] = (pr - hot) / (double)batch;"),
+    ("step hands the update no gradient normaliser", INIT,
+     'momentum(st["values"], st["vel_w"], g[l], lr, mu, Sg[l], dtype, nesterov)',
+     'momentum(st["values"], st["vel_w"], g[l], lr, mu, None, dtype, nesterov)'),
     ("biases never updated", INIT,
      'momentum(st["bias"], st["vel_b"], db[l], lr, mu, Sdb[l], dtype, nesterov)',
      'momentum(st["bias"], st["vel_b"], 0 * db[l], lr, mu, Sdb[l], dtype, nesterov)'),

@@ -403,3 +403,100 @@ def test_training_loop_matches_masked_dense_autograd(oracle, nesterov):
             got = np.array([W[i, lay.indices[p]] for i in range(lay.rows) for p in range(lay.indptr[i], lay.indptr[i + 1])])
             np.testing.assert_allclose(state[l]["values"], got, rtol=1e-10, atol=1e-13, err_msg=f"values[{l}] after step {t}")
             np.testing.assert_allclose(state[l]["bias"], bs[l].detach().numpy(), rtol=1e-10, atol=1e-13, err_msg=f"bias[{l}] after step {t}")
+
+
+# ---- the normalisers S = sum of |terms| that set every tolerance of the parity tests ------------------
+# Each one is recomputed here from loops written out in the test, on inputs with non-zero velocity and
+# mixed signs, and compared exactly (to fp64 rounding of a different summation order).
+
+def test_loss_normaliser_is_mean_of_abs_lse_plus_abs_target_logit(oracle):
+    rng = np.random.default_rng(91)
+    C, B = 7, 9
+    Z = rng.standard_normal((C, B)) * 4.0 - 1.0      # logits of both signs, some lse negative
+    Z[:, 0] -= 9.0                                   # a column whose log-sum-exp is negative
+    labels = rng.integers(0, C, size=B)
+    loss, S_loss, dZ, SdZ = oracle.softmax_ce(Z, labels, np.float64)
+    s = 0.0; l = 0.0
+    for c in range(B):
+        m = max(Z[i, c] for i in range(C))
+        lse = m + math.log(sum(math.exp(Z[i, c] - m) for i in range(C)))
+        l += lse - Z[labels[c], c]
+        s += abs(lse) + abs(Z[labels[c], c])
+        for i in range(C):
+            p = math.exp(Z[i, c] - lse); hot = 1.0 if i == labels[c] else 0.0
+            assert SdZ[i, c] == pytest.approx((p + hot) / B, rel=1e-13)
+            assert dZ[i, c] == pytest.approx((p - hot) / B, rel=1e-12, abs=1e-17)
+    assert any(max(Z[:, c]) + math.log(np.exp(Z[:, c] - max(Z[:, c])).sum()) < 0 for c in range(B))
+    assert loss == pytest.approx(l / B, rel=1e-13)
+    assert S_loss == pytest.approx(s / B, rel=1e-13)
+    assert S_loss > abs(loss)                        # |lse| + |z_t| dominates |lse - z_t|
+
+
+@pytest.mark.parametrize("with_Sg", [False, True])
+@pytest.mark.parametrize("lr", [0.05, -0.05])
+def test_momentum_normalisers_plain(oracle, with_Sg, lr):
+    """Sv = mu |v| + |lr| Sg and Sw = |w| + Sv, with Sg = |g| when no normaliser of g is handed in."""
+    rng = np.random.default_rng(92)
+    n, mu = 40, 0.9
+    w0, v0, g = rng.standard_normal(n), rng.standard_normal(n), rng.standard_normal(n)
+    Sg = np.abs(g) * (1.0 + rng.random(n) * 3.0) if with_Sg else None    # Sg >= |g|, as a sum of |terms| is
+    w, v, Sw, Sv = oracle.momentum(w0, v0, g, lr, mu, Sg=Sg, dtype=np.float64)
+    for k in range(n):
+        sg = abs(lr) * (Sg[k] if with_Sg else abs(g[k]))
+        sv = mu * abs(v0[k]) + sg
+        assert Sv[k] == pytest.approx(sv, rel=1e-14)
+        assert Sw[k] == pytest.approx(abs(w0[k]) + sv, rel=1e-14)
+        assert v[k] == pytest.approx(mu * v0[k] - lr * g[k], rel=1e-13, abs=1e-16)
+        assert w[k] == pytest.approx(w0[k] + mu * v0[k] - lr * g[k], rel=1e-13, abs=1e-16)
+    # the normalisers are those of the starting point: they do not follow the new velocity
+    assert not np.allclose(Sv, np.abs(v))
+
+
+@pytest.mark.parametrize("with_Sg", [False, True])
+def test_momentum_normalisers_nesterov_with_velocity(oracle, with_Sg):
+    """Nesterov, expanded: w' = w + mu^2 v - (1 + mu) lr g, so Sw = |w| + mu^2 |v| + (1 + mu) lr Sg; Sv as plain."""
+    rng = np.random.default_rng(93)
+    n, mu, lr = 40, 0.8, 0.07
+    w0, v0, g = rng.standard_normal(n), rng.standard_normal(n), rng.standard_normal(n)
+    Sg = np.abs(g) * (1.0 + rng.random(n) * 3.0) if with_Sg else None
+    w, v, Sw, Sv = oracle.momentum(w0, v0, g, lr, mu, Sg=Sg, dtype=np.float64, nesterov=True)
+    for k in range(n):
+        sg = lr * (Sg[k] if with_Sg else abs(g[k]))
+        assert Sv[k] == pytest.approx(mu * abs(v0[k]) + sg, rel=1e-14)
+        assert Sw[k] == pytest.approx(abs(w0[k]) + mu * mu * abs(v0[k]) + (1.0 + mu) * sg, rel=1e-14)
+        assert w[k] == pytest.approx(w0[k] + mu * mu * v0[k] - (1.0 + mu) * lr * g[k], rel=1e-13, abs=1e-16)
+
+
+@pytest.mark.parametrize("nesterov", [False, True])
+def test_step_normalisers_follow_the_gradient_normalisers(oracle, nesterov):
+    """The normalisers a whole step reports for the new weights, velocities and biases are built from the
+    step's own Sg / Sdb (sums over the batch of |dZ x|, |dZ|) and from the state the step started with."""
+    mlp = _tiny_mlp()
+    rng = np.random.default_rng(94)
+    B, lr, mu = 6, 0.2, 0.9
+    state = oracle.new_state(mlp.layers, np.float64)
+    for t in range(2):      # the second step starts with non-zero velocities
+        X = rng.standard_normal((7, B)); labels = rng.integers(0, 3, size=B)
+        before = [{k: np.array(st[k]) for k in ("values", "bias", "vel_w", "vel_b")} for st in state]
+        out = oracle.mlp_step(state, X, labels, lr, mu, np.float64, nesterov=nesterov)
+        for l, lay in enumerate(mlp.layers):
+            inp = X if l == 0 else out["A"][l - 1]
+            p = 0
+            for i in range(lay.rows):
+                sdb = sum(abs(out["dZ"][l][i, c]) for c in range(B))
+                assert out["Sdb"][l][i] == pytest.approx(sdb, rel=1e-13)
+                svb = mu * abs(before[l]["vel_b"][i]) + lr * sdb
+                assert out["Sbv"][l][i] == pytest.approx(svb, rel=1e-13)
+                swb = abs(before[l]["bias"][i]) + (mu * svb + lr * sdb if nesterov else svb)
+                assert out["Sbw"][l][i] == pytest.approx(swb, rel=1e-13)
+                for q in range(lay.indptr[i], lay.indptr[i + 1]):
+                    sg = sum(abs(out["dZ"][l][i, c] * inp[lay.indices[q], c]) for c in range(B))
+                    assert out["Sg"][l][q] == pytest.approx(sg, rel=1e-13)
+                    sv = mu * abs(before[l]["vel_w"][q]) + lr * sg
+                    assert out["Sv"][l][q] == pytest.approx(sv, rel=1e-13)
+                    sw = abs(before[l]["values"][q]) + (mu * sv + lr * sg if nesterov else sv)
+                    assert out["Sw"][l][q] == pytest.approx(sw, rel=1e-13)
+                    p += 1
+            assert p == lay.nnz
+        if t == 1:
+            assert all(np.abs(b["vel_w"]).max() > 0 for b in before)
