@@ -97,18 +97,6 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
                          int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host,
                          int32_t *counts_host);
 
-/* Measurement aid: which partition later sparse_linear_create / sparse_linear_rebind /
- * nerva_plan_*_host calls build (process-wide; layers already bound keep theirs).
- * NERVA_PARTITION_BALANCED (default): the partition described above.  NERVA_PARTITION_ROW_SPLIT:
- * plain row splitting -- one wave per row whatever its length, no huge rows, no packed short
- * rows, no staged products -- so that the balanced partition can be timed against it on the same
- * matrix.  NERVA_PARTITION_PREFER_STAGED: the balanced partition, but the staged products and the
- * staged SDDMM (see nerva_plan_staged_host) run wherever they can (batch of at least
- * NERVA_STAGE_MIN_BATCH columns, a multiple of 4), also where the library's own rule expects them
- * to be slower. */
-enum { NERVA_PARTITION_BALANCED = 0, NERVA_PARTITION_ROW_SPLIT = 1, NERVA_PARTITION_PREFER_STAGED = 2 };
-int nerva_set_partition_mode(int32_t mode);
-
 /* The second partition, which the products Y = S X and Y = S^T X use on matrices with many short
  * rows (HOST arrays, needs no GPU).  Rows of at most NERVA_PACK_MAX_LEN stored entries are listed
  * longest first (ties in row order) and are served one row per group of lanes, several rows per
@@ -214,14 +202,20 @@ int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
 int sparse_linear_enable_dense(nerva_layer *layer, void *stream);
 
 /* The library keeps derived copies of values[] (the mirror's values, the dense copies above) and
- * updates them whenever it updates values[].  After the CALLER has written values[] (loaded
- * weights, a prune-and-grow step without rebind), this call brings the copies up to date;
- * mlp_train_step and mlp_forward rely on them.  sparse_linear_forward / sparse_linear_backward
- * refresh what they read on every call and do not need it. */
+ * updates them whenever it updates values[], with one exception: mlp_train_step leaves the mirror's
+ * values of the MLP's FIRST layer alone, because no product of the step reads them (the first layer's
+ * input gradient is not computed).  The layer remembers that: the next call that reads them -- a
+ * training step of an MLP that has the layer at a later position, sparse_linear_backward, this call --
+ * refreshes them first.  After the CALLER has written values[] (loaded weights, a prune-and-grow
+ * step without rebind), this call brings all copies up to date; mlp_train_step and mlp_forward rely
+ * on them.  sparse_linear_forward / sparse_linear_backward refresh what they read on every call and
+ * do not need it. */
 int sparse_linear_sync_values(nerva_layer *layer, void *stream);
 
 /* Device pointers of the mirror, for inspection: indptr_t[cols+1], indices_t[nnz],
- * values_t[nnz], perm[nnz] (mirror position -> CSR position). Any output may be NULL. */
+ * values_t[nnz], perm[nnz] (mirror position -> CSR position). Any output may be NULL.
+ * values_t of a layer that mlp_train_step has trained as an MLP's first layer may be behind
+ * values[] (see sparse_linear_sync_values, which brings it up to date). */
 int sparse_linear_mirror(const nerva_layer *layer, const int32_t **indptr_t,
                          const int32_t **indices_t, const float **values_t,
                          const int32_t **perm);
@@ -335,25 +329,6 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
  * workspace at the A_L offset. */
 int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch,
                 void *workspace, size_t workspace_bytes, void *stream);
-
-/* Per-kernel timing of mlp_train_step with HIP events, for benchmarks.  After
- * mlp_profile_enable(mlp, max_steps > 0) the next max_steps training steps record an event
- * before every kernel launch and one after the last, on the step's stream (events are created
- * on the fly: a profiled step allocates, must not be captured in a graph, and runs slower than
- * a plain one).  mlp_profile_read waits for the recorded events and returns, per launch slot of
- * a step (in launch order), the elapsed milliseconds from its event to the next one, summed over
- * the recorded steps (the launches of a step run back to back, so the slots add up to the step); the slots keep their
- * meaning until the next mlp_profile_enable.  mlp_profile_enable(mlp, 0) switches timing off
- * and frees the events.  Slot names look like "spmm_forward[0]", "sddmm_update[2]".
- *   n_slots_host, steps_host: HOST int32; ms_sum_host: HOST double[max_slots]. */
-int mlp_profile_enable(nerva_mlp *mlp, int32_t max_steps);
-int mlp_profile_read(nerva_mlp *mlp, int32_t max_slots, int32_t *n_slots_host,
-                     double *ms_sum_host, int32_t *steps_host);
-const char *mlp_profile_slot_name(const nerva_mlp *mlp, int32_t slot);
-
-/* Plain device copy dst[k] = src[k], k in [0, n): the known-size kernel that memory
- * traffic counters are calibrated against.  Not part of the training path. */
-int nerva_copy_f32(float *dst, const float *src, int64_t n, void *stream);
 
 #ifdef __cplusplus
 }

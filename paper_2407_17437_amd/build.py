@@ -34,22 +34,5 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def build_microbench(verbose: bool = False, name: str = "microbench_gather") -> str:
-    """A stand-alone gather-rate measurement (not part of the library): microbench_gather (L2 and LDS
-    gathers with per-lane index loads) or microbench_lds_gather (LDS gathers with DPP row broadcasts)."""
-    exe = os.path.join(PKG, name)
-    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, name + ".hip"), "-o", exe]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, cwd=CSRC, capture_output=True, text=True)
-    if res.returncode != 0:
-        sys.stderr.write(res.stderr)
-        raise RuntimeError("hipcc failed")
-    return exe
-
-
 if __name__ == "__main__":
     print(build_library(verbose=True))
-    print(build_microbench(verbose=True))
-    print(build_microbench(verbose=True, name="microbench_lds_gather"))

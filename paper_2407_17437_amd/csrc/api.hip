@@ -1,6 +1,7 @@
 // C ABI of the sparse MLP training step: argument checking, layer / MLP handles, the
 // one-off mirror build, and the kernel sequence of a training step.
 #include "../../include/nerva_sparse.h"
+#include "../../include/nerva_sparse_bench.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -84,6 +85,11 @@ struct nerva_layer {
     int64_t full_scratch_ld = 0;
     float *dense_scratch = nullptr;  // partial tiles of a K-split product: kDenseMaxSplits x max(rows, cols) x dense_scratch_ld
     int64_t dense_scratch_ld = 0;
+    // values_t lags behind values[]: a training step updated this layer as the first layer of an MLP,
+    // whose mirror no product reads, and left the mirror's values alone.  Whoever reads values_t next
+    // (a step that has the layer further up, sparse_linear_backward, sparse_linear_sync_values)
+    // refreshes it first.
+    bool mirror_stale = false;
 };
 
 // Optional per-kernel timing of mlp_train_step: one HIP event before every launch and one after
@@ -830,6 +836,7 @@ int sparse_linear_sync_values(nerva_layer *layer, void *stream)
     if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
     hipStream_t s = as_stream(stream);
     HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
+    layer->mirror_stale = false;
     if (layer->dense_on) HIP_TRY(refresh_dense_copies(layer, s));
     return NERVA_OK;
 }
@@ -896,6 +903,7 @@ int sparse_linear_backward(nerva_layer *layer, const float *X, int32_t ldx, cons
         HIP_TRY(dense_transposed(layer, dY, lddy, dX, lddx, nullptr, 0, batch, s));
     } else if (dX) {
         HIP_TRY(launch_gather(layer->values_t, layer->values, layer->perm, layer->nnz, s));
+        layer->mirror_stale = false;
         SpmmArgs a{};
         a.blocks = layer->plan_t; a.nnz = layer->nnz; a.scratch = layer->scratch; a.scratch_ld = layer->scratch_ld;
         a.indptr = layer->indptr_t; a.indices = layer->indices_t; a.values = layer->values_t;
@@ -1133,6 +1141,15 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
     const int nesterov = (mlp->flags & NERVA_MLP_NESTEROV) ? 1 : 0;
     auto A = [&](int l) { return reinterpret_cast<float *>(ws + L.A[l]); };
     auto dZ = [&](int l) { return reinterpret_cast<float *>(ws + L.dZ[l]); };
+
+    // a layer that was last trained as the first layer of another MLP: its mirror's values are behind
+    for (int l = 1; l < n; ++l) {
+        nerva_layer *ly = mlp->layers[l];
+        if (!ly->mirror_stale) continue;
+        HIP_TRY(launch_gather(ly->values_t, ly->values, ly->perm, ly->nnz, s));
+        ly->mirror_stale = false;
+    }
+    if (mlp->layers[0]->nnz > 0) mlp->layers[0]->mirror_stale = true;  // neither pipeline below writes layer 0's mirror
 
     // feedforward, then the loss gradient / batch size
     const nerva_layer *last = mlp->layers[n - 1];

@@ -752,6 +752,10 @@ __global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmAr
 // With a partial plan (RowBlocks::staged_partial) the kernel serves the long rows only and a
 // second launch, the packed kernel, the others.
 constexpr int kStageWaves = kWavesPerBlock;
+// LDS byte offset of a zero-filled row behind the staged block: where a lane with no entry of its own
+// gathers from, so that it multiplies its weight 0 with 0 and not with an operand row that the
+// output row does not reference (which may hold Inf or NaN).
+constexpr int kStageZeroRow = kStageRows * kStageCols * 4;
 constexpr int kStageRounds = 2;  // rounds in which a block is copied into LDS (8 / kStageRounds float4 per thread and round)
 static_assert(kStageRangeRows == kStageWaves * 4 * kStageJ && kStageJ <= 16, "a lane row owns kStageJ rows of the range");
 
@@ -831,7 +835,7 @@ __device__ __forceinline__ void staged_segment(const SpmmArgs &a, const char *ld
     int o[kStageDepth], o2[kStageDepth];
     float ww[kStageDepth], w2[kStageDepth];
     auto load_chunk = [&](int first, int &oo, float &wo) {
-        oo = 0;
+        oo = kStageZeroRow;
         wo = 0.f;
         if (first < longest) {  // uniform
             const int e = first + lig;
@@ -894,7 +898,7 @@ __device__ __forceinline__ void staged_ids(int n_ranges, int n_tiles, int &range
 template <bool XMASK>
 __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const SpmmArgs a, const int n_tiles)
 {
-    __shared__ float4 stage[kStageRows * kStageCols / 4];
+    __shared__ float4 stage[kStageRows * kStageCols / 4 + kStageCols / 4];  // the block, then one row of zeros
     const int n_ranges = a.blocks.staged_ranges;
     int range, tile;
     staged_ids(n_ranges, n_tiles, range, tile);
@@ -904,6 +908,7 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
     const int col = tile * kStageCols + lig * 4;
     const bool col_on = col < a.batch;
     const char *lds = reinterpret_cast<const char *>(stage) + lig * 16;
+    if (threadIdx.x < kStageCols / 4) stage[kStageRows * kStageCols / 4 + threadIdx.x] = make_float4(0.f, 0.f, 0.f, 0.f);  // (visible after the first barrier)
     const int n_cb = a.blocks.staged_cblocks;
     // The lane row's J-th row sits in slot (J * 16 + wave) * 4 + lrow of the range; lane J of the
     // lane row keeps that slot's row id and, block after block, its segment bounds.
@@ -930,7 +935,7 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
     auto first_chunks = [&](int blk, int e_lo, int e_hi, int (&off)[kStageJ], float (&w)[kStageJ]) {
         static_for(all_j, [&](auto jc) {
             constexpr int j = decltype(jc)::value;
-            off[j] = 0;
+            off[j] = kStageZeroRow;
             w[j] = 0.f;
             if (j < n_j) {
                 int p0, len;
@@ -974,7 +979,7 @@ __global__ __launch_bounds__(kStageWaves * kWave) void spmm_staged_kernel(const 
             first_chunks(b + 1, e1, e2, off_next, w_next);
             if (b + 3 <= n_cb) e3 = ends[(b + 3) * kStageRangeRows];
         } else {
-            static_for(all_j, [&](auto jc) { off_next[decltype(jc)::value] = 0; w_next[decltype(jc)::value] = 0.f; });
+            static_for(all_j, [&](auto jc) { off_next[decltype(jc)::value] = kStageZeroRow; w_next[decltype(jc)::value] = 0.f; });
         }
         lds_barrier();
         static_for(all_j, [&](auto jc) {
@@ -2056,17 +2061,34 @@ hipError_t spmm_tiled_go(const SpmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Work-groups of the packed launch for lane groups of gs lanes: those that serve the short rows, and
+// the launch's grid size (tiles rounded up to whole rounds of the 8 XCDs when the ids are decoded
+// XCD-first).  One place, so that the launch and the checks that the grid fits agree.
+struct PackedGrid {
+    int n_tiles, spread, n_pack_blocks;
+    int64_t ids;
+};
+PackedGrid packed_grid(const SpmmArgs &a, int gs, bool with_long_rows)
+{
+    PackedGrid g;
+    const int ne = kWave / gs;
+    g.n_tiles = (a.batch + gs * 4 - 1) / (gs * 4);
+    g.spread = g.n_tiles >= 8;
+    const int64_t n_sets = (static_cast<int64_t>(a.blocks.n_short) + ne - 1) / ne;
+    g.n_pack_blocks = static_cast<int>((n_sets + kWavesPerBlock * kPackSets - 1) / (kWavesPerBlock * kPackSets));
+    const int64_t nrb = static_cast<int64_t>(g.n_pack_blocks) + (with_long_rows ? a.blocks.n_long_blocks : 0);
+    g.ids = (g.spread ? static_cast<int64_t>((g.n_tiles + 7) / 8) * 8 : g.n_tiles) * nrb;
+    return g;
+}
+constexpr int64_t kMaxGridIds = (1ll << 31) - 1;
+
 template <int GS>
 hipError_t spmm_packed_go(const SpmmArgs &a, hipStream_t s)
 {
-    constexpr int NE = kWave / GS;
-    const int n_tiles = (a.batch + GS * 4 - 1) / (GS * 4);
-    const int spread = n_tiles >= 8;
-    const int n_sets = (a.blocks.n_short + NE - 1) / NE;
-    const int n_pack_blocks = (n_sets + kWavesPerBlock * kPackSets - 1) / (kWavesPerBlock * kPackSets);
-    const int64_t nrb = static_cast<int64_t>(n_pack_blocks) + a.blocks.n_long_blocks;
-    const int64_t ids = (spread ? static_cast<int64_t>((n_tiles + 7) / 8) * 8 : n_tiles) * nrb;
-    dim3 grid(static_cast<unsigned>(ids));
+    const PackedGrid pg = packed_grid(a, GS, true);
+    const int n_tiles = pg.n_tiles, spread = pg.spread, n_pack_blocks = pg.n_pack_blocks;
+    if (pg.ids > kMaxGridIds) return hipErrorInvalidConfiguration;  // (callers check before choosing this path)
+    dim3 grid(static_cast<unsigned>(pg.ids));
     if (a.XM)
         hipLaunchKernelGGL((spmm_packed_kernel<GS, true>), grid, dim3(kBlock), 0, s, a, n_tiles, spread, n_pack_blocks);
     else
@@ -2136,8 +2158,7 @@ bool spmm_staged_ok(const SpmmArgs &a)
 // whether the rows a partial plan leaves out take the packed kernel, which runs inside column tiles only
 bool staged_rest_packed(const SpmmArgs &a, int tg)
 {
-    return a.blocks.n_short > 0 && tg != 0 && spmm_offsets_ok(a) &&
-           static_cast<int64_t>(a.blocks.n_short / 64 + 1) * ((a.batch + 31) / 32 + 8) < (1ll << 31);
+    return a.blocks.n_short > 0 && tg != 0 && spmm_offsets_ok(a) && packed_grid(a, tg, false).ids <= kMaxGridIds;
 }
 
 bool sddmm_vec_ok(const SddmmArgs &a);
@@ -2335,9 +2356,8 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
     if (spmm_vec_ok(a)) {
         if (spmm_offsets_ok(a)) {
             const int tg = spmm_tile_group(a);
-            if (a.blocks.n_short > 0 && tg != 0 &&
-                (static_cast<int64_t>(a.blocks.n_short / 64 + 1 + a.blocks.n_long_blocks) * ((a.batch + 31) / 32 + 8) < (1ll << 31))) {
-                switch (tg ? tg : (a.batch <= 64 ? 16 : 32)) {
+            if (a.blocks.n_short > 0 && tg != 0 && packed_grid(a, tg, true).ids <= kMaxGridIds) {
+                switch (tg) {
                     case 32: return spmm_packed_go<32>(a, s);
                     case 16: return spmm_packed_go<16>(a, s);
                     default: return spmm_packed_go<8>(a, s);

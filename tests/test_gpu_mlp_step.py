@@ -365,3 +365,47 @@ def test_mlp_forward_single_examples(nb, torch_mod, oracle, batch, ld):
         prev = got
     assert logits.shape == (10, batch)
     M.close()
+
+
+def test_layer_trained_as_first_layer_then_chained_further_up(nb, torch_mod, oracle):
+    """A training step leaves the mirror's values of an MLP's first layer alone (nothing reads them).  The same
+    layer object chained at a later position of another MLP must backpropagate through its CURRENT weights: the
+    library remembers that the mirror is behind and refreshes it before the first product that reads it."""
+    torch = torch_mod
+    batch, lr, mu = 64, 0.05, 0.9
+    first = wl.make_mlp((40, 48, 10), sparsity=0.6, bias_std=0.1, pattern_seed=110, value_seed=210)
+    M1 = nb.MLP(first, batch)
+    Xs, Ts = wl.make_batches(40, 10, batch, 3, seed=310)
+    for t in range(3):       # three steps: layer 0's weights move away from the mirror's copy
+        M1.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, lr, mu)
+    torch.cuda.synchronize()
+    shared = M1.layers[0]                                       # 48 x 40, ReLU
+    w_now = shared.values.cpu().numpy().copy()
+    _, _, vt_addr, perm_addr = nb.sparse_linear_mirror(shared.handle)
+    from test_gpu_parity import raw_f32
+    perm = raw_i32(nb, torch, perm_addr, shared.nnz)
+    assert not np.array_equal(raw_f32(nb, torch, vt_addr, shared.nnz), w_now[perm])      # the mirror is behind
+    # a second MLP: a new 40-wide input layer below, the shared layer in the middle, a new output layer on top
+    below = wl.make_mlp((30, 40, 10), sparsity=0.5, bias_std=0.1, pattern_seed=111, value_seed=211).layers[0]
+    top = wl.make_mlp((40, 48, 10), sparsity=0.5, bias_std=0.1, pattern_seed=112, value_seed=212).layers[1]
+    L0 = nb.SparseLinear(below, batch); L2 = nb.SparseLinear(top, batch)
+    handle = nb.mlp_create([L0.handle, shared.handle, L2.handle], [L0.velocity, shared.velocity, L2.velocity],
+                           [L0.bias_velocity, shared.bias_velocity, L2.bias_velocity], batch)
+    nbytes = nb.mlp_workspace_bytes(handle, batch)
+    ws = torch.full((nbytes // 4,), float("nan"), device="cuda"); loss = torch.zeros(1, device="cuda")
+    lay = nb.mlp_workspace_layout(handle, batch, 3)
+    X2, T2 = wl.make_batches(30, 10, batch, 1, seed=311)
+    Xd = nb.to_dense(X2[0])
+    nb.mlp_train_step(handle, Xd, Xd.stride(0), torch.as_tensor(T2[0]).cuda(), batch, lr, mu, ws, loss)
+    torch.cuda.synchronize()
+    ld = lay[0]
+    dZ1 = ws[lay[1 + 4 * 1 + 1] // 4:][:48 * ld].view(48, ld)[:, :batch].cpu().numpy()
+    dZ0 = ws[lay[1 + 4 * 0 + 1] // 4:][:40 * ld].view(40, ld)[:, :batch].cpu().numpy()
+    A0 = ws[lay[1 + 4 * 0 + 0] // 4:][:40 * ld].view(40, ld)[:, :batch].cpu().numpy()
+    d = first.layers[0]
+    dA, SdA = oracle.spmm_t(d.rows, d.cols, d.indptr, d.indices, w_now, dZ1)
+    close(dZ0, np.where(A0 > 0, dA, 0).astype(np.float32), SdA, what="dZ below the shared layer (current weights)")
+    # and afterwards the mirror follows the weights again (the layer sits above the first one now)
+    assert np.array_equal(raw_f32(nb, torch, vt_addr, shared.nnz), shared.values.cpu().numpy()[perm])
+    nb.mlp_destroy(handle)
+    L0.close(); L2.close(); M1.close()

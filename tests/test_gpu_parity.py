@@ -572,3 +572,33 @@ def _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged):
     gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, lay.indptr, lay.indices, dZ, X)
     close(g.cpu().numpy(), gr, Sg, what="dvalues"); close(db.cpu().numpy(), dbr, Sdb, what="dbias")
     L.close()
+
+
+def test_staged_product_keeps_a_non_finite_operand_row_to_the_rows_that_read_it(nb, torch_mod, oracle):
+    """Definition of A = S B (Section 4): output row i depends on operand row j only if (i, j) is stored.  An operand
+    row of Inf must therefore reach exactly the output rows that reference it, also in the staged product, whose
+    lanes without an entry of their own ride along with weight 0: they gather a zero row, not an operand row.  The
+    rows chosen are the first of a column block of 512, where such a lane would otherwise read."""
+    torch = torch_mod
+    rows, cols, batch = 2048, 1100, 512
+    lay = layer_case(rows, cols, 0.3, seed=rows + cols)
+    assert nb.nerva_plan_staged_host(rows, cols, lay.indptr, lay.indices, batch)[0].shape[0] > 0     # the staged kernel runs
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((cols, batch)).astype(np.float32)
+    for j in (0, 512, 1024):
+        X[j, :] = np.inf
+    L = nb.SparseLinear(lay, max_batch=batch)
+    Yd = nb.dense(rows, batch)
+    nb.sparse_linear_forward(L.handle, nb.to_dense(X), Yd, batch)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    row_of = np.repeat(np.arange(rows), np.diff(lay.indptr))
+    touched = np.zeros(rows, dtype=bool)
+    touched[row_of[np.isin(lay.indices, (0, 512, 1024))]] = True
+    assert 0.2 * rows < touched.sum() < 0.9 * rows
+    Xf = X.copy(); Xf[[0, 512, 1024], :] = 0.0                   # for the untouched rows these operand rows do not exist
+    Yr, S = oracle.spmm(rows, cols, lay.indptr, lay.indices, lay.values, lay.bias, Xf, False)
+    assert np.all(np.isfinite(Y[~touched])), "an operand row of Inf reached output rows that do not reference it"
+    close(Y[~touched], Yr[~touched], S[~touched], what="rows that do not reference the Inf rows")
+    assert not np.isfinite(Y[touched]).all(axis=1).any()          # and every row that does reference one shows it
+    L.close()

@@ -20,7 +20,8 @@ def nb():
 
 
 def test_header_symbols_are_exported(nb):
-    header = open(os.path.join(ROOT, "include", "nerva_sparse.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b([a-z_0-9]+)\s*\(", header)) - {"defined"}
     assert declared == set(nb.EXPORTS), declared ^ set(nb.EXPORTS)
@@ -31,7 +32,7 @@ def test_header_symbols_are_exported(nb):
 
 def test_library_is_newer_than_its_sources(nb):
     csrc = os.path.join(ROOT, "paper_2407_17437_amd", "csrc")
-    srcs = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(ROOT, "include", "nerva_sparse.h")]
+    srcs = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
     stale = [s for s in srcs if os.path.getmtime(s) > os.path.getmtime(nb.LIB_PATH)]
     assert not stale, f"rebuild the library: {stale} changed after it was built"
 
