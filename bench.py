@@ -1,18 +1,27 @@
 #!/usr/bin/env python3
-"""Benchmark of the sparse-MLP training step on one MI355X.
+"""Benchmark of the sparse-MLP training step and of the isolated sparse kernels on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extras]
 
 A "step" is one call of mlp_train_step (feedforward, loss gradient, backpropagation, momentum
-update) on one mini-batch that is already resident in HBM.  The default workload is the
-paper's MLP 3072-1024-512-10 at 90 % sparsity, batch 100, one synthetic epoch of 50,000
-N(0,1) samples (500 steps).  Prints one JSON line with the throughput, the roofline position
-of the dominant kernel (HIP-event timing of every kernel of the step, taken in a second pass
-over the same steps) and the CPU oracle timed on a bounded sample of the same workload.
+update) on one mini-batch that is already resident in HBM.  The headline workload is the largest
+single-GPU configuration: the wide MLP 3072-8192-8192-10 at 1 % global density (Erdos-Renyi split),
+batch 1024.  One JSON line is printed with
+
+  * the throughput of K timed steps (samples/s),
+  * `roofline`: the dominant launch of a step, timed with HIP events on the step's stream in a second
+    pass over the same steps, its algorithmic bytes and the fraction of the HBM peak they amount to,
+  * `cpu_baseline`: the CPU oracle on a bounded sample of the same workload, all host threads
+    (`cpu_baseline_1thread`: the same on one thread),
+  * `extras` (unless --no-extras): the paper's MLP 3072-1024-512-10 at 90 % sparsity and batch 100, the
+    sparsity sweep 50 % ... 99.9 % on it with the least-squares line through step time against stored
+    entries, and the three kernels alone on 16384 x 16384 power-law matrices (forward, transposed, SDDMM
+    x three densities x batch 128 / 1024: microseconds, algorithmic GB/s, fraction of the HBM peak).
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -32,7 +41,8 @@ WORKLOADS = {
     "cfg4": ((3072, 8192, 8192, 10), None, 0.01, 1024, 32,
              "MLP 3072-8192-8192-10, global density 1% split by Erdos-Renyi, batch 1024"),
 }
-for _s in (0.5, 0.8, 0.9, 0.95, 0.99, 0.999):
+SWEEP = (0.5, 0.8, 0.9, 0.95, 0.99, 0.999)
+for _s in SWEEP:
     WORKLOADS[f"sweep{_s}"] = ((3072, 1024, 512, 10), _s, None, 100, 64,
                                f"MLP 3072-1024-512-10, {_s * 100:g}% sparsity, batch 100")
 
@@ -69,82 +79,45 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
     return 0.0
 
 
-def inference(args, np, torch, nb, wl) -> int:
-    """Batch-1 inference (Section 5.4 of the paper measures the time for one example): K forward passes, each on
-    its own resident example stored as a plain vector, microseconds per example."""
-    sizes, sparsity, er, _, _, desc = WORKLOADS[args.workload]
-    mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
-    pool = 256
-    Xs, _ = wl.make_batches(sizes[0], sizes[-1], 1, pool, seed=3000)
-    Xd = torch.as_tensor(Xs).cuda().contiguous()              # (pool, features, 1): leading dimension 1
-    M = nb.MLP(mlp, 1)
-    x_ptr, x_stride = Xd.data_ptr(), sizes[0] * 4
-
-    def run(first, count):
-        for k in range(first, first + count):
-            nb.mlp_forward(M.handle, x_ptr + (k % pool) * x_stride, 1, 1, M.workspace)
-
-    K, W = args.steps, args.warmup
-    run(0, W)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(W, K)
-    torch.cuda.synchronize()
-    sec = time.perf_counter() - t0
-    cpu = None
-    if args.cpu_seconds > 0:
-        import oracle
-        st = oracle.new_state(mlp.layers, np.float32)
-        n = 50
-        t = time.perf_counter()
-        for k in range(n):
-            oracle.mlp_forward(st, Xs[k % pool], np.float32)
-        dt = time.perf_counter() - t
-        cpu = {"value": round(dt / n * 1e6, 1), "unit": "us/example", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{n} forward passes on single examples"}
-    print(json.dumps({"metric": "batch-1 inference time", "value": round(sec / K * 1e6, 3), "unit": "us/example",
-                      "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
-                      "config": {"workload": f"{args.workload}, forward only, batch 1: {desc}",
-                                 "layer_nnz": [l.nnz for l in mlp.layers]},
-                      "cpu_baseline": cpu}))
-    M.close()
-    return 0
+def csrc_digest() -> str:
+    """Digest of the kernel sources: what a stored counter reading must have been taken with to count."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2407_17437_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        h.update(f.encode())
+        h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:16]
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
-    ap.add_argument("--profile-steps", type=int, default=100, help="steps of the per-kernel event pass (0: skip)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0: skip)")
-    ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
-    ap.add_argument("--unfused", action="store_true")
-    ap.add_argument("--dense-from-density", type=float, default=None,
-                    help="layers of at least this density take the dense MFMA route for their two products (default: none)")
-    ap.add_argument("--separate-head", action="store_true",
-                    help="keep the output layer's forward product, loss and transposed product as three launches")
-    ap.add_argument("--prefer-staged", action="store_true",
-                    help="measurement aid: staged (LDS) products and SDDMM wherever they can run, not only where the library expects them to pay")
-    ap.add_argument("--inference", action="store_true",
-                    help="instead of training steps: forward passes on ONE example (batch 1), microseconds per example")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
-              file=sys.stderr)
-        return 2
+def stored_traffic(workload: str, kernel: str):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, and where
+    they come from; (None, reason) when there is none or the kernels have changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload under profiles/"
+    rec = json.load(open(path))
+    if rec.get("csrc_digest") != csrc_digest():
+        return None, f"profiles/{os.path.basename(path)} was taken with other kernel sources (digest {rec.get('csrc_digest')}): stale"
+    return rec.get("bytes_per_launch", {}).get(kernel), f"profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, kernel sources {rec['csrc_digest']})"
 
-    import numpy as np
-    import torch
-    from paper_2407_17437_amd import binding as nb
-    from paper_2407_17437_amd import workloads as wl
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    torch.cuda.set_device(0)
-    if args.inference:
-        return inference(args, np, torch, nb, wl)
-    sizes, sparsity, er, batch, pool, desc = WORKLOADS[args.workload]
+class Env:
+    pass
+
+
+_T0 = time.perf_counter()
+
+
+def log(msg: str) -> None:
+    """Progress on stderr (the JSON line on stdout stays alone)."""
+    print(f"[bench {time.perf_counter() - _T0:6.1f} s] {msg}", file=sys.stderr, flush=True)
+
+
+def measure_mlp(env, name: str, K: int, W: int, profile_steps: int, args, copy_gbs: float):
+    """K timed steps of the named workload after W warm-up steps, then the per-launch event pass."""
+    np, torch, nb, wl = env.np, env.torch, env.nb, env.wl
+    sizes, sparsity, er, batch, pool, desc = WORKLOADS[name]
+    log(f"{name}: building the network and {pool} batches")
     mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
     Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, pool, seed=3000)
     ld = nb.padded_ld(batch)
@@ -155,6 +128,7 @@ def main() -> int:
         nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
     M = nb.MLP(mlp, batch, (nb.NERVA_MLP_UNFUSED if args.unfused else 0) |
                (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0), dense_from_density=args.dense_from_density)
+    nb.nerva_set_partition_mode(nb.NERVA_PARTITION_BALANCED)
     x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4
     t_ptr, t_stride = Td.data_ptr(), batch * 4
     lr, mu = 0.01, 0.9
@@ -187,14 +161,189 @@ def main() -> int:
             for i in range(first // args.graph, (first + count) // args.graph):
                 graphs[i % len(graphs)].replay()
 
+    if graphs:
+        K = max(args.graph, K // args.graph * args.graph)
+        W = (W + args.graph - 1) // args.graph * args.graph
+    log(f"{name}: {W} warm-up + {K} timed steps")
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, K)
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    log(f"{name}: {sec / K * 1e3:.4f} ms per step")
+    loss_end = float(M.loss.item())
+    assert np.isfinite(loss_end), "training diverged"
+
+    # ---- per-launch HIP-event pass over the same steps (plain launches, events on the step's stream) ----
+    roofline, kernels = None, []
+    if profile_steps > 0:
+        P = min(profile_steps, max(K, 1))
+        nb.mlp_profile_enable(M.handle, P)
+        for k in range(W + K, W + K + P):
+            step(k)
+        torch.cuda.synchronize()
+        steps_done, slots = nb.mlp_profile_read(M.handle)
+        nb.mlp_profile_enable(M.handle, 0)
+        for slot, ms in slots:
+            # "a+b[l]" is one grid that runs kernel a of layer l and kernel b of layer l+1
+            # (the three-part name is the fused head of the output layer: all of layer l)
+            l = int(slot.split("[")[1].rstrip("]"))
+            kinds = slot.split("[")[0].split("+")
+            if len(kinds) == 3:
+                kinds = ["+".join(kinds)]
+            byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
+            if len(kinds) == 2:
+                byt += slot_bytes(kinds[1], M.layers[l + 1], batch, has_mirror_scatter=True)
+            us = ms * 1e3 / max(steps_done, 1)
+            kernels.append({"kernel": slot, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
+                            "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})
+        dom = max(kernels, key=lambda r: r["avg_us"])
+        plain = not graphs and not args.unfused and not args.separate_head and args.dense_from_density is None and not args.prefer_staged
+        traffic, source = stored_traffic(name, dom["kernel"]) if plain else (None, "not the default launch configuration")
+        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],
+                    "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": traffic, "traffic_source": source,
+                    "copy_kernel_gbs": round(copy_gbs, 1), "frac_of_copy_kernel": round(dom["gbs"] / copy_gbs, 5),
+                    "step_algorithmic_bytes": int(sum(r["algorithmic_bytes"] for r in kernels)),
+                    "step_frac": round(sum(r["algorithmic_bytes"] for r in kernels) / (sec / K) / 1e9 / HBM_PEAK_GBS, 5),
+                    "timing": f"HIP events between the launches of a step on the step's stream, {steps_done} steps"}
+    res = {"name": name, "desc": desc, "batch": batch, "K": K, "W": W, "sec": sec, "ms_per_step": sec / K * 1e3,
+           "samples_per_s": K * batch / sec, "loss": loss_end, "layer_nnz": [l.nnz for l in mlp.layers],
+           "kernels": kernels, "roofline": roofline, "graphs": bool(graphs), "lr": lr, "mu": mu,
+           "mlp": mlp, "Xs": Xs, "Ts": Ts, "pool": pool}
+    M.close()
+    del Xd, Td
+    return res
+
+
+def oracle_baseline(env, res, seconds: float, threads=None):
+    """The CPU oracle on a bounded sample of the workload that `res` describes: whole training steps on the same
+    network and batches, as many as fit into `seconds` (at least one)."""
+    import oracle
+    np = env.np
+    all_threads = oracle.num_threads()
+    log(f"{res['name']}: CPU oracle on {threads or all_threads} thread(s), up to {seconds:.0f} s")
+    if threads is not None:
+        oracle.set_num_threads(threads)
+    try:
+        mlp, Xs, Ts, pool, batch = res["mlp"], res["Xs"], res["Ts"], res["pool"], res["batch"]
+        st = oracle.new_state(mlp.layers, np.float32)
+        t = time.perf_counter()
+        oracle.mlp_step(st, Xs[0], Ts[0], res["lr"], res["mu"], np.float32)
+        one = time.perf_counter() - t
+        n = int(max(1, min(pool - 1, (seconds - one) / max(one, 1e-6))))
+        t = time.perf_counter()
+        for k in range(1, 1 + n):
+            oracle.mlp_step(st, Xs[k % pool], Ts[k % pool], res["lr"], res["mu"], np.float32)
+        dt = time.perf_counter() - t
+        return {"value": round(n * batch / dt, 1), "unit": "samples/s", "cores": oracle.num_threads(), "kind": "oracle",
+                "sample": f"{n} training steps of batch {batch} on the same network and batches ({dt:.1f} s), after one untimed step",
+                "ms_per_step": round(dt / n * 1e3, 3)}
+    finally:
+        oracle.set_num_threads(all_threads)
+
+
+def inference(args, env) -> int:
+    """Batch-1 inference (Section 5.4 of the paper measures the time for one example): K forward passes, each on
+    its own resident example stored as a plain vector, microseconds per example."""
+    np, torch, nb, wl = env.np, env.torch, env.nb, env.wl
+    sizes, sparsity, er, _, _, desc = WORKLOADS[args.workload]
+    mlp = wl.make_mlp(sizes, sparsity=sparsity) if er is None else wl.make_mlp(sizes, er_density=er)
+    pool = 256
+    Xs, _ = wl.make_batches(sizes[0], sizes[-1], 1, pool, seed=3000)
+    Xd = torch.as_tensor(Xs).cuda().contiguous()              # (pool, features, 1): leading dimension 1
+    M = nb.MLP(mlp, 1)
+    x_ptr, x_stride = Xd.data_ptr(), sizes[0] * 4
+
+    def run(first, count):
+        for k in range(first, first + count):
+            nb.mlp_forward(M.handle, x_ptr + (k % pool) * x_stride, 1, 1, M.workspace)
+
+    K, W = args.steps, args.warmup
+    run(0, W)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(W, K)
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        st = oracle.new_state(mlp.layers, np.float32)
+        n = 50
+        t = time.perf_counter()
+        for k in range(n):
+            oracle.mlp_forward(st, Xs[k % pool], np.float32)
+        dt = time.perf_counter() - t
+        cpu = {"value": round(dt / n * 1e6, 1), "unit": "us/example", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{n} forward passes on single examples"}
+    print(json.dumps({"metric": "batch-1 inference time", "value": round(sec / K * 1e6, 3), "unit": "us/example",
+                      "n_gpus": 1, "steps": K, "warmup": W, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"{args.workload}, forward only, batch 1: {desc}"},
+                      "cpu_baseline": cpu}))
+    M.close()
+    return 0
+
+
+def fit_line(x, y):
+    """Least squares y = a + b x and the coefficient of determination."""
+    n = len(x)
+    mx, my = sum(x) / n, sum(y) / n
+    sxx = sum((u - mx) ** 2 for u in x)
+    b = sum((u - mx) * (v - my) for u, v in zip(x, y)) / sxx
+    a = my - b * mx
+    ss_res = sum((v - (a + b * u)) ** 2 for u, v in zip(x, y))
+    ss_tot = sum((v - my) ** 2 for v in y)
+    return a, b, 1.0 - ss_res / ss_tot
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
+    ap.add_argument("--profile-steps", type=int, default=100, help="steps of the per-kernel event pass (0: skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of each CPU-oracle leg (0: skip)")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload: no small MLP, no sweep, no isolated kernels")
+    ap.add_argument("--extras-steps", type=int, default=500, help="timed steps of each small-MLP point of the extras")
+    ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
+    ap.add_argument("--unfused", action="store_true")
+    ap.add_argument("--dense-from-density", type=float, default=None,
+                    help="layers of at least this density take the dense MFMA route for their two products (default: the library's own choice)")
+    ap.add_argument("--separate-head", action="store_true",
+                    help="keep the output layer's forward product, loss and transposed product as three launches")
+    ap.add_argument("--prefer-staged", action="store_true",
+                    help="measurement aid: staged (LDS) products and SDDMM wherever they can run, not only where the library expects them to pay")
+    ap.add_argument("--inference", action="store_true",
+                    help="instead of training steps: forward passes on ONE example (batch 1), microseconds per example")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the step has no multi-GPU path); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    env = Env()
+    import numpy as np
+    import torch
+    from paper_2407_17437_amd import binding as nb
+    from paper_2407_17437_amd import workloads as wl
+    env.np, env.torch, env.nb, env.wl = np, torch, nb, wl
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    if args.inference:
+        return inference(args, env)
+
     # one plain copy of known size (256 MiB read + 256 MiB written): the reference that HBM traffic
-    # counters of a profiled run are scaled by; outside the timed region
+    # counters of a profiled run are scaled by; outside every timed region
     cal_src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
     cal_dst = torch.empty_like(cal_src)
     nb.nerva_copy_f32(cal_dst, cal_src, cal_src.numel())
     torch.cuda.synchronize()
     # the same copy twice more, timed: what a plain streaming kernel of this library reaches on this
-    # GPU today, reported next to the published peak (outside the timed region as well)
+    # GPU today, reported next to the published peak
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     nb.nerva_copy_f32(cal_dst, cal_src, cal_src.numel())
     e0.record()
@@ -203,88 +352,62 @@ def main() -> int:
     copy_gbs = 2 * cal_src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del cal_src, cal_dst
 
-    K, W = args.steps, args.warmup
-    if graphs:
-        K = max(args.graph, K // args.graph * args.graph)
-        W = (W + args.graph - 1) // args.graph * args.graph
-    run(0, W)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(W, K)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    sec = t1 - t0
-    loss_end = float(M.loss.item())
-    assert np.isfinite(loss_end), "training diverged"
-    value = K * batch / sec
-
-    # ---- per-kernel HIP-event pass over the same steps (plain launches) -------------------
-    roofline = None
-    kernels = []
-    if args.profile_steps > 0:
-        P = min(args.profile_steps, K)
-        nb.mlp_profile_enable(M.handle, P)
-        for k in range(W + K, W + K + P):
-            step(k)
-        torch.cuda.synchronize()
-        steps_done, slots = nb.mlp_profile_read(M.handle)
-        nb.mlp_profile_enable(M.handle, 0)
-        for name, ms in slots:
-            # "a+b[l]" is one grid that runs kernel a of layer l and kernel b of layer l+1
-            # (the three-part name is the fused head of the output layer: all of layer l)
-            l = int(name.split("[")[1].rstrip("]"))
-            kinds = name.split("[")[0].split("+")
-            if len(kinds) == 3:
-                kinds = ["+".join(kinds)]
-            byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
-            if len(kinds) == 2:
-                l2 = l + 1
-                byt += slot_bytes(kinds[1], M.layers[l2], batch, has_mirror_scatter=(l2 > 0))
-            us = ms * 1e3 / max(steps_done, 1)
-            kernels.append({"kernel": name, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
-                            "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})
-        dom = max(kernels, key=lambda r: r["avg_us"])
-        # HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this same command
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
-        if os.path.exists(tpath) and not graphs and not args.unfused and not args.separate_head and args.dense_from_density is None:
-            traffic = json.load(open(tpath)).get("bytes_per_launch", {}).get(dom["kernel"])
-        roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],
-                    "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": traffic,
-                    "copy_kernel_gbs": round(copy_gbs, 1), "frac_of_copy_kernel": round(dom["gbs"] / copy_gbs, 5),
-                    "timing": f"HIP events between the launches of a step, {steps_done} steps"}
-
-    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
-    cpu = None
+    head = measure_mlp(env, args.workload, args.steps, args.warmup, args.profile_steps, args, copy_gbs)
+    cpu = cpu1 = None
     if args.cpu_seconds > 0:
-        import oracle
-        st = oracle.new_state(mlp.layers, np.float32)
-        t = time.perf_counter()
-        oracle.mlp_step(st, Xs[0], Ts[0], lr, mu, np.float32)
-        one = time.perf_counter() - t
-        n = int(max(2, min(pool - 1, args.cpu_seconds / max(one, 1e-6))))
-        t = time.perf_counter()
-        for k in range(1, 1 + n):
-            oracle.mlp_step(st, Xs[k % pool], Ts[k % pool], lr, mu, np.float32)
-        dt = time.perf_counter() - t
-        cpu = {"value": round(n * batch / dt, 1), "unit": "samples/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{n} training steps of batch {batch} on the same network and batches ({dt:.1f} s)",
-               "ms_per_step": round(dt / n * 1e3, 3)}
+        cpu = oracle_baseline(env, head, args.cpu_seconds)
+        cpu1 = oracle_baseline(env, head, args.cpu_seconds, threads=1)
+
+    extras = None
+    if not args.no_extras:
+        extras = {}
+        t_extra = time.perf_counter()
+        Ks, Ws = args.extras_steps, 50
+        # the paper's MLP at 90 % sparsity (one epoch = 500 steps of batch 100)
+        if args.workload != "cfg2":
+            r = measure_mlp(env, "cfg2", Ks, Ws, min(100, Ks), args, copy_gbs)
+            extras["cfg2"] = {"workload": "cfg2: " + r["desc"], "steps": r["K"], "warmup": r["W"],
+                              "ms_per_step": round(r["ms_per_step"], 5), "samples_per_s": round(r["samples_per_s"], 1),
+                              "roofline": r["roofline"], "kernels": r["kernels"],
+                              "cpu_baseline": oracle_baseline(env, r, min(args.cpu_seconds, 5.0)) if args.cpu_seconds > 0 else None}
+        # step time against stored entries, 50 % ... 99.9 % sparsity
+        pts = []
+        for s in SWEEP:
+            r = measure_mlp(env, f"sweep{s}", Ks, Ws, 0, args, copy_gbs)
+            pts.append({"sparsity": s, "nnz": sum(r["layer_nnz"]), "us_per_step": round(r["ms_per_step"] * 1e3, 3),
+                        "samples_per_s": round(r["samples_per_s"], 1)})
+        a, b, r2 = fit_line([p["nnz"] / 1e6 for p in pts], [p["us_per_step"] for p in pts])
+        extras["sweep"] = {"workload": "MLP 3072-1024-512-10, batch 100, per-layer sparsity 50 ... 99.9 %",
+                           "steps": Ks, "warmup": Ws, "points": pts,
+                           "fit": {"model": "us_per_step = a + b * (stored entries / 1e6)", "a_us": round(a, 3),
+                                   "b_us_per_million_entries": round(b, 3), "r2": round(r2, 5)}}
+        # the three kernels alone on 16384 x 16384 power-law matrices
+        from paper_2407_17437_amd import kernel_bench
+        log("isolated kernels on 16384 x 16384 power-law matrices")
+        rows = kernel_bench.run_cases(reps=10, emit=lambda r: log(f"  {r['kernel']} density {r['density']} batch {r['batch']}: {r['us_back_to_back']} us"))
+        extras["cfg5_kernels"] = {
+            "workload": "16384 x 16384 CSR, power-law (rank^-1.2) row lengths, densities 0.1 / 1 / 10 %, dense operand of 128 / 1024 columns",
+            "timing": "HIP events; us_cold: median of 10 launches each after a pass that evicts the caches; us_back_to_back: 10 launches in a row",
+            "peak_gbs": HBM_PEAK_GBS,
+            "table": [{k: r[k] for k in ("kernel", "density", "batch", "nnz", "us_cold", "us_back_to_back", "algorithmic_MB",
+                                         "gbs_cold", "frac_hbm_cold", "gbs_back_to_back", "frac_hbm_back_to_back",
+                                         "tflops_back_to_back")} for r in rows]}
+        extras["seconds"] = round(time.perf_counter() - t_extra, 1)
 
     out = {
-        "metric": "sparse-MLP train samples/s", "value": round(value, 1), "unit": "samples/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(sec / K * 1e3, 5),
+        "metric": "sparse-MLP train samples/s", "value": round(head["samples_per_s"], 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": head["K"], "warmup": head["W"], "ms_per_step": round(head["ms_per_step"], 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "layer_nnz": [l.nnz for l in mlp.layers],
-                   "batch": batch, "lr": lr, "momentum": mu, "launch": f"hip graph of {args.graph} steps" if graphs else "stream",
-                   "fused_update": not args.unfused, "final_loss": round(loss_end, 5)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "config": {"workload": f"{args.workload}: {head['desc']}"},
+        "roofline": head["roofline"], "cpu_baseline": cpu, "cpu_baseline_1thread": cpu1,
+        "details": {"layer_nnz": head["layer_nnz"], "batch": head["batch"], "lr": head["lr"], "momentum": head["mu"],
+                    "launch": f"hip graph of {args.graph} steps" if head["graphs"] else "stream",
+                    "fused_update": not args.unfused, "final_loss": round(head["loss"], 5)},
+        "kernels": head["kernels"], "extras": extras,
         "context": "paper: ~4x faster than masked PyTorch at 99% sparsity, CIFAR-10 MLP, Intel i7-6700 4 cores, MKL "
                    "(abstract, Section 5.5, Appendix A); another machine, not a target",
     }
     print(json.dumps(out))
-    M.close()
     return 0
 
 

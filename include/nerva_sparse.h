@@ -325,6 +325,25 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
                    int32_t batch, float lr, float momentum, void *workspace,
                    size_t workspace_bytes, float *loss_out, void *stream);
 
+/* mlp_train_step for callers that cannot allocate device memory or keep a workspace of their own --
+ * code under HIP graph capture, tight training loops, harnesses that forbid hipMalloc.  The same
+ * step with the same kernels and the same results, but the intermediates (what mlp_workspace_layout
+ * describes) live in a workspace that is part of the library itself: a static device array of
+ * NERVA_STATIC_WORKSPACE_BYTES that every GPU on which the library runs holds until the process
+ * ends.  The call allocates nothing and frees nothing (no hipMalloc, no events, no host buffers
+ * that outlive it); per-launch timing (nerva_sparse_bench.h) is therefore refused while it is on.
+ * The caller still passes the batch, the labels and loss_out, and owns the weights and momentum
+ * buffers as before; the intermediates cannot be read back.  An MLP / batch whose workspace
+ * (mlp_workspace_bytes) exceeds the static one is rejected with NERVA_ERR_WORKSPACE and a message
+ * that names both sizes; nothing has been enqueued then.  The array is shared by every call on
+ * that GPU and keeps the previous call's contents (nothing in it has to start at zero): calls on
+ * different streams, or on different MLPs, that overlap in time on one GPU race -- order them on one
+ * stream or with events.  The array's device address is looked up when the first MLP is created on
+ * a device (mlp_create), so a captured call does no look-up. */
+#define NERVA_STATIC_WORKSPACE_BYTES (32u << 20)
+int mlp_train_step_static(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels,
+                          int32_t batch, float lr, float momentum, float *loss_out, void *stream);
+
 /* Forward pass only (inference on a batch): logits (rows_L, ld) are left in the
  * workspace at the A_L offset. */
 int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch,

@@ -25,6 +25,7 @@ NERVA_STAGE_ROWS, NERVA_STAGE_COLS, NERVA_STAGE_MIN_BATCH, NERVA_STAGE_RANGE_ROW
 NERVA_PARTITION_BALANCED, NERVA_PARTITION_ROW_SPLIT, NERVA_PARTITION_PREFER_STAGED = 0, 1, 2
 NERVA_MLP_DEFAULT, NERVA_MLP_UNFUSED, NERVA_MLP_NESTEROV, NERVA_MLP_SEPARATE_HEAD = 0, 1, 2, 4
 NERVA_WAVES_PER_BLOCK = 16
+NERVA_STATIC_WORKSPACE_BYTES = 32 << 20
 NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
@@ -32,7 +33,7 @@ EXPORTS = [
     "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_enable_dense", "sparse_linear_sync_values", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
-    "mlp_workspace_layout", "mlp_train_step", "mlp_forward", "nerva_copy_f32",
+    "mlp_workspace_layout", "mlp_train_step", "mlp_train_step_static", "mlp_forward", "nerva_copy_f32",
     "mlp_profile_enable", "mlp_profile_read", "mlp_profile_slot_name",
 ]
 
@@ -75,6 +76,7 @@ def _load() -> ctypes.CDLL:
         "mlp_workspace_bytes": (sz, [vp, i32]),
         "mlp_workspace_layout": (ctypes.c_int, [vp, i32, vp]),
         "mlp_train_step": (ctypes.c_int, [vp, vp, i32, vp, i32, f32, f32, vp, sz, vp, vp]),
+        "mlp_train_step_static": (ctypes.c_int, [vp, vp, i32, vp, i32, f32, f32, vp, vp]),
         "mlp_forward": (ctypes.c_int, [vp, vp, i32, i32, vp, sz, vp]),
         "nerva_copy_f32": (ctypes.c_int, [vp, vp, i64, vp]),
         "mlp_profile_enable": (ctypes.c_int, [vp, i32]),
@@ -270,6 +272,13 @@ def mlp_train_step(mlp: int, X, ldx: int, labels, batch: int, lr: float, momentu
     lp = labels if isinstance(labels, int) else _ptr(labels)
     _check(lib.mlp_train_step(mlp, xp, ldx, lp, batch, lr, momentum, _ptr(workspace),
                               workspace.numel() * workspace.element_size(), _ptr(loss_out), _stream(stream)))
+
+
+def mlp_train_step_static(mlp: int, X, ldx: int, labels, batch: int, lr: float, momentum: float, loss_out, stream=None) -> None:
+    """The same step on the library's own static workspace; X and labels may be tensors or raw device addresses."""
+    xp = X if isinstance(X, int) else _ptr(X)
+    lp = labels if isinstance(labels, int) else _ptr(labels)
+    _check(lib.mlp_train_step_static(mlp, xp, ldx, lp, batch, lr, momentum, _ptr(loss_out), _stream(stream)))
 
 
 def mlp_forward(mlp: int, X, ldx: int, batch: int, workspace, stream=None) -> None:

@@ -12,13 +12,44 @@
 #include <climits>
 #include <atomic>
 #include <functional>
+#include <mutex>
 #include <vector>
 
 #include "kernels.h"
 
 using namespace nerva;
 
+// Workspace of mlp_train_step_static: one array per GPU, part of the library's code object, held
+// from the moment the library is loaded on a device until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress; the device address it yields (one per device) is
+// what kernels, copies and fills are given.
+constexpr size_t kStaticScratchBytes = NERVA_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once resolved
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (resolved once per device, with that device current).
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 thread_local std::string g_last_error;
 std::atomic<int> g_partition_mode{0};  // see nerva_set_partition_mode
@@ -980,6 +1011,16 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     }
     nerva_mlp *m = new (std::nothrow) nerva_mlp;
     if (!m) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
+    {
+        // set-up time: the address of the static workspace on this device, so that
+        // mlp_train_step_static has nothing left to look up
+        void *ptr = nullptr;
+        const hipError_t e = static_scratch(&ptr);
+        if (e != hipSuccess) {
+            delete m;
+            return hip_fail(e, "address of the static workspace");
+        }
+    }
     m->layers.assign(layers, layers + n_layers);
     m->vel.assign(velocities, velocities + n_layers);
     m->bias_vel.assign(bias_velocities, bias_velocities + n_layers);
@@ -1127,6 +1168,9 @@ int mlp_forward(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, void
     return forward_chain(mlp, X, ldx, batch, static_cast<char *>(workspace), L, as_stream(stream), mlp->layers.size());
 }
 
+static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
+                      float momentum, void *workspace, const Layout &L, float *loss_out, void *stream);
+
 int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
                    float momentum, void *workspace, size_t workspace_bytes, float *loss_out, void *stream)
 {
@@ -1134,6 +1178,32 @@ int mlp_train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *l
     int rc = check_step_args(mlp, X, ldx, batch, workspace, workspace_bytes, L);
     if (rc != NERVA_OK) return rc;
     if (!labels) return fail(NERVA_ERR_ARGUMENT, "labels is null");
+    return train_step(mlp, X, ldx, labels, batch, lr, momentum, workspace, L, loss_out, stream);
+}
+
+int mlp_train_step_static(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
+                          float momentum, float *loss_out, void *stream)
+{
+    if (!mlp || !X || !labels) return fail(NERVA_ERR_ARGUMENT, "null argument");
+    if (mlp->prof.on) return fail(NERVA_ERR_ARGUMENT, "per-launch timing creates events: not available in mlp_train_step_static");
+    int rc = check_batch(batch, ldx, "ldx");
+    if (rc != NERVA_OK) return rc;
+    if (batch > mlp->max_batch) return fail(NERVA_ERR_SHAPE, "batch %d exceeds max_batch %d", batch, mlp->max_batch);
+    const Layout L = make_layout(mlp, batch);
+    if (static_cast<size_t>(L.bytes) > kStaticScratchBytes)
+        return fail(NERVA_ERR_WORKSPACE, "this MLP at batch %d needs a workspace of %lld bytes, the static one has %zu: use mlp_train_step with a workspace of your own",
+                    batch, (long long)L.bytes, kStaticScratchBytes);
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);  // a table look-up once mlp_create has run on this device
+    if (e != hipSuccess) return hip_fail(e, "address of the static workspace");
+    // nothing in the workspace has to start at zero: every stage writes what the next one reads
+    return train_step(mlp, X, ldx, labels, batch, lr, momentum, ws, L, loss_out, stream);
+}
+
+static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t *labels, int32_t batch, float lr,
+                      float momentum, void *workspace, const Layout &L, float *loss_out, void *stream)
+{
+    int rc = NERVA_OK;
     hipStream_t s = as_stream(stream);
     char *ws = static_cast<char *>(workspace);
     const int n = static_cast<int>(mlp->layers.size());

@@ -242,7 +242,7 @@ def _config5_case(nb, torch, oracle, z, batch):
     # forward product and SDDMM: rows of W, one or more from every class of W's partitions
     picked = partition_sample(nb, n, n, z.indptr, z.indices, batch, rng, budget)
     reasons = sorted(set(picked.values()))
-    assert any(r.startswith("huge row") for r in reasons) and any(r.startswith("lg ") for r in reasons), reasons
+    assert any(r.startswith("lg ") for r in reasons) and (rn.max() < n or any(r.startswith("huge row") for r in reasons)), reasons
     sel = np.array(sorted(picked), dtype=np.int64)
     ip, ix, pos = sub_rows(z, sel)
     Yr, S = oracle.spmm(len(sel), n, ip, ix, z.values[pos], z.bias[sel], X, False)
