@@ -208,6 +208,25 @@ hipError_t launch_dense_gemm(const DenseArgs &a, hipStream_t s);
 hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows,
                                 float *dense, int64_t ld, float *dense_t, int64_t ld_t, hipStream_t s);
 
+// ---- binding a pattern: the work that grows with the number of stored entries, on the device ----
+// Check that device arrays hold a canonical CSR pattern.  status (device, 4 ints) receives
+// {OR of the kCsr* flags found, first row with wrong row pointers, first entry with a wrong column
+// index, 0}; rows whose pointers are wrong are not walked, so nothing outside the arrays is read.
+enum : int32_t { kCsrBadFirst = 1, kCsrDecreasing = 2, kCsrBeyondNnz = 4, kCsrBadLast = 8, kCsrColumnRange = 16, kCsrNotAscending = 32 };
+hipError_t launch_validate_csr(int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr, const int32_t *indices,
+                               int32_t *status, hipStream_t s);
+// CSC mirror of a canonical CSR pattern (stable counting sort by column): indptr_t[cols + 1],
+// indices_t[nnz] (row of each mirror entry), perm[nnz] (mirror position -> CSR position), pos_t[nnz]
+// (the inverse).  work: mirror_work_ints(cols, T) ints of scratch, T = mirror_tiles(rows, cols, nnz).
+int32_t mirror_tiles(int32_t rows, int32_t cols, int32_t nnz);
+size_t mirror_work_ints(int32_t cols, int32_t T);
+hipError_t launch_build_mirror(int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr, const int32_t *indices,
+                               int32_t *indptr_t, int32_t *indices_t, int32_t *perm, int32_t *pos_t, int32_t *work, int32_t T,
+                               hipStream_t s);
+// RowBlocks::staged_ends from RowBlocks::staged_rows and the pattern
+hipError_t launch_staged_ends(const int32_t *indptr, const int32_t *indices, const int32_t *slot_rows, int32_t *ends, int32_t ranges,
+                              int32_t n_cb, hipStream_t s);
+
 // The end of the forward pass and the start of the backward pass for a small output layer, in
 // one launch: logits Z = W X + b, softmax cross-entropy (loss and dZ = (softmax - onehot) / batch),
 // and the gradient handed to the layer below, dX = (W^T dZ) * [X > 0] (X is that layer's ReLU
