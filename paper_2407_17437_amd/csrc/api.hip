@@ -81,6 +81,18 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 }  // namespace
 
+// What a bound pattern owns on the device besides scratch: the mirror and the partition tables.  A
+// layer keeps two sets: sparse_linear_rebind builds the new pattern's structures in the spare set while
+// the current one stays valid, and swaps on success; buffers are reused when large enough, so
+// repeated topology updates do not allocate.
+struct PatternBuffers {
+    int32_t *indptr_t = nullptr;    // [cols + 1]
+    int32_t *mirror_mem = nullptr;  // indices_t | perm | pos_t | values_t, round_up(nnz, 64) elements each
+    size_t mirror_ints = 0;
+    int32_t *plan_mem = nullptr, *plan_t_mem = nullptr;
+    size_t plan_ints = 0, plan_t_ints = 0;
+};
+
 struct nerva_layer {
     int32_t rows = 0, cols = 0, nnz = 0, activation = 0, max_batch = 0;
     // caller-owned
@@ -88,22 +100,27 @@ struct nerva_layer {
     const int32_t *indices = nullptr;
     float *values = nullptr;
     float *bias = nullptr;
-    // owned: CSR of W^T and the position maps
+    // owned: CSR of W^T and the position maps (views into cur.mirror_mem / cur.indptr_t)
+    PatternBuffers cur, spare;
     int32_t *indptr_t = nullptr;   // [cols+1]
     int32_t *indices_t = nullptr;  // [nnz] row index of each mirror entry
     float *values_t = nullptr;     // [nnz]
     int32_t *perm = nullptr;       // [nnz] mirror position -> CSR position
     int32_t *pos_t = nullptr;      // [nnz] CSR position -> mirror position
-    // owned: static work partitions of W (by rows) and of the mirror (by W's columns)
-    int32_t *plan_mem = nullptr;
-    int32_t *plan_t_mem = nullptr;
+    // static work partitions of W (by rows) and of the mirror (by W's columns): views into cur.plan_mem / cur.plan_t_mem
     RowBlocks plan{}, plan_t{};
+    // owned scratch of the set-up kernels: counters of the mirror build, then 4 status ints
+    int32_t *build_work = nullptr;
+    size_t build_work_ints = 0;
+    int32_t *status = nullptr;     // [4] result of the device-side CSR check
     // owned: partial rows of huge-row work-groups, shared by the forward and the transposed product
     float *scratch = nullptr;
+    size_t scratch_floats = 0;
     int64_t scratch_ld = 0;
     // owned: per-tile partial products of the column-tiled SDDMM (only for layers whose input
     // at max_batch columns does not fit an L2)
     float *partial = nullptr;
+    size_t partial_floats = 0;
     int64_t partial_stride = 0, partial_db_at = 0;
     int32_t partial_tiles = 0;
     // owned, only after sparse_linear_enable_dense: zero-filled dense copies of W (rows x dense_ld)
@@ -112,7 +129,8 @@ struct nerva_layer {
     float *dense = nullptr, *dense_t = nullptr;
     int64_t dense_ld = 0, dense_t_ld = 0;
     // owned, only for a matrix that stores every entry and has at most kFullMaxRows rows
-    float *full_scratch = nullptr;   // slice partials of the streaming product, (slices * rows, full_scratch_ld)
+    bool full = false;               // the bound pattern is such a matrix
+    float *full_scratch = nullptr;   // slice partials of the streaming product, (slices * rows, full_scratch_ld); kept once allocated
     int64_t full_scratch_ld = 0;
     float *dense_scratch = nullptr;  // partial tiles of a K-split product: kDenseMaxSplits x max(rows, cols) x dense_scratch_ld
     int64_t dense_scratch_ld = 0;
@@ -182,6 +200,25 @@ Layout make_layout(const nerva_mlp *m, int32_t batch)
     return L;
 }
 
+// Rows by stored entries descending, ties by row id: one counting sort, O(rows + longest row), that
+// every partition of a pattern is then read off from.
+struct RowsByLength {
+    std::vector<int32_t> order;
+    int32_t longest = 0;
+};
+
+RowsByLength rows_by_length(int32_t rows, const int32_t *indptr)
+{
+    RowsByLength R;
+    for (int32_t i = 0; i < rows; ++i) R.longest = std::max(R.longest, indptr[i + 1] - indptr[i]);
+    std::vector<int32_t> start(static_cast<size_t>(R.longest) + 2, 0);
+    for (int32_t i = 0; i < rows; ++i) ++start[R.longest - (indptr[i + 1] - indptr[i]) + 1];
+    for (size_t k = 1; k < start.size(); ++k) start[k] += start[k - 1];
+    R.order.resize(rows);
+    for (int32_t i = 0; i < rows; ++i) R.order[start[R.longest - (indptr[i + 1] - indptr[i])]++] = i;
+    return R;
+}
+
 // Rows are grouped by the number of waves that share one row: 2^lg, the smallest power of two
 // that leaves each wave at most `target` stored entries, target = nnz / 4096 kept within 8..64
 // (measured: with every gather of a pass in flight, fewer and longer shares beat more waves).  A
@@ -201,7 +238,7 @@ struct RowPlan {
 
 // skip_upto >= 0: rows with at most that many entries are left out (they go to the packed path);
 // only_upto: rows with more entries than that are left out (they go to the staged kernels).
-RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, int32_t only_upto = INT32_MAX)
+RowPlan plan_rows(int32_t rows, const int32_t *indptr, const RowsByLength &by_len, int32_t skip_upto = -1, int32_t only_upto = INT32_MAX)
 {
     RowPlan P;
     const int64_t nnz = indptr[rows];
@@ -216,22 +253,15 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, i
     const int64_t block_cap = huge_target * kWavesPerBlock;
     int max_lg = 0;
     while ((1 << max_lg) < kWavesPerBlock) ++max_lg;
-    std::vector<int8_t> lg_of(rows);
+    std::vector<int8_t> ordinary(rows);
     std::vector<int32_t> count(max_lg + 1, 0);
     const bool row_split_only = g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT;
-    for (int32_t i = 0; i < rows; ++i) {
+    int32_t n_ordinary = 0;
+    for (int32_t i = 0; i < rows; ++i) {   // huge rows keep row order: their work-groups are also their scratch slots
         const int64_t n = indptr[i + 1] - indptr[i];
-        if (n <= skip_upto || n > only_upto) {
-            lg_of[i] = -2;
-            continue;
-        }
-        if (row_split_only) {  // one wave per row whatever its length
-            lg_of[i] = 0;
-            ++count[0];
-            continue;
-        }
-        if (n > 4 * block_cap) {
-            lg_of[i] = -1;
+        ordinary[i] = 0;
+        if (n <= skip_upto || n > only_upto) continue;
+        if (!row_split_only && n > 4 * block_cap) {
             const int32_t parts = static_cast<int32_t>((n + 2 * block_cap - 1) / (2 * block_cap));
             const int64_t share = (n + parts - 1) / parts;
             const int32_t first = P.n_blocks();
@@ -244,53 +274,49 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, i
             continue;
         }
         int lg = 0;
-        while (lg < max_lg && (n + (1 << lg) - 1) / (1 << lg) > target) ++lg;
-        lg_of[i] = static_cast<int8_t>(lg);
+        if (!row_split_only)   // (plain row splitting: one wave per row whatever its length)
+            while (lg < max_lg && (n + (1 << lg) - 1) / (1 << lg) > target) ++lg;
+        ordinary[i] = 1;
         ++count[lg];
+        ++n_ordinary;
     }
     P.n_huge_blocks = P.n_blocks();
     // A class whose rows do not fill its last work-group hands that work-group's rows (its longest)
     // to the next class, twice the waves per row, if that class's own last work-group has room for
     // them: one work-group fewer to schedule.  (The 1024 x 3072
     // layer of the paper's MLP at 90 % sparsity has 1023 rows of one class and 1 of the next: 513
-    // work-groups on a chip that holds 512 at a time.)
+    // work-groups on a chip that holds 512 at a time.)  The class is monotone in the row's length, so
+    // in the order "longest first" every class is one run of rows and the rows handed up are the
+    // first of their class's run: only the counts move.
     if (!row_split_only && skip_upto < 0 && only_upto == INT32_MAX) {
-        std::vector<int32_t> by_len;
         for (int lg = 0; lg < max_lg; ++lg) {
             const int32_t left_over = count[lg] % (kWavesPerBlock >> lg), above = kWavesPerBlock >> (lg + 1);
             // ... where the next class has room for them in a work-group it needs anyway
             if (!left_over || (count[lg + 1] + left_over + above - 1) / above != (count[lg + 1] + above - 1) / above) continue;
-            by_len.clear();
-            for (int32_t i = 0; i < rows; ++i)
-                if (lg_of[i] == lg) by_len.push_back(i);
-            std::stable_sort(by_len.begin(), by_len.end(), [&](int32_t x, int32_t y) {
-                return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
-            });
-            for (int32_t k = 0; k < left_over; ++k) lg_of[by_len[k]] = static_cast<int8_t>(lg + 1);
             count[lg] -= left_over;
             count[lg + 1] += left_over;
         }
     }
-    for (int lg = max_lg; lg >= 0; --lg) {
-        if (!count[lg]) continue;
-        const int32_t begin = static_cast<int32_t>(P.row_order.size());
-        for (int32_t i = 0; i < rows; ++i)
-            if (lg_of[i] == lg) P.row_order.push_back(i);
-        const int32_t end = static_cast<int32_t>(P.row_order.size());
-        // longest first inside the class (ties in row order): the rows of a work-group are alike,
-        // and the work-groups that take longest start first
-        std::stable_sort(P.row_order.begin() + begin, P.row_order.begin() + end, [&](int32_t x, int32_t y) {
-            return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
-        });
-        const int32_t per_block = kWavesPerBlock >> lg;
-        for (int32_t f = begin; f < end; f += per_block) {
-            const int32_t n_rows = end - f < per_block ? end - f : per_block;
-            P.blocks.insert(P.blocks.end(), {lg | (n_rows << 8), f, 0, 0});
+    // ordinary rows longest first, ties in row order: the classes follow each other, heaviest first, and
+    // inside a class the rows of a work-group are alike and the work-groups that take longest start first
+    P.row_order.reserve(n_ordinary);
+    for (int32_t r : by_len.order)
+        if (ordinary[r]) P.row_order.push_back(r);
+    {
+        int32_t f = 0;
+        for (int lg = max_lg; lg >= 0; --lg) {
+            const int32_t end = f + count[lg], per_block = kWavesPerBlock >> lg;
+            for (; f < end; f += per_block) {
+                const int32_t n_rows = end - f < per_block ? end - f : per_block;
+                P.blocks.insert(P.blocks.end(), {lg | (n_rows << 8), f, 0, 0});
+            }
+            f = end;
         }
     }
     // The same partition per wave: each of the 2^lg waves of a row takes a contiguous share of
     // its entries, a multiple of 4 entries long (the kernels work on 1, 2 or 4 entries at a time).
-    P.waves.reserve(P.blocks.size() * kWavesPerBlock);
+    P.waves.resize(P.blocks.size() * kWavesPerBlock);
+    int32_t *out = P.waves.data();
     for (int32_t b = 0; b < P.n_blocks(); ++b) {
         const int32_t info = P.blocks[4 * b], y = P.blocks[4 * b + 1];
         const bool huge = (info & kHugeFlag) != 0;
@@ -312,8 +338,10 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, i
             per = (per + 3) / 4 * 4;
             const int64_t s0 = p0 + part * per < p1 ? p0 + part * per : p1;
             const int64_t s1 = s0 + per < p1 ? s0 + per : p1;
-            P.waves.insert(P.waves.end(), {row, static_cast<int32_t>(s0), static_cast<int32_t>(s1),
-                                           part | (lg << 4) | (lead ? 256 : 0) | (huge ? 512 : 0)});
+            *out++ = row;
+            *out++ = static_cast<int32_t>(s0);
+            *out++ = static_cast<int32_t>(s1);
+            *out++ = part | (lg << 4) | (lead ? 256 : 0) | (huge ? 512 : 0);
         }
     }
     return P;
@@ -322,71 +350,68 @@ RowPlan plan_rows(int32_t rows, const int32_t *indptr, int32_t skip_upto = -1, i
 // Rows of at most kPackMaxLen entries, longest first (ties in row order), 4 ints per row
 // {row, first entry, entries, 0}, padded with {-1, 0, 0, 0} to a multiple of 64 rows.  Empty when
 // there are fewer than kPackMinRows of them: the packed path pays off on large matrices only.
-std::vector<int32_t> short_row_table(int32_t rows, const int32_t *indptr, int32_t *n_short)
+std::vector<int32_t> short_row_table(int32_t rows, const int32_t *indptr, const RowsByLength &by_len, int32_t *n_short)
 {
-    std::vector<int32_t> count(kPackMaxLen + 2, 0);
     int32_t n = 0;
-    for (int32_t i = 0; i < rows; ++i) {
-        const int64_t len = indptr[i + 1] - indptr[i];
-        if (len <= kPackMaxLen) { ++count[kPackMaxLen - len + 1]; ++n; }
-    }
+    for (int32_t i = 0; i < rows; ++i) n += indptr[i + 1] - indptr[i] <= kPackMaxLen;
     *n_short = 0;
     std::vector<int32_t> t;
     if (n < kPackMinRows || indptr[rows] == 0 || g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT) return t;
-    for (int k = 1; k <= kPackMaxLen + 1; ++k) count[k] += count[k - 1];  // counting sort by descending length
     t.assign(static_cast<size_t>(round_up(n, 64)) * 4, 0);
     for (int64_t k = n; k < round_up(n, 64); ++k) t[4 * k] = -1;
-    for (int32_t i = 0; i < rows; ++i) {
-        const int64_t len = indptr[i + 1] - indptr[i];
+    int32_t k = 0;
+    for (int32_t i : by_len.order) {
+        const int32_t len = indptr[i + 1] - indptr[i];
         if (len > kPackMaxLen) continue;
-        const int32_t k = count[kPackMaxLen - len]++;
-        t[4 * k] = i; t[4 * k + 1] = indptr[i]; t[4 * k + 2] = static_cast<int32_t>(len);
+        t[4 * k] = i; t[4 * k + 1] = indptr[i]; t[4 * k + 2] = len;
+        ++k;
     }
     *n_short = n;
     return t;
 }
 
 // Share of the stored entries that gather one of the kHotRows most referenced operand rows;
-// other_indptr is the row-pointer array of the transposed orientation (its row lengths are the
-// reference counts).
-float hot_row_share(int32_t other_rows, const int32_t *other_indptr)
+// `other` is the transposed orientation (its row lengths are the reference counts).
+float hot_row_share(int32_t other_rows, const int32_t *other_indptr, const RowsByLength &other_by_len)
 {
     const int64_t nnz = other_indptr[other_rows];
     if (nnz == 0) return 0.f;
     if (other_rows <= kHotRows) return 1.f;
-    std::vector<int32_t> len(other_rows);
-    for (int32_t i = 0; i < other_rows; ++i) len[i] = other_indptr[i + 1] - other_indptr[i];
-    std::nth_element(len.begin(), len.begin() + kHotRows, len.end(), std::greater<int32_t>());
     int64_t top = 0;
-    for (int32_t i = 0; i < kHotRows; ++i) top += len[i];
+    for (int32_t k = 0; k < kHotRows; ++k) {
+        const int32_t r = other_by_len.order[k];
+        top += other_indptr[r + 1] - other_indptr[r];
+    }
     return static_cast<float>(static_cast<double>(top) / static_cast<double>(nnz));
 }
 
-// Row ranges, slot order and segment bounds of the staged product (RowBlocks::staged_*) for a
-// matrix whose products run at up to max_batch columns; empty when that product would never be chosen.
+// Row ranges and slot order of the staged product (RowBlocks::staged_*) for a matrix whose products
+// run at up to max_batch columns; empty when that product would never be chosen.  The segment
+// bounds (`ends`) depend on the column indices: the host API fills them here, a layer on the device.
 struct StagedPlan {
     std::vector<int32_t> rows;    // [ranges * kStageRangeRows]
-    std::vector<int32_t> ends;    // [ranges * (cblocks + 1) * kStageRangeRows]
+    std::vector<int32_t> ends;    // [ranges * (cblocks + 1) * kStageRangeRows] (host API only)
     std::vector<int32_t> groups;  // [ranges]
     int32_t ranges = 0, cblocks = 0;
     int32_t longest_share = 0;    // most entries any one slot serves
     int32_t n_rows = 0;           // rows the plan covers
     int64_t nnz = 0;              // and their stored entries
+    size_t ends_ints() const { return static_cast<size_t>(ranges) * (cblocks + 1) * kStageRangeRows; }
 };
 
-StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const int32_t *indices, int32_t max_batch,
+StagedPlan plan_staged(int32_t all_rows, int32_t cols, const int32_t *indptr, const RowsByLength &by_len, int32_t max_batch,
                        int32_t min_len = 0)
 {
     StagedPlan H;
     // the rows the plan covers: all of them, or those of at least min_len stored entries
     std::vector<int32_t> covered;
     int64_t nnz = 0;
-    for (int32_t r = 0; r < rows; ++r)
+    for (int32_t r = 0; r < all_rows; ++r)
         if (indptr[r + 1] - indptr[r] >= min_len) {
             covered.push_back(r);
             nnz += indptr[r + 1] - indptr[r];
         }
-    rows = static_cast<int32_t>(covered.size());  // from here on: rows of the plan, covered[k] their ids
+    const int32_t rows = static_cast<int32_t>(covered.size());  // from here on: rows of the plan, covered[k] their ids
     const bool preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
     if (g_partition_mode.load() == NERVA_PARTITION_ROW_SPLIT || max_batch < kStageMinBatch || nnz == 0) return H;
     const int32_t n_tiles = (max_batch + kStageCols - 1) / kStageCols;
@@ -415,7 +440,8 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
     // quarter of every segment ("quad": four slots, group-aligned).
     const int64_t quad_len = std::max<int64_t>(256, total / want / 32);
     auto slots_of = [&](int32_t r) { return indptr[r + 1] - indptr[r] >= quad_len ? 4 : 1; };
-    std::vector<int32_t> first_row{0};
+    std::vector<int32_t> range_of(all_rows, -1);
+    int32_t ranges = 0;
     {
         int32_t range = 0, in_range = 0;
         int64_t done = 0;
@@ -423,139 +449,179 @@ StagedPlan plan_staged(int32_t rows, int32_t cols, const int32_t *indptr, const 
             const int32_t r = covered[k];
             const bool next = range + 1 < want && done * want >= total * (range + 1);
             if ((next || in_range + slots_of(r) > kStageRangeRows) && in_range > 0) {
-                first_row.push_back(k);
+                ++ranges;
                 in_range = 0;
             }
             if (next) ++range;
             done += cost(r);
             in_range += slots_of(r);
+            range_of[r] = ranges;
         }
-        first_row.push_back(rows);
+        ++ranges;
     }
-    const int32_t ranges = static_cast<int32_t>(first_row.size()) - 1;
     H.ranges = ranges;
     H.cblocks = cblocks;
     H.n_rows = rows;
     H.nnz = nnz;
     H.rows.assign(static_cast<size_t>(ranges) * kStageRangeRows, -1);
-    H.ends.assign(static_cast<size_t>(ranges) * (cblocks + 1) * kStageRangeRows, 0);
-    H.groups.resize(ranges);
-    std::vector<int32_t> order;
-    for (int32_t q = 0; q < ranges; ++q) {
-        const int32_t r0 = first_row[q], n = first_row[q + 1] - r0;
-        order.resize(n);
-        for (int32_t i = 0; i < n; ++i) order[i] = covered[r0 + i];
-        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
-            return indptr[x + 1] - indptr[x] > indptr[y + 1] - indptr[y];
-        });
-        int32_t *e = H.ends.data() + static_cast<size_t>(q) * (cblocks + 1) * kStageRangeRows;
-        int32_t slot = 0;  // quads come first (longest rows), so they start at multiples of 4
-        for (int32_t i = 0; i < n; ++i) {
-            const int32_t r = order[i], copies = slots_of(r);
-            const int32_t len = indptr[r + 1] - indptr[r];
-            const int32_t share = copies == 4 ? (len + 3) / 4 : len;
-            if (share > H.longest_share) H.longest_share = share;
-            const int32_t *lo = indices + indptr[r], *hi = indices + indptr[r + 1];
-            for (int32_t b = 0; b <= cblocks; ++b) {
-                if (b > 0) lo = std::lower_bound(lo, hi, b * kStageRows);
-                for (int32_t c = 0; c < copies; ++c)
-                    e[static_cast<size_t>(b) * kStageRangeRows + slot + c] = static_cast<int32_t>(lo - indices);
-            }
-            for (int32_t c = 0; c < copies; ++c)
-                H.rows[static_cast<size_t>(q) * kStageRangeRows + slot + c] = copies == 4 ? (r | kStageQuad) : r;
-            slot += copies;
-        }
-        H.groups[q] = (slot + 63) / 64;
+    H.groups.assign(ranges, 0);
+    // inside a range: longest first, ties in row order -- the global order, read range by range;
+    // quads come first (the longest rows), so they start at multiples of 4
+    std::vector<int32_t> slot(ranges, 0);
+    for (int32_t r : by_len.order) {
+        const int32_t q = range_of[r];
+        if (q < 0) continue;
+        const int32_t copies = slots_of(r), len = indptr[r + 1] - indptr[r];
+        const int32_t share = copies == 4 ? (len + 3) / 4 : len;
+        if (share > H.longest_share) H.longest_share = share;
+        for (int32_t c = 0; c < copies; ++c)
+            H.rows[static_cast<size_t>(q) * kStageRangeRows + slot[q] + c] = copies == 4 ? (r | kStageQuad) : r;
+        slot[q] += copies;
     }
+    for (int32_t q = 0; q < ranges; ++q) H.groups[q] = (slot[q] + 63) / 64;
     return H;
 }
 
-hipError_t upload_plan(int32_t rows, const int32_t *indptr_host, const int32_t *indices_host, int32_t max_batch,
-                       int32_t other_rows, const int32_t *other_indptr_host,
-                       int32_t **mem, RowBlocks *plan, hipStream_t s, std::vector<int32_t> &staging)
+// the segment bounds of a plan from host copies of the pattern (what staged_ends_kernel computes for a layer)
+void fill_staged_ends_host(StagedPlan &H, const int32_t *indptr, const int32_t *indices)
 {
-    const RowPlan P = plan_rows(rows, indptr_host);
+    H.ends.assign(H.ends_ints(), 0);
+    for (int32_t q = 0; q < H.ranges; ++q) {
+        int32_t *e = H.ends.data() + static_cast<size_t>(q) * (H.cblocks + 1) * kStageRangeRows;
+        for (int32_t slot = 0; slot < kStageRangeRows; ++slot) {
+            int32_t r = H.rows[static_cast<size_t>(q) * kStageRangeRows + slot];
+            if (r < 0) continue;
+            r &= ~kStageQuad;
+            const int32_t *lo = indices + indptr[r], *hi = indices + indptr[r + 1];
+            for (int32_t b = 0; b <= H.cblocks; ++b) {
+                if (b > 0) lo = std::lower_bound(lo, hi, b * kStageRows);
+                e[static_cast<size_t>(b) * kStageRangeRows + slot] = static_cast<int32_t>(lo - indices);
+            }
+        }
+    }
+}
+
+// All partitions of one orientation of a pattern, planned on the host from its row pointers, laid
+// out as they go to the device: `staging` is copied to the start of the plan's device memory, the
+// segment bounds of the staged plan (ends_ints ints, computed on the device) follow it.
+struct HostPlan {
+    std::vector<int32_t> staging;
+    size_t blocks_at = 0, huge_at = 0, waves_at = 0, staged_at = 0, long_at = 0, rest_at = 0, short_at = 0, order_at = 0, groups_at = 0;
+    size_t ends_ints = 0;
+    RowBlocks view{};   // counts and flags filled in; pointers are set once the device address is known
+    size_t total_ints() const { return staging.size() + ends_ints; }
+};
+
+HostPlan make_plan(int32_t rows, const int32_t *indptr_host, const RowsByLength &by_len, int32_t max_batch, int32_t other_rows,
+                   float hot_share)
+{
+    HostPlan hp;
+    const RowPlan P = plan_rows(rows, indptr_host, by_len);
     int32_t n_short = 0;
-    const std::vector<int32_t> short_rows = short_row_table(rows, indptr_host, &n_short);
-    int32_t longest_row = 0;
-    for (int32_t r = 0; r < rows; ++r) longest_row = std::max(longest_row, indptr_host[r + 1] - indptr_host[r]);
+    const std::vector<int32_t> short_rows = short_row_table(rows, indptr_host, by_len, &n_short);
+    const int32_t longest_row = by_len.longest;
     // The staged product serves all rows, or, where the rows differ widely in length and the short
     // ones have the packed path to go to, the rows beyond that path's length limit only.
     StagedPlan H;
     bool staged_partial = false;
     if (n_short > 0 && n_short < rows && g_partition_mode.load() == NERVA_PARTITION_BALANCED &&
         static_cast<int64_t>(longest_row) * rows > 4 * static_cast<int64_t>(indptr_host[rows])) {
-        H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch, kPackMaxLen + 1);
+        H = plan_staged(rows, other_rows, indptr_host, by_len, max_batch, kPackMaxLen + 1);
         staged_partial = H.ranges > 0;
     }
-    if (!staged_partial) H = plan_staged(rows, other_rows, indptr_host, indices_host, max_batch);
+    if (!staged_partial) H = plan_staged(rows, other_rows, indptr_host, by_len, max_batch);
     RowPlan Q, Z;
-    if (n_short > 0) Q = plan_rows(rows, indptr_host, kPackMaxLen);
-    if (staged_partial) Z = plan_rows(rows, indptr_host, -1, kPackMaxLen);  // the short rows' partition for the SDDMM
+    if (n_short > 0) Q = plan_rows(rows, indptr_host, by_len, kPackMaxLen);
+    if (staged_partial) Z = plan_rows(rows, indptr_host, by_len, -1, kPackMaxLen);  // the short rows' partition for the SDDMM
     // 16-byte records first so that they stay 16-byte aligned
-    staging = P.blocks;
-    staging.insert(staging.end(), P.huge_rows.begin(), P.huge_rows.end());
-    staging.insert(staging.end(), P.waves.begin(), P.waves.end());
-    const size_t staged_at = staging.size();
-    staging.insert(staging.end(), H.rows.begin(), H.rows.end());  // (multiples of kStageRangeRows: what follows stays 16-byte aligned)
-    staging.insert(staging.end(), H.ends.begin(), H.ends.end());
-    const size_t long_at = staging.size();
-    staging.insert(staging.end(), Q.waves.begin(), Q.waves.end());
-    const size_t rest_at = staging.size();
-    staging.insert(staging.end(), Z.waves.begin(), Z.waves.end());
-    const size_t short_at = staging.size();
-    staging.insert(staging.end(), short_rows.begin(), short_rows.end());
-    const size_t order_at = staging.size();
-    staging.insert(staging.end(), P.row_order.begin(), P.row_order.end());
-    const size_t groups_at = staging.size();
-    staging.insert(staging.end(), H.groups.begin(), H.groups.end());
-    if (staging.empty()) staging.push_back(0);
-    hipError_t e = hipMalloc(mem, staging.size() * 4);
-    if (e != hipSuccess) return e;
-    e = hipMemcpyAsync(*mem, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, s);
-    plan->blocks = reinterpret_cast<const int4 *>(*mem);
-    plan->huge_rows = reinterpret_cast<const int4 *>(*mem + P.blocks.size());
-    plan->waves = reinterpret_cast<const int4 *>(*mem + P.blocks.size() + P.huge_rows.size());
-    plan->row_order = *mem + order_at;
-    plan->long_waves = reinterpret_cast<const int4 *>(*mem + long_at);
-    plan->short_rows = reinterpret_cast<const int4 *>(*mem + short_at);
-    plan->n_short = n_short;
-    plan->hot_share = hot_row_share(other_rows, other_indptr_host);
-    plan->n_long_blocks = Q.n_blocks();
-    plan->n_blocks = P.n_blocks();
-    plan->n_huge_rows = P.n_huge_rows();
-    plan->n_huge_blocks = P.n_huge_blocks;
-    plan->staged_rows = H.ranges ? *mem + staged_at : nullptr;
-    plan->staged_ends = H.ranges ? *mem + staged_at + H.rows.size() : nullptr;
-    plan->staged_groups = H.ranges ? *mem + groups_at : nullptr;
-    plan->staged_ranges = H.ranges;
-    plan->staged_cblocks = H.cblocks;
-    plan->staged_preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
-    plan->staged_longest_share = H.longest_share;
-    plan->staged_longest_row = longest_row;
-    plan->staged_partial = staged_partial;
-    plan->rest_waves = reinterpret_cast<const int4 *>(*mem + rest_at);
-    plan->n_rest_blocks = Z.n_blocks();
-    plan->staged_row_count = H.n_rows;
-    plan->staged_nnz = static_cast<int32_t>(H.nnz);
-    return e;
+    std::vector<int32_t> &st = hp.staging;
+    st.reserve(P.blocks.size() + P.huge_rows.size() + P.waves.size() + H.rows.size() + Q.waves.size() + Z.waves.size() +
+               short_rows.size() + P.row_order.size() + H.groups.size() + 1);
+    hp.blocks_at = st.size(); st.insert(st.end(), P.blocks.begin(), P.blocks.end());
+    hp.huge_at = st.size(); st.insert(st.end(), P.huge_rows.begin(), P.huge_rows.end());
+    hp.waves_at = st.size(); st.insert(st.end(), P.waves.begin(), P.waves.end());
+    hp.staged_at = st.size(); st.insert(st.end(), H.rows.begin(), H.rows.end());  // (multiples of kStageRangeRows: what follows stays 16-byte aligned)
+    hp.long_at = st.size(); st.insert(st.end(), Q.waves.begin(), Q.waves.end());
+    hp.rest_at = st.size(); st.insert(st.end(), Z.waves.begin(), Z.waves.end());
+    hp.short_at = st.size(); st.insert(st.end(), short_rows.begin(), short_rows.end());
+    hp.order_at = st.size(); st.insert(st.end(), P.row_order.begin(), P.row_order.end());
+    hp.groups_at = st.size(); st.insert(st.end(), H.groups.begin(), H.groups.end());
+    if (st.empty()) st.push_back(0);
+    hp.ends_ints = H.ends_ints();
+    RowBlocks &v = hp.view;
+    v.n_short = n_short;
+    v.hot_share = hot_share;
+    v.n_long_blocks = Q.n_blocks();
+    v.n_blocks = P.n_blocks();
+    v.n_huge_rows = P.n_huge_rows();
+    v.n_huge_blocks = P.n_huge_blocks;
+    v.staged_ranges = H.ranges;
+    v.staged_cblocks = H.cblocks;
+    v.staged_preferred = g_partition_mode.load() == NERVA_PARTITION_PREFER_STAGED;
+    v.staged_longest_share = H.longest_share;
+    v.staged_longest_row = longest_row;
+    v.staged_partial = staged_partial;
+    v.n_rest_blocks = Z.n_blocks();
+    v.staged_row_count = H.n_rows;
+    v.staged_nnz = static_cast<int32_t>(H.nnz);
+    return hp;
+}
+
+// the plan's tables at their device address
+RowBlocks plan_view(const HostPlan &hp, const int32_t *mem)
+{
+    RowBlocks v = hp.view;
+    v.blocks = reinterpret_cast<const int4 *>(mem + hp.blocks_at);
+    v.huge_rows = reinterpret_cast<const int4 *>(mem + hp.huge_at);
+    v.waves = reinterpret_cast<const int4 *>(mem + hp.waves_at);
+    v.row_order = mem + hp.order_at;
+    v.long_waves = reinterpret_cast<const int4 *>(mem + hp.long_at);
+    v.rest_waves = reinterpret_cast<const int4 *>(mem + hp.rest_at);
+    v.short_rows = reinterpret_cast<const int4 *>(mem + hp.short_at);
+    v.staged_rows = v.staged_ranges ? mem + hp.staged_at : nullptr;
+    v.staged_ends = v.staged_ranges ? mem + hp.staging.size() : nullptr;
+    v.staged_groups = v.staged_ranges ? mem + hp.groups_at : nullptr;
+    return v;
+}
+
+void free_pattern_buffers(PatternBuffers &b)
+{
+    (void)hipFree(b.indptr_t);
+    (void)hipFree(b.mirror_mem);
+    (void)hipFree(b.plan_mem);
+    (void)hipFree(b.plan_t_mem);
+    b = PatternBuffers{};
 }
 
 void free_layer_buffers(nerva_layer *l)
 {
-    (void)hipFree(l->plan_mem);
-    (void)hipFree(l->plan_t_mem);
+    free_pattern_buffers(l->cur);
+    free_pattern_buffers(l->spare);
+    (void)hipFree(l->build_work);
+    (void)hipFree(l->status);
     (void)hipFree(l->scratch);
-    (void)hipFree(l->indptr_t);
-    (void)hipFree(l->indices_t);
-    (void)hipFree(l->values_t);
     (void)hipFree(l->partial);
     (void)hipFree(l->dense);
     (void)hipFree(l->dense_t);
     (void)hipFree(l->dense_scratch);
     (void)hipFree(l->full_scratch);
-    (void)hipFree(l->perm);
-    (void)hipFree(l->pos_t);
+}
+
+// Room for `need` elements of 4 bytes in *ptr, whose capacity is *have: kept if large enough, else
+// replaced by a larger allocation (the old contents are not kept).  On failure nothing changes.
+template <typename T>
+hipError_t reserve(T **ptr, size_t *have, size_t need)
+{
+    if (need <= *have && *ptr) return hipSuccess;
+    if (need == 0) need = 1;
+    const size_t want = need + need / 8;
+    void *fresh = nullptr;
+    const hipError_t e = hipMalloc(&fresh, want * 4);
+    if (e != hipSuccess) return e;
+    (void)hipFree(*ptr);
+    *ptr = static_cast<T *>(fresh);
+    *have = want;
+    return hipSuccess;
 }
 
 // Marks the start of one launch with an event while profiling is on; costs one branch otherwise.
@@ -627,7 +693,7 @@ int nerva_plan_rows_host(int32_t rows, const int32_t *indptr_host, int32_t *row_
                          int32_t *blocks_host, int32_t *huge_rows_host, int32_t *waves_host, int32_t *counts_host)
 {
     if (rows <= 0 || !indptr_host || !counts_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
-    const RowPlan P = plan_rows(rows, indptr_host);
+    const RowPlan P = plan_rows(rows, indptr_host, rows_by_length(rows, indptr_host));
     counts_host[0] = static_cast<int32_t>(P.row_order.size());
     counts_host[1] = P.n_blocks();
     counts_host[2] = P.n_huge_rows();
@@ -644,9 +710,10 @@ int nerva_plan_short_rows_host(int32_t rows, const int32_t *indptr_host, int32_t
 {
     if (rows <= 0 || !indptr_host || !counts_host) return fail(NERVA_ERR_ARGUMENT, "bad argument");
     int32_t n_short = 0;
-    const std::vector<int32_t> t = short_row_table(rows, indptr_host, &n_short);
+    const RowsByLength by_len = rows_by_length(rows, indptr_host);
+    const std::vector<int32_t> t = short_row_table(rows, indptr_host, by_len, &n_short);
     RowPlan Q;
-    if (n_short > 0) Q = plan_rows(rows, indptr_host, kPackMaxLen);
+    if (n_short > 0) Q = plan_rows(rows, indptr_host, by_len, kPackMaxLen);
     counts_host[0] = n_short;
     counts_host[1] = Q.n_blocks();
     counts_host[2] = Q.n_huge_blocks;
@@ -663,7 +730,8 @@ int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_hos
         return fail(NERVA_ERR_ARGUMENT, "bad argument");
     static_assert(NERVA_STAGE_ROWS == kStageRows && NERVA_STAGE_COLS == kStageCols && NERVA_STAGE_MIN_BATCH == kStageMinBatch &&
                   NERVA_STAGE_RANGE_ROWS == kStageRangeRows && NERVA_STAGE_QUAD == kStageQuad, "header and kernels disagree");
-    const StagedPlan H = plan_staged(rows, cols, indptr_host, indices_host, max_batch, min_entries);
+    StagedPlan H = plan_staged(rows, cols, indptr_host, rows_by_length(rows, indptr_host), max_batch, min_entries);
+    if (ends_host && H.ranges) fill_staged_ends_host(H, indptr_host, indices_host);
     counts_host[0] = H.ranges;
     counts_host[1] = H.cblocks;
     if (slot_rows_host && !H.rows.empty()) memcpy(slot_rows_host, H.rows.data(), H.rows.size() * 4);
@@ -719,85 +787,130 @@ static hipError_t dense_transposed(const nerva_layer *l, const float *dZ, int64_
 // the dense route needs a batch wide enough to fill its 32-column tiles
 static bool use_dense(const nerva_layer *l, int32_t batch) { return l->dense_on && batch >= 16; }
 
-// Everything a pattern allows to be precomputed, for a layer whose sizes, caller-owned arrays
-// and max_batch are set and whose owned pointers are all null: validates the CSR, builds the mirror
-// and the position maps (host counting sort), the two partitions and the work buffers.  On failure
-// the layer owns nothing.
-static int build_structures(nerva_layer *l, hipStream_t s)
+// Message for the status word of the device-side CSR check (launch_validate_csr).
+static int csr_status_error(const int32_t *st)
 {
-    const int32_t rows = l->rows, cols = l->cols, nnz = l->nnz, max_batch = l->max_batch;
-    const int32_t *indptr = l->indptr, *indices = l->indices;
-    float *values = l->values;
-    std::vector<int32_t> h_indptr(static_cast<size_t>(rows) + 1), h_indices(static_cast<size_t>(nnz));
+    const int f = st[0];
+    if (f & kCsrBadFirst) return fail(NERVA_ERR_CSR, "indptr[0] is not 0");
+    if (f & kCsrDecreasing) return fail(NERVA_ERR_CSR, "indptr decreases at row %d", st[1]);
+    if (f & kCsrBeyondNnz) return fail(NERVA_ERR_CSR, "indptr[%d] lies outside [0, nnz]", st[1]);
+    if (f & kCsrBadLast) return fail(NERVA_ERR_CSR, "indptr[rows] differs from nnz");
+    if (f & kCsrColumnRange) return fail(NERVA_ERR_CSR, "column index out of range at position %d", st[2]);
+    if (f & kCsrNotAscending) return fail(NERVA_ERR_CSR, "column indices not strictly ascending at position %d", st[2]);
+    return fail(NERVA_ERR_CSR, "pattern is not canonical CSR (status 0x%x)", f);
+}
+
+// Everything a pattern allows to be precomputed, for a layer `l` that describes the NEW pattern (sizes,
+// caller-owned arrays, max_batch) and owns the buffers to build into: l->spare receives the mirror and the
+// partition tables (l->cur, if any, is not touched), the scratch buffers grow as needed.  What grows with
+// the stored entries runs on the device: the CSR check, the mirror with its position maps (a stable
+// counting sort by column) and the staged plans' segment bounds; the row partitions, which depend on the
+// row lengths only, are planned on the host from copies of the two row-pointer arrays.  On failure
+// (NERVA_ERR_CSR, NERVA_ERR_HIP) nothing that a product reads has been changed.  On success the caller swaps
+// l->spare into l->cur and adopts `plan`, `plan_t`.
+struct BuiltPattern {
+    RowBlocks plan{}, plan_t{};
+    int64_t partial_stride = 0, partial_db_at = 0;
+    int32_t partial_tiles = 0;
+    int64_t scratch_ld = 0, full_scratch_ld = 0;
+    bool full = false;
+};
+
+static int build_structures(nerva_layer *l, int32_t nnz, const int32_t *indptr, const int32_t *indices, const float *values,
+                            BuiltPattern *out, hipStream_t s)
+{
+    const int32_t rows = l->rows, cols = l->cols, max_batch = l->max_batch;
+    PatternBuffers &B = l->spare;
+    // 1. the pattern is checked where it lives; the row pointers come to the host for the partitions
+    std::vector<int32_t> h_indptr(static_cast<size_t>(rows) + 1), h_indptr_t(static_cast<size_t>(cols) + 1);
+    int32_t h_status[4] = {0, 0, 0, 0};
+    if (!l->status) HIP_TRY(hipMalloc(&l->status, 4 * sizeof(int32_t)));
+    HIP_TRY(launch_validate_csr(rows, cols, nnz, indptr, indices, l->status, s));
     HIP_TRY(hipMemcpyAsync(h_indptr.data(), indptr, h_indptr.size() * 4, hipMemcpyDeviceToHost, s));
-    if (nnz) HIP_TRY(hipMemcpyAsync(h_indices.data(), indices, h_indices.size() * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(h_status, l->status, sizeof h_status, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    int rc = nerva_validate_csr_host(rows, cols, nnz, h_indptr.data(), h_indices.data());
-    if (rc != NERVA_OK) return rc;
+    if (h_status[0] != 0) return csr_status_error(h_status);
 
-    // Counting sort of the stored entries by column; ties keep row order, so the mirror is
-    // the canonical CSR of W^T.  Integer work, done when a pattern is bound, not per step.
-    std::vector<int32_t> h_indptr_t(static_cast<size_t>(cols) + 1, 0), h_indices_t(nnz), h_perm(nnz), h_pos_t(nnz);
-    for (int32_t p = 0; p < nnz; ++p) ++h_indptr_t[h_indices[p] + 1];
-    for (int32_t j = 0; j < cols; ++j) h_indptr_t[j + 1] += h_indptr_t[j];
+    // 2. the mirror, on the device, into the spare set
+    const size_t n64 = static_cast<size_t>(round_up(nnz > 0 ? nnz : 1, 64));
+    const int32_t T = mirror_tiles(rows, cols, nnz);
+    size_t indptr_t_have = B.indptr_t ? static_cast<size_t>(cols) + 1 : 0;
+    HIP_TRY(reserve(&B.indptr_t, &indptr_t_have, static_cast<size_t>(cols) + 1));
+    HIP_TRY(reserve(&B.mirror_mem, &B.mirror_ints, 4 * n64));
+    HIP_TRY(reserve(&l->build_work, &l->build_work_ints, mirror_work_ints(cols, T)));
+    int32_t *indices_t = B.mirror_mem, *perm = B.mirror_mem + n64, *pos_t = B.mirror_mem + 2 * n64;
+    float *values_t = reinterpret_cast<float *>(B.mirror_mem + 3 * n64);
+    HIP_TRY(launch_build_mirror(rows, cols, nnz, indptr, indices, B.indptr_t, indices_t, perm, pos_t, l->build_work, T, s));
+    HIP_TRY(hipMemcpyAsync(h_indptr_t.data(), B.indptr_t, h_indptr_t.size() * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(launch_gather(values_t, values, perm, nnz, s));
+    // ... while the host orders the rows by length
+    const RowsByLength by_len = rows_by_length(rows, h_indptr.data());
+    HIP_TRY(hipStreamSynchronize(s));
+    const RowsByLength by_len_t = rows_by_length(cols, h_indptr_t.data());
+
+    // 3. the partitions of both orientations (integer work on row lengths), then their tables to the device
+    const HostPlan hp = make_plan(rows, h_indptr.data(), by_len, max_batch, cols, hot_row_share(cols, h_indptr_t.data(), by_len_t));
+    const HostPlan hp_t = make_plan(cols, h_indptr_t.data(), by_len_t, max_batch, rows, hot_row_share(rows, h_indptr.data(), by_len));
+    HIP_TRY(reserve(&B.plan_mem, &B.plan_ints, hp.total_ints()));
+    HIP_TRY(reserve(&B.plan_t_mem, &B.plan_t_ints, hp_t.total_ints()));
+    HIP_TRY(hipMemcpyAsync(B.plan_mem, hp.staging.data(), hp.staging.size() * 4, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(B.plan_t_mem, hp_t.staging.data(), hp_t.staging.size() * 4, hipMemcpyHostToDevice, s));
+    out->plan = plan_view(hp, B.plan_mem);
+    out->plan_t = plan_view(hp_t, B.plan_t_mem);
+    if (out->plan.staged_ranges)
+        HIP_TRY(launch_staged_ends(indptr, indices, out->plan.staged_rows, const_cast<int32_t *>(out->plan.staged_ends),
+                                   out->plan.staged_ranges, out->plan.staged_cblocks, s));
+    if (out->plan_t.staged_ranges)
+        HIP_TRY(launch_staged_ends(B.indptr_t, indices_t, out->plan_t.staged_rows, const_cast<int32_t *>(out->plan_t.staged_ends),
+                                   out->plan_t.staged_ranges, out->plan_t.staged_cblocks, s));
+
+    // 4. scratch buffers (they hold nothing between calls: grown in place)
     {
-        std::vector<int32_t> cursor(h_indptr_t.begin(), h_indptr_t.end() - 1);
-        for (int32_t i = 0; i < rows; ++i)
-            for (int32_t p = h_indptr[i]; p < h_indptr[i + 1]; ++p) {
-                const int32_t q = cursor[h_indices[p]]++;
-                h_indices_t[q] = i;
-                h_perm[q] = p;
-                h_pos_t[p] = q;
-            }
-    }
-
-    const size_t nb = static_cast<size_t>(nnz > 0 ? nnz : 1) * 4;
-    hipError_t e = hipMalloc(&l->indptr_t, (static_cast<size_t>(cols) + 1) * 4);
-    if (e == hipSuccess) e = hipMalloc(&l->indices_t, nb);
-    if (e == hipSuccess) e = hipMalloc(&l->values_t, nb);
-    if (e == hipSuccess) e = hipMalloc(&l->perm, nb);
-    if (e == hipSuccess) e = hipMalloc(&l->pos_t, nb);
-    if (e == hipSuccess) e = hipMemcpyAsync(l->indptr_t, h_indptr_t.data(), h_indptr_t.size() * 4, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->indices_t, h_indices_t.data(), nb, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->perm, h_perm.data(), nb, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess && nnz) e = hipMemcpyAsync(l->pos_t, h_pos_t.data(), nb, hipMemcpyHostToDevice, s);
-    std::vector<int32_t> stage_a, stage_b;
-    if (e == hipSuccess) e = upload_plan(rows, h_indptr.data(), h_indices.data(), max_batch, cols, h_indptr_t.data(), &l->plan_mem, &l->plan, s, stage_a);
-    if (e == hipSuccess) e = upload_plan(cols, h_indptr_t.data(), h_indices_t.data(), max_batch, rows, h_indptr.data(), &l->plan_t_mem, &l->plan_t, s, stage_b);
-    if (e == hipSuccess) {
         // room for the column-tiled SDDMM at max_batch columns, if that batch would be tiled
-        const int w = tile_columns(cols, max_batch, nnz, rows, l->plan.hot_share, false, true);
+        const int w = tile_columns(cols, max_batch, nnz, rows, out->plan.hot_share, false, true);
         int32_t tiles = w > 0 ? (max_batch + w - 1) / w : 0;
-        if (l->plan.staged_rows && (max_batch + kStageCols - 1) / kStageCols > tiles) tiles = (max_batch + kStageCols - 1) / kStageCols;
+        if (out->plan.staged_rows && (max_batch + kStageCols - 1) / kStageCols > tiles) tiles = (max_batch + kStageCols - 1) / kStageCols;
+        out->partial_tiles = 0;
         if (tiles > 0) {
-            l->partial_tiles = tiles;
-            l->partial_db_at = round_up(nnz, 64);
-            l->partial_stride = l->partial_db_at + round_up(rows, 64);
-            const size_t bytes = static_cast<size_t>(l->partial_tiles) * l->partial_stride * 4;
-            if (bytes <= (4ull << 30))
-                e = hipMalloc(&l->partial, bytes);
-            else
-                l->partial_tiles = 0;  // too large to be worth it: the untiled kernel stays
+            out->partial_db_at = round_up(nnz, 64);
+            out->partial_stride = out->partial_db_at + round_up(rows, 64);
+            const size_t floats = static_cast<size_t>(tiles) * out->partial_stride;
+            if (floats * 4 <= (4ull << 30)) {  // (beyond that it is too large to be worth it: the untiled kernel stays)
+                HIP_TRY(reserve(&l->partial, &l->partial_floats, floats));
+                out->partial_tiles = tiles;
+            }
+        }
+        const int64_t slots = out->plan.n_huge_blocks > out->plan_t.n_huge_blocks ? out->plan.n_huge_blocks : out->plan_t.n_huge_blocks;
+        out->scratch_ld = round_up(max_batch, 64);
+        if (slots > 0) HIP_TRY(reserve(&l->scratch, &l->scratch_floats, static_cast<size_t>(slots) * out->scratch_ld));
+        out->full = rows <= kFullMaxRows && static_cast<int64_t>(nnz) == static_cast<int64_t>(rows) * cols;
+        out->full_scratch_ld = round_up(max_batch, 64);
+        if (out->full && !l->full_scratch) {
+            const int64_t slices = (cols + kFullSlice - 1) / kFullSlice;
+            HIP_TRY(hipMalloc(&l->full_scratch, static_cast<size_t>(slices) * rows * out->full_scratch_ld * 4));
         }
     }
-    if (e == hipSuccess) {
-        const int64_t slots = l->plan.n_huge_blocks > l->plan_t.n_huge_blocks ? l->plan.n_huge_blocks : l->plan_t.n_huge_blocks;
-        l->scratch_ld = round_up(max_batch, 64);
-        if (slots > 0) e = hipMalloc(&l->scratch, static_cast<size_t>(slots) * l->scratch_ld * 4);
-    }
-    if (e == hipSuccess && rows <= kFullMaxRows && static_cast<int64_t>(nnz) == static_cast<int64_t>(rows) * cols) {
-        l->full_scratch_ld = round_up(max_batch, 64);
-        const int64_t slices = (cols + kFullSlice - 1) / kFullSlice;
-        e = hipMalloc(&l->full_scratch, static_cast<size_t>(slices) * rows * l->full_scratch_ld * 4);
-    }
-    if (e == hipSuccess) e = launch_gather(l->values_t, values, l->perm, nnz, s);
-    if (e == hipSuccess && l->dense_on) e = build_dense_copies(l, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);  // host staging vectors die at return
-    if (e != hipSuccess) {
-        free_layer_buffers(l);
-        return hip_fail(e, "building the layer's structures");
-    }
+    HIP_TRY(hipStreamSynchronize(s));  // the host staging vectors die at return
     return NERVA_OK;
+}
+
+// The spare set, just built, becomes the layer's pattern; the set it replaces becomes the spare one.
+static void adopt_pattern(nerva_layer *l, int32_t nnz, const int32_t *indptr, const int32_t *indices, float *values, const BuiltPattern &bp)
+{
+    std::swap(l->cur, l->spare);
+    const size_t n64 = static_cast<size_t>(round_up(nnz > 0 ? nnz : 1, 64));
+    l->nnz = nnz; l->indptr = indptr; l->indices = indices; l->values = values;
+    l->indptr_t = l->cur.indptr_t;
+    l->indices_t = l->cur.mirror_mem;
+    l->perm = l->cur.mirror_mem + n64;
+    l->pos_t = l->cur.mirror_mem + 2 * n64;
+    l->values_t = reinterpret_cast<float *>(l->cur.mirror_mem + 3 * n64);
+    l->plan = bp.plan; l->plan_t = bp.plan_t;
+    l->partial_stride = bp.partial_stride; l->partial_db_at = bp.partial_db_at; l->partial_tiles = bp.partial_tiles;
+    l->scratch_ld = bp.scratch_ld;
+    l->full_scratch_ld = bp.full_scratch_ld;
+    l->full = bp.full;
+    l->mirror_stale = false;
 }
 
 int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t nnz, const int32_t *indptr,
@@ -812,13 +925,15 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
     if (max_batch <= 0 || max_batch >= (1 << 30)) return fail(NERVA_ERR_ARGUMENT, "max_batch must be positive (got %d)", max_batch);
     nerva_layer *l = new (std::nothrow) nerva_layer;
     if (!l) return fail(NERVA_ERR_ARGUMENT, "out of host memory");
-    l->rows = rows; l->cols = cols; l->nnz = nnz; l->activation = activation; l->max_batch = max_batch;
-    l->indptr = indptr; l->indices = indices; l->values = values; l->bias = bias;
-    const int rc = build_structures(l, as_stream(stream));
+    l->rows = rows; l->cols = cols; l->activation = activation; l->max_batch = max_batch; l->bias = bias;
+    BuiltPattern bp;
+    const int rc = build_structures(l, nnz, indptr, indices, values, &bp, as_stream(stream));
     if (rc != NERVA_OK) {
+        free_layer_buffers(l);
         delete l;
         return rc;
     }
+    adopt_pattern(l, nnz, indptr, indices, values, bp);
     *out = l;
     return NERVA_OK;
 }
@@ -830,14 +945,18 @@ int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
     if (nnz < 0 || !indptr || (nnz > 0 && (!indices || !values))) return fail(NERVA_ERR_ARGUMENT, "null pattern or values pointer");
     hipStream_t s = as_stream(stream);
     HIP_TRY(hipStreamSynchronize(s));  // launches already queued on this stream still use the old structures
-    nerva_layer fresh;
-    fresh.rows = layer->rows; fresh.cols = layer->cols; fresh.nnz = nnz; fresh.activation = layer->activation;
-    fresh.max_batch = layer->max_batch; fresh.bias = layer->bias; fresh.dense_on = layer->dense_on;
-    fresh.indptr = indptr; fresh.indices = indices; fresh.values = values;
-    const int rc = build_structures(&fresh, s);
-    if (rc != NERVA_OK) return rc;  // the layer keeps its old pattern
-    free_layer_buffers(layer);
-    *layer = fresh;
+    BuiltPattern bp;
+    const int rc = build_structures(layer, nnz, indptr, indices, values, &bp, s);
+    if (rc != NERVA_OK) return rc;  // the layer keeps its old pattern: only the spare set and scratch buffers were written
+    adopt_pattern(layer, nnz, indptr, indices, values, bp);
+    if (layer->dense_on) {
+        // the dense copies hold the old pattern's entries: cleared and filled again
+        const size_t bytes = static_cast<size_t>(layer->rows) * layer->dense_ld * 4, bytes_t = static_cast<size_t>(layer->cols) * layer->dense_t_ld * 4;
+        HIP_TRY(hipMemsetAsync(layer->dense, 0, bytes, s));
+        HIP_TRY(hipMemsetAsync(layer->dense_t, 0, bytes_t, s));
+        HIP_TRY(refresh_dense_copies(layer, s));
+        HIP_TRY(hipStreamSynchronize(s));
+    }
     return NERVA_OK;
 }
 
@@ -909,7 +1028,7 @@ int sparse_linear_forward(const nerva_layer *layer, const float *X, int32_t ldx,
     a.indptr = layer->indptr; a.indices = layer->indices; a.values = layer->values; a.bias = layer->bias;
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy;
     a.rows = layer->rows; a.x_rows = layer->cols; a.batch = batch; a.relu = layer->activation == NERVA_ACT_RELU;
-    a.full_scratch = layer->full_scratch; a.full_scratch_ld = layer->full_scratch_ld;
+    a.full_scratch = layer->full ? layer->full_scratch : nullptr; a.full_scratch_ld = layer->full_scratch_ld;
     HIP_TRY(launch_spmm(a, as_stream(stream)));
     return NERVA_OK;
 }
@@ -1145,7 +1264,7 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
         a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
         a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
         a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
-        a.full_scratch = ly->full_scratch; a.full_scratch_ld = ly->full_scratch_ld;
+        a.full_scratch = ly->full ? ly->full_scratch : nullptr; a.full_scratch_ld = ly->full_scratch_ld;
         if (use_dense(ly, batch)) {
             Timed tm(mlp->prof, s, "dense_forward", static_cast<int>(l));
             HIP_TRY(dense_forward(ly, in, ldin, A, L.ld, batch, s));
