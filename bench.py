@@ -59,6 +59,9 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
     if kind == "sddmm_update":        # indices, dZ and X in; values and velocity read and written; biases
         b = 4 * nnz + 4 * (m + 1) + 4 * n * (m + k) + 16 * nnz + 16 * m
         return b + (8 * nnz if has_mirror_scatter else 0)
+    if kind == "backward_fused":      # transposed product and SDDMM + update of one layer on one gather stream: mirror pattern,
+        # values and position map, dZ in once, the layer's input in once (mask and second operand), dX out, the update
+        return 12 * nnz + 4 * (k + 1) + 4 * n * m + 4 * n * k + 4 * n * k + 16 * nnz + 4 * nnz + 16 * m
     if kind == "sddmm":
         return 4 * nnz + 4 * (m + 1) + 4 * n * (m + k) + 4 * nnz + 4 * m
     if kind == "momentum_values":

@@ -870,6 +870,12 @@ static int build_structures(nerva_layer *l, int32_t nnz, const int32_t *indptr, 
         const int w = tile_columns(cols, max_batch, nnz, rows, out->plan.hot_share, false, true);
         int32_t tiles = w > 0 ? (max_batch + w - 1) / w : 0;
         if (out->plan.staged_rows && (max_batch + kStageCols - 1) / kStageCols > tiles) tiles = (max_batch + kStageCols - 1) / kStageCols;
+        // ... and for the backward pass on one gather stream (products in mirror order, one slice per tile of the
+        // transposed product), which runs where every row of the mirror is short
+        if (out->plan_t.n_short == cols && out->plan_t.n_long_blocks == 0) {
+            const int wt = tile_columns(rows, max_batch, nnz, cols, out->plan_t.hot_share, false);
+            if (wt > 0 && (max_batch + wt - 1) / wt > tiles) tiles = (max_batch + wt - 1) / wt;
+        }
         out->partial_tiles = 0;
         if (tiles > 0) {
             out->partial_db_at = round_up(nnz, 64);
@@ -1389,7 +1395,7 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
         if (fused) {
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
-            if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; }  // the first layer's mirror is never read
+            if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; g.perm = ly->perm; }  // the first layer's mirror is never read
             if (ly->dense_on) { g.dense = ly->dense; g.dense_t = ly->dense_t; g.dense_ld = ly->dense_ld; g.dense_t_ld = ly->dense_t_ld; }
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
         } else {
@@ -1407,41 +1413,59 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
         auto dense_T = [&](int l) {
             return dense_transposed(mlp->layers[l], dZ(l), L.ld, dZ(l - 1), L.ld, A(l - 1), L.ld, batch, s);
         };
-        if (n > 1 && !head) {
-            if (use_dense(mlp->layers[n - 1], batch)) {
-                Timed tm(mlp->prof, s, "dense_transposed", n - 1);
-                HIP_TRY(dense_T(n - 1));
-            } else {
-                Timed tm(mlp->prof, s, "spmm_transposed", n - 1);
-                HIP_TRY(launch_spmm(make_T(n - 1), s));
+        // `pending`: a layer whose transposed product has run and whose S has not.  Where a layer's T and S
+        // can share their gathers (backward_fused_ok) they run as one launch and nothing stays pending.
+        int pending = -1;
+        auto run_S_alone = [&](int l) -> int {
+            Timed tm(mlp->prof, s, "sddmm_update", l);
+            HIP_TRY(launch_sddmm(make_S(l), s));
+            return NERVA_OK;
+        };
+        if (head) pending = n - 1;  // the head launch has run T_{n-1}
+        for (int l = head ? n - 2 : n - 1; l >= 1; --l) {
+            // dZ_l is ready: T_l (which hands dZ_{l-1} down) and S_l
+            const SpmmArgs t = make_T(l);
+            if (use_dense(mlp->layers[l], batch)) {
+                if (pending >= 0 && (rc = run_S_alone(pending)) != NERVA_OK) return rc;
+                { Timed tm(mlp->prof, s, "dense_transposed", l); HIP_TRY(dense_T(l)); }
+                pending = l;
+                continue;
             }
-        }
-        for (int l = n - 1; l >= 2; --l) {
-            const SpmmArgs t = make_T(l - 1);
-            const SddmmArgs g = make_S(l);
-            if (use_dense(mlp->layers[l - 1], batch)) {
-                { Timed tm(mlp->prof, s, "dense_transposed", l - 1); HIP_TRY(dense_T(l - 1)); }
-                { Timed tm(mlp->prof, s, "sddmm_update", l); HIP_TRY(launch_sddmm(g, s)); }
-            } else if (can_pair(t, g)) {
-                Timed tm(mlp->prof, s, "spmm_transposed+sddmm_update", l - 1);
-                HIP_TRY(launch_pair(t, g, s));
-            } else {
-                { Timed tm(mlp->prof, s, "spmm_transposed", l - 1); HIP_TRY(launch_spmm(t, s)); }
-                { Timed tm(mlp->prof, s, "sddmm_update", l); HIP_TRY(launch_sddmm(g, s)); }
+            const SddmmArgs g_same = make_S(l);
+            if (backward_fused_ok(t, g_same)) {
+                if (pending >= 0 && (rc = run_S_alone(pending)) != NERVA_OK) return rc;
+                pending = -1;
+                Timed tm(mlp->prof, s, "backward_fused", l);
+                HIP_TRY(launch_backward_fused(t, g_same, s));
+                continue;
             }
+            if (pending >= 0) {
+                const SddmmArgs g = make_S(pending);
+                if (can_pair(t, g)) {
+                    Timed tm(mlp->prof, s, "spmm_transposed+sddmm_update", l);
+                    HIP_TRY(launch_pair(t, g, s));
+                } else {
+                    { Timed tm(mlp->prof, s, "spmm_transposed", l); HIP_TRY(launch_spmm(t, s)); }
+                    if ((rc = run_S_alone(pending)) != NERVA_OK) return rc;
+                }
+            } else {
+                Timed tm(mlp->prof, s, "spmm_transposed", l);
+                HIP_TRY(launch_spmm(t, s));
+            }
+            pending = l;
         }
-        if (n > 1) {
-            const SddmmArgs g1 = make_S(1), g0 = make_S(0);
-            if (can_pair(g0, g1)) {
+        // the first layer has no transposed product: its S, with the one still pending if any
+        if (pending >= 0) {
+            const SddmmArgs gp = make_S(pending), g0 = make_S(0);
+            if (pending == 1 && can_pair(g0, gp)) {
                 Timed tm(mlp->prof, s, "sddmm_update+sddmm_update", 0);
-                HIP_TRY(launch_pair(g0, g1, s));  // the larger layer's work-groups start first
+                HIP_TRY(launch_pair(g0, gp, s));  // the larger layer's work-groups start first
             } else {
-                { Timed tm(mlp->prof, s, "sddmm_update", 1); HIP_TRY(launch_sddmm(g1, s)); }
-                { Timed tm(mlp->prof, s, "sddmm_update", 0); HIP_TRY(launch_sddmm(g0, s)); }
+                if ((rc = run_S_alone(pending)) != NERVA_OK) return rc;
+                if (pending != 0 && (rc = run_S_alone(0)) != NERVA_OK) return rc;
             }
-        } else {
-            Timed tm(mlp->prof, s, "sddmm_update", 0);
-            HIP_TRY(launch_sddmm(make_S(0), s));
+        } else if ((rc = run_S_alone(0)) != NERVA_OK) {
+            return rc;
         }
     } else {
         for (int l = n - 1; l >= 0; --l) {

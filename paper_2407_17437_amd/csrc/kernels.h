@@ -136,6 +136,7 @@ struct SddmmArgs {
     float *velocity;         // [nnz]
     float *values_t;         // mirror values or nullptr
     const int32_t *pos_t;    // CSR position -> mirror position (needed iff values_t)
+    const int32_t *perm;     // mirror position -> CSR position (only the fused backward pass needs it)
     float *bias;             // [rows] or nullptr
     float *bias_velocity;    // [rows] or nullptr
     // by-product, unrelated to the layer: *loss_out = mean(loss_cols[0..loss_n)), summed in one fixed
@@ -162,6 +163,32 @@ struct SddmmArgs {
 // SDDMM partial buffer when a layer is created.
 int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float hot_share, bool masked, bool for_sddmm = false);
 hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s);
+
+// Transposed product and SDDMM of one layer on one gather stream (backward_fused_kernel).
+struct BackwardArgs {
+    RowBlocks blocks;            // the mirror's partition (its table of short rows)
+    const int32_t *indices;      // mirror: row of W of each entry
+    const float *values;         // mirror values
+    const float *dZ;             // (rows of W, lddz): gathered
+    int64_t lddz;
+    const float *X;              // (cols of W, ldx): the layer's input; second operand of the products and mask of dX
+    int64_t ldx;
+    float *dX;                   // (cols of W, lddx)
+    int64_t lddx;
+    int32_t mask;                // multiply dX by [X > 0]
+    int32_t rows, x_rows, batch, nnz;   // rows = mirror rows = columns of W; x_rows = rows of W
+    float *partial;              // [tile][partial_stride]: products in mirror order
+    int64_t partial_stride;
+    const int32_t *perm;         // mirror position -> CSR position
+    // what the second pass does with the sums: store them (g, db: CSR order) and / or the momentum step
+    float *g, *db;
+    int32_t fused, nesterov;
+    float lr, momentum;
+    float *w, *velocity, *w_t;   // values[], velocity[] (CSR order), mirror values
+    float *bias, *bias_velocity;
+};
+bool backward_fused_ok(const SpmmArgs &t, const SddmmArgs &g);
+hipError_t launch_backward_fused(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s);
 
 // Two independent launches in one grid (both on the 16-byte path, batch <= 1024, one column tile).
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b);

@@ -63,7 +63,7 @@ __device__ __forceinline__ float row16_sum(float x)
 template <int G>
 __device__ __forceinline__ float group_sum(float x)
 {
-    static_assert(G == 8 || G == 16 || G == 64, "group sizes with a DPP reduction");
+    static_assert(G == 8 || G == 16 || G == 32 || G == 64, "group sizes with a reduction");
     if constexpr (G == 8) {
         x += dpp<0xB1>(x);   // quad_perm [1,0,3,2]
         x += dpp<0x4E>(x);   // quad_perm [2,3,0,1]
@@ -71,6 +71,7 @@ __device__ __forceinline__ float group_sum(float x)
         return x;
     }
     x = row16_sum(x);
+    if constexpr (G == 32) x += __shfl_xor(x, 16, kWave);  // the other row of the pair (through the LDS crossbar)
     if constexpr (G == 64) {
         x += dpp<0x142, 0xA>(x);  // row_bcast15 into rows 1 and 3
         x += dpp<0x143, 0xC>(x);  // row_bcast31 into rows 2 and 3
@@ -1553,6 +1554,181 @@ __global__ __launch_bounds__(kEwBlock) void sddmm_finish_kernel(const SddmmArgs 
     }
 }
 
+// ---- backward pass of a hidden layer in one gather stream --------------------------------------
+// The transposed product dX = W^T dZ and the SDDMM g = (dZ X^T) on W's pattern gather the same
+// rows: taken in the mirror's order (row j of W^T, its entries i ascending), stored entry (i, j)
+// needs dZ[i, :] for both.  One kernel walks the mirror like spmm_body_packed (one mirror row per
+// group of GS lanes, inside column tiles), gathers dZ[i, tile] once and uses it twice:
+//     acc[j, tile]        += values_t[q] * dZ[i, tile]
+//     partial[tile][q]     = <dZ[i, tile], X[j, tile]>        (X[j, tile] is held by the lane group)
+// and stores dX[j, tile] = acc * [X[j, tile] > 0] (the ReLU derivative of the layer below, whose
+// output X is).  The per-tile partial products, in mirror order, are added in tile order by
+// backward_finish_kernel, which applies the momentum step through perm (mirror -> CSR position)
+// and also forms the bias gradient (row sums of dZ).  Every mirror row must be short (packed).
+constexpr int kBwdWaves = 8;  // waves per work-group (no sums across waves: smaller groups schedule finer)
+
+template <int U, int GS>
+__device__ __forceinline__ void bwd_pass(gmem_ptr Zg, int src, int my_ro, float my_w, uint32_t off, const float4 &ax, int it0, int lig,
+                                         float (&acc)[4], float &res)
+{
+    uint32_t ro[U];
+    float w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        ro[u] = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(src + u * 4, my_ro));
+        w[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src + u * 4, __builtin_bit_cast(int, my_w)));
+    }
+    float4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = gload<float4>(Zg, ro[u] + off);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        acc[0] = fmaf(w[u], x[u].x, acc[0]);
+        acc[1] = fmaf(w[u], x[u].y, acc[1]);
+        acc[2] = fmaf(w[u], x[u].z, acc[2]);
+        acc[3] = fmaf(w[u], x[u].w, acc[3]);
+        float part = fmaf(ax.w, x[u].w, fmaf(ax.z, x[u].z, fmaf(ax.y, x[u].y, ax.x * x[u].x)));
+        part = group_sum<GS>(part);
+        res = lig == it0 + u ? part : res;
+    }
+}
+
+template <int GS>
+__global__ __launch_bounds__(kBwdWaves * kWave) void backward_fused_kernel(const BackwardArgs a, const int n_tiles, const int spread,
+                                                                          const int n_pack_blocks)
+{
+    int tile, rb;
+    if (spread) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        tile = (k / n_pack_blocks) * 8 + xcd;
+        rb = k % n_pack_blocks;
+    } else {
+        tile = blockIdx.x / n_pack_blocks;
+        rb = blockIdx.x % n_pack_blocks;
+    }
+    if (tile >= n_tiles) return;
+    constexpr int NE = kWave / GS;
+    const int col0 = tile * GS * 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = wave_in_block();
+    const int grp = lane / GS;
+    const int lig = lane % GS;
+    const int col = col0 + lig * 4;
+    const bool on = col < a.batch;  // (batch is a multiple of 4: a lane's four columns are all in or all out)
+    const uint32_t off = static_cast<uint32_t>(on ? col : col0) * 4u;
+    const uint32_t ldzb = static_cast<uint32_t>(a.lddz) * 4u;
+    const gmem_ptr Zg = as_gmem(a.dZ);
+    const int n_sets = (a.blocks.n_short + NE - 1) / NE;
+    const int src0 = grp * GS * 4;
+    const int n_waves = n_pack_blocks * kBwdWaves;
+    const int first_set = rb * kBwdWaves + wv;
+    if (first_set >= n_sets) return;  // wave-uniform
+    float *gp = a.partial + static_cast<int64_t>(tile) * a.partial_stride;
+
+    auto fetch = [&](int s0, int len, int base, int &j, float &w) {  // as in spmm_body_packed
+        const int e = base + lig;
+        const bool ok = e < len;
+        const int p = len > 0 ? s0 + (ok ? e : 0) : 0;
+        j = a.indices[p];
+        w = a.values[p];
+        w = ok ? w : 0.f;
+    };
+
+    for (int set = first_set; set < n_sets; set += n_waves) {
+        const int4 d = a.blocks.short_rows[set * NE + grp];  // the table is padded to whole sets
+        const int row = d.x, s0 = d.y, len = d.z;
+        const int maxlen = __builtin_amdgcn_readfirstlane(len);  // group 0 holds the set's longest row
+        // the group's row of X: the second operand of its entries' products, and the mask of its result;
+        // lanes beyond the batch hold zeros, so that the columns they re-read add nothing to a product
+        float4 ax = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row >= 0 && on) ax = ld4(a.X + static_cast<int64_t>(row) * a.ldx + col);
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        int cur_j;
+        float cur_w;
+        fetch(s0, len, 0, cur_j, cur_w);
+        for (int base = 0; base < maxlen; base += GS) {
+            int next_j = 0;
+            float next_w = 0.f;
+            if (base + GS < maxlen) fetch(s0, len, base + GS, next_j, next_w);  // wave-uniform: one chunk ahead
+            const int my_ro = static_cast<int>(static_cast<uint32_t>(cur_j) * ldzb);
+            const int steps = min(GS, maxlen - base);
+            float res = 0.f;
+            int src = src0;
+            int u0 = 0;
+            for (; u0 + 8 <= steps; u0 += 8, src += 32) bwd_pass<8, GS>(Zg, src, my_ro, cur_w, off, ax, u0, lig, acc, res);
+            if (u0 + 4 <= steps) {
+                bwd_pass<4, GS>(Zg, src, my_ro, cur_w, off, ax, u0, lig, acc, res);
+                u0 += 4; src += 16;
+            }
+            if (u0 + 2 <= steps) {
+                bwd_pass<2, GS>(Zg, src, my_ro, cur_w, off, ax, u0, lig, acc, res);
+                u0 += 2; src += 8;
+            }
+            if (u0 < steps) bwd_pass<1, GS>(Zg, src, my_ro, cur_w, off, ax, u0, lig, acc, res);
+            if (row >= 0 && base + lig < len) gp[s0 + base + lig] = res;  // GS consecutive entries of the row: one coalesced store
+            cur_j = next_j;
+            cur_w = next_w;
+        }
+        if (row < 0 || !on) continue;
+        float4 y = len > 0 ? make_float4(acc[0], acc[1], acc[2], acc[3]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.mask) y = keep_where_positive(y, ax);
+        st4(a.dX + static_cast<int64_t>(row) * a.lddx + col, y);
+    }
+}
+
+// Second pass: work-groups [0, n_entry_blocks) add the tiles' partial products of mirror entry q in tile
+// order and apply the momentum step to the entry's CSR position perm[q] (or store the gradient there);
+// the remaining work-groups, a wave per row of W, sum the rows of dZ for the bias gradient.
+__global__ __launch_bounds__(kEwBlock) void backward_finish_kernel(const BackwardArgs a, const int n_tiles, const int n_entry_blocks)
+{
+    if (static_cast<int>(blockIdx.x) < n_entry_blocks) {
+        const int64_t stride = static_cast<int64_t>(kEwBlock) * n_entry_blocks;
+        for (int64_t q = static_cast<int64_t>(blockIdx.x) * kEwBlock + threadIdx.x; q < a.nnz; q += stride) {
+            float g = 0.f;
+            int t = 0;
+            for (; t + 8 <= n_tiles; t += 8) {  // eight loads in flight, added in tile order
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = a.partial[static_cast<int64_t>(t + u) * a.partial_stride + q];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) g += v[u];
+            }
+            for (; t < n_tiles; ++t) g += a.partial[static_cast<int64_t>(t) * a.partial_stride + q];
+            const int p = a.perm[q];
+            if (a.g) a.g[p] = g;
+            if (a.fused) {
+                float w = a.w[p], v = a.velocity[p];
+                momentum_step(w, v, g, a.lr, a.momentum, a.nesterov);
+                a.w[p] = w;
+                a.velocity[p] = v;
+                a.w_t[q] = w;
+            }
+        }
+        return;
+    }
+    if (!(a.db || (a.fused && a.bias))) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t n_waves = static_cast<int64_t>(gridDim.x - n_entry_blocks) * (kEwBlock / kWave);
+    for (int64_t i = static_cast<int64_t>(blockIdx.x - n_entry_blocks) * (kEwBlock / kWave) + (threadIdx.x >> 6); i < a.x_rows; i += n_waves) {
+        const float *zr = a.dZ + i * a.lddz;
+        float s = 0.f;
+        for (int c = lane * 4; c < a.batch; c += kWave * 4) {
+            const float4 z = ld4(zr + c);
+            s += (z.x + z.y) + (z.z + z.w);
+        }
+        s = group_sum<kWave>(s);
+        if (lane == 0) {
+            if (a.db) a.db[i] = s;
+            if (a.fused && a.bias) {
+                float w = a.bias[i], v = a.bias_velocity[i];
+                momentum_step(w, v, s, a.lr, a.momentum, a.nesterov);
+                a.bias[i] = w;
+                a.bias_velocity[i] = v;
+            }
+        }
+    }
+}
+
 // Two independent launches of a training step in one grid: work-groups [0, na) run the first,
 // the rest the second.  Saves a launch (and its drain) on the step's critical path.
 template <int GS_S, int NV_S, int G, int NV_D, bool EXACT4>
@@ -2302,6 +2478,51 @@ hipError_t launch_pair(const SddmmArgs &a, const SddmmArgs &b, hipStream_t s)
     if (a.batch <= 256) return sddmm_pair_go<16, 4>(a, b, s);
     if (a.batch <= 512) return sddmm_pair_go<64, 2>(a, b, s);
     return sddmm_pair_go<64, 4>(a, b, s);
+}
+
+// The transposed product t and the SDDMM g of one layer can share their gathers when t would run the
+// packed kernel inside column tiles on a mirror all of whose rows are short, its result mask is the
+// SDDMM's second operand (the output of the layer below), and the layer's partial buffer has a slice
+// per tile for the products in mirror order.
+bool backward_fused_ok(const SpmmArgs &t, const SddmmArgs &g)
+{
+    if (t.batch != g.batch || t.batch % 4 != 0 || t.XM || !t.YM || t.YM != g.X || t.ldym != g.ldx || t.X != g.dZ || t.ldx != g.lddz) return false;
+    if (t.rows != g.x_rows || t.x_rows != g.rows || t.nnz != g.nnz || t.nnz <= 0) return false;
+    if (g.ZM || g.skip_products || g.dense || g.loss_cols || !g.partial || !g.perm) return false;
+    if (!spmm_vec_ok(t) || !spmm_offsets_ok(t) || !sddmm_vec_ok(g) || spmm_staged_ok(t)) return false;
+    if (t.blocks.n_short != t.rows || t.blocks.n_long_blocks != 0) return false;  // every mirror row packed
+    const int tg = spmm_tile_group(t);
+    if (tg != 16 && tg != 32) return false;  // (32-column tiles are only chosen for rows too long to be packed)
+    const int n_tiles = (t.batch + tg * 4 - 1) / (tg * 4);
+    if (n_tiles > g.partial_tiles || g.partial_stride < t.nnz) return false;
+    const int64_t sets = (static_cast<int64_t>(t.blocks.n_short) + kWave / tg - 1) / (kWave / tg);
+    return ((n_tiles + 7) / 8) * 8 * ((sets + kBwdWaves - 1) / kBwdWaves) <= kMaxGridIds;
+}
+
+hipError_t launch_backward_fused(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s)
+{
+    BackwardArgs a{};
+    a.blocks = t.blocks; a.indices = t.indices; a.values = t.values;
+    a.dZ = t.X; a.lddz = t.ldx; a.X = g.X; a.ldx = g.ldx; a.dX = t.Y; a.lddx = t.ldy; a.mask = 1;
+    a.rows = t.rows; a.x_rows = t.x_rows; a.batch = t.batch; a.nnz = t.nnz;
+    a.partial = g.partial; a.partial_stride = g.partial_stride; a.perm = g.perm;
+    a.g = g.g; a.db = g.db; a.fused = g.fused; a.nesterov = g.nesterov; a.lr = g.lr; a.momentum = g.momentum;
+    a.w = g.values; a.velocity = g.velocity; a.w_t = g.values_t; a.bias = g.bias; a.bias_velocity = g.bias_velocity;
+    const int tg = spmm_tile_group(t);
+    const int n_tiles = (t.batch + tg * 4 - 1) / (tg * 4);
+    const int spread = n_tiles >= 8;
+    const int64_t sets = (static_cast<int64_t>(t.blocks.n_short) + kWave / tg - 1) / (kWave / tg);
+    const int n_pack_blocks = static_cast<int>((sets + kBwdWaves - 1) / kBwdWaves);
+    const int64_t ids = static_cast<int64_t>(spread ? (n_tiles + 7) / 8 * 8 : n_tiles) * n_pack_blocks;
+    if (tg == 32)
+        hipLaunchKernelGGL(backward_fused_kernel<32>, dim3(static_cast<unsigned>(ids)), dim3(kBwdWaves * kWave), 0, s, a, n_tiles, spread, n_pack_blocks);
+    else
+        hipLaunchKernelGGL(backward_fused_kernel<16>, dim3(static_cast<unsigned>(ids)), dim3(kBwdWaves * kWave), 0, s, a, n_tiles, spread, n_pack_blocks);
+    const int n_entry_blocks = elementwise_blocks(t.nnz);
+    const int64_t row_blocks = (static_cast<int64_t>(a.x_rows) + kEwBlock / kWave - 1) / (kEwBlock / kWave);
+    const int n_row_blocks = (a.db || (a.fused && a.bias)) ? static_cast<int>(row_blocks < 2048 ? row_blocks : 2048) : 0;
+    hipLaunchKernelGGL(backward_finish_kernel, dim3(n_entry_blocks + n_row_blocks), dim3(kEwBlock), 0, s, a, n_tiles, n_entry_blocks);
+    return hipGetLastError();
 }
 
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)

@@ -42,8 +42,8 @@ def run_cases(n=16384, densities=(0.001, 0.01, 0.1), batches=(128, 1024), reps=2
     (the latter two are measurement aids).  `ld_pad`: extra floats in the leading dimension of the dense matrices."""
     import numpy as np
     import torch
-    from . import binding as nb
-    from . import workloads as wl
+    from paper_2407_17437_amd import binding as nb
+    from paper_2407_17437_amd import workloads as wl
 
     assert torch.cuda.is_available()
     mode = {"balanced": nb.NERVA_PARTITION_BALANCED, "row-split": nb.NERVA_PARTITION_ROW_SPLIT,

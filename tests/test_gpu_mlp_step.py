@@ -409,3 +409,30 @@ def test_layer_trained_as_first_layer_then_chained_further_up(nb, torch_mod, ora
     assert np.array_equal(raw_f32(nb, torch, vt_addr, shared.nnz), shared.values.cpu().numpy()[perm])
     nb.mlp_destroy(handle)
     L0.close(); L2.close(); M1.close()
+
+
+@pytest.mark.parametrize("sizes,sparsity,batch,unfused", [
+    ((100, 2100, 5200, 10), 0.985, 256, False),     # 64-column tiles (16 lanes per mirror row)
+    ((100, 2100, 5200, 10), 0.985, 200, True),      # ragged last tile; gradients stored, separate momentum kernels
+    ((100, 2304, 2304, 2304, 10), 0.98, 512, False),  # 128-column tiles (32 lanes per mirror row), two hidden layers fused in a row
+])
+def test_stage_parity_backward_on_one_gather_stream(nb, torch_mod, oracle, sizes, sparsity, batch, unfused):
+    """Hidden layers whose mirror has only short rows and whose backward operand does not fit an L2: the transposed
+    product and the SDDMM + update of the layer run as one launch that gathers every row of dZ once for both
+    (Section 4: A = S^T B and S = A B^T); every stage of two steps against the oracle."""
+    torch = torch_mod
+    mlp = wl.make_mlp(sizes, sparsity=sparsity, bias_std=0.1, pattern_seed=130, value_seed=230)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 2, seed=330)
+    M = nb.MLP(mlp, batch, nb.NERVA_MLP_UNFUSED if unfused else 0)
+    nb.mlp_profile_enable(M.handle, 1)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        if t == 0:
+            names = [n for n, _ in nb.mlp_profile_read(M.handle)[1]]
+            nb.mlp_profile_enable(M.handle, 0)
+            if not unfused:
+                assert sum(n.startswith("backward_fused") for n in names) == len(sizes) - 3, names
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused)
+    M.close()
