@@ -70,6 +70,8 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
         return 20 * m
     if kind == "mirror_refresh":
         return 12 * nnz
+    if kind == "dense_sddmm_update":  # dZ and X in, the dense gradient written and read on the pattern, the update, the dense copy
+        return 4 * n * (m + k) + 4 * m * k + 4 * nnz + 4 * nnz + 16 * nnz + 4 * nnz + 16 * m + (8 * nnz if has_mirror_scatter else 0)
     if kind == "dense_forward":       # the dense copy of the weights, X in, Y out, bias
         return 4 * m * k + 4 * n * (k + m) + 4 * m
     if kind == "dense_transposed":    # the dense copy, dZ in, dX out, ReLU mask in
@@ -129,8 +131,10 @@ def measure_mlp(env, name: str, K: int, W: int, profile_steps: int, args, copy_g
     Td = torch.as_tensor(Ts).cuda()
     if args.prefer_staged:
         nb.nerva_set_partition_mode(nb.NERVA_PARTITION_PREFER_STAGED)
+    if args.dense_from_density is not None:
+        nb.nerva_set_dense_threshold(args.dense_from_density)
     M = nb.MLP(mlp, batch, (nb.NERVA_MLP_UNFUSED if args.unfused else 0) |
-               (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0), dense_from_density=args.dense_from_density)
+               (nb.NERVA_MLP_SEPARATE_HEAD if args.separate_head else 0))
     nb.nerva_set_partition_mode(nb.NERVA_PARTITION_BALANCED)
     x_ptr, x_stride = Xd.data_ptr(), sizes[0] * ld * 4
     t_ptr, t_stride = Td.data_ptr(), batch * 4
@@ -314,7 +318,7 @@ def main() -> int:
     ap.add_argument("--graph", type=int, default=0, help="capture this many steps per HIP graph (0: plain launches)")
     ap.add_argument("--unfused", action="store_true")
     ap.add_argument("--dense-from-density", type=float, default=None,
-                    help="layers of at least this density take the dense MFMA route for their two products (default: the library's own choice)")
+                    help="measurement aid: density from which layers take the dense MFMA route (default: the library's own threshold, 0.4; 2 = never)")
     ap.add_argument("--separate-head", action="store_true",
                     help="keep the output layer's forward product, loss and transposed product as three launches")
     ap.add_argument("--prefer-staged", action="store_true",

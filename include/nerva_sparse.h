@@ -194,18 +194,21 @@ void sparse_linear_destroy(nerva_layer *layer);
 int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
                          const int32_t *indices, float *values, void *stream);
 
-/* Density-adaptive layer ("Discussion and Conclusion": dense computation where a layer is not
- * sparse enough for the sparse kernels to win; Section 5.5 / Table 2 show masks winning at 50 %
- * sparsity).  After this call the layer's products Y = S X and Y = S^T X on batches of at
- * least 16 columns run as dense fp32 MFMA products on two zero-filled dense copies of the weights
- * (W and W^T, rows x cols floats each, owned by the layer); S = A B^T on the pattern, the
- * momentum update and values[] stay sparse and remain the layer's state, and every update the
- * library applies is written to the copies as well.  Results agree with the sparse route to
- * rounding (other summation order); entries off the pattern contribute 0 * x, so an operand that
- * holds Inf/NaN spreads differently.  Which layers to switch is the caller's choice (density at
- * least 1/2 is the paper's regime; on the 3072-1024-512-10 network at batch 100 the sparse route
- * was still the faster one at 50 % density).  Survives
- * sparse_linear_rebind.  Errors: NERVA_ERR_SHAPE (rows x cols beyond 2^31), NERVA_ERR_HIP. */
+/* Density-adaptive layer ("Discussion and Conclusion" and Appendix C.3: dense computation where a layer is
+ * not sparse enough for the sparse kernels to win; Section 5.3 shows masks winning at 50 % sparsity and the
+ * sparse kernels from about 80 % on).  A layer on the dense route keeps one zero-filled dense copy of its
+ * weights (rows x cols floats, columns padded to a multiple of 64; owned by the layer) and a dense gradient of
+ * the same shape.  On batches of at least 16 columns its products Y = S X and Y = S^T X run as fp32 MFMA
+ * products on that copy, and inside mlp_train_step S = A B^T is formed as a dense product of which only the
+ * entries on the pattern are used.  values[] stays the layer's state, in CSR, and the momentum update touches
+ * the stored entries only: the pattern is as immutable as on the sparse route, and every update the library
+ * applies is written to the copy as well.  Results agree with the sparse route to rounding (other summation
+ * order); entries off the pattern contribute 0 * x, so an operand that holds Inf/NaN spreads differently.
+ * sparse_linear_create and sparse_linear_rebind take the route by themselves for a pattern of at least 40 %
+ * density with at least 64 rows and 64 columns (the cut-over measured on the 3072-1024-512-10 network at batch
+ * 100: the dense route's step takes 81 - 91 us whatever the density, the sparse route's 106 us at 50 % and
+ * 57 us at 80 % sparsity); this call switches any layer over by hand.  A route once taken is kept across sparse_linear_rebind.
+ * Errors: NERVA_ERR_SHAPE (rows x cols beyond 2^31), NERVA_ERR_HIP. */
 int sparse_linear_enable_dense(nerva_layer *layer, void *stream);
 
 /* The library keeps derived copies of values[] (the mirror's values, the dense copies above) and

@@ -24,6 +24,11 @@ extern "C" {
 enum { NERVA_PARTITION_BALANCED = 0, NERVA_PARTITION_ROW_SPLIT = 1, NERVA_PARTITION_PREFER_STAGED = 2 };
 int nerva_set_partition_mode(int32_t mode);
 
+/* Measurement aid: the density from which sparse_linear_create / sparse_linear_rebind put a layer on the
+ * dense route by themselves (process-wide; layers already bound keep their route).  Default 0.4; a value above
+ * 1 keeps every later layer on the sparse route, 0 sends every layer of at least 64 x 64 down the dense one. */
+int nerva_set_dense_threshold(float density);
+
 /* Per-kernel timing of mlp_train_step with HIP events, for benchmarks.  After
  * mlp_profile_enable(mlp, max_steps > 0) the next max_steps training steps record an event
  * before every kernel launch and one after the last, on the step's stream (events are created

@@ -29,7 +29,7 @@ NERVA_STATIC_WORKSPACE_BYTES = 32 << 20
 NERVA_HUGE_FLAG = 0x40000000
 
 EXPORTS = [
-    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_plan_staged_host", "nerva_set_partition_mode",
+    "nerva_last_error", "nerva_build_info", "nerva_validate_csr_host", "nerva_plan_rows_host", "nerva_plan_short_rows_host", "nerva_plan_staged_host", "nerva_set_partition_mode", "nerva_set_dense_threshold",
     "sparse_linear_create", "sparse_linear_destroy", "sparse_linear_rebind", "sparse_linear_enable_dense", "sparse_linear_sync_values", "sparse_linear_mirror",
     "sparse_linear_forward", "sparse_linear_backward", "sgd_update_values", "sgd_update_values_nesterov",
     "softmax_cross_entropy", "mlp_create", "mlp_destroy", "mlp_rebind_velocity", "mlp_workspace_bytes",
@@ -59,6 +59,7 @@ def _load() -> ctypes.CDLL:
         "nerva_plan_short_rows_host": (ctypes.c_int, [i32, vp, vp, vp, vp]),
         "nerva_plan_staged_host": (ctypes.c_int, [i32, i32, vp, vp, i32, i32, vp, vp, vp]),
         "nerva_set_partition_mode": (ctypes.c_int, [i32]),
+        "nerva_set_dense_threshold": (ctypes.c_int, [f32]),
         "sparse_linear_create": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, vp]),
         "sparse_linear_destroy": (None, [vp]),
         "sparse_linear_rebind": (ctypes.c_int, [vp, i32, vp, vp, vp, vp]),
@@ -150,6 +151,10 @@ def nerva_plan_rows_host(rows: int, indptr):
 
 def nerva_set_partition_mode(mode: int) -> None:
     _check(lib.nerva_set_partition_mode(mode))
+
+
+def nerva_set_dense_threshold(density: float) -> None:
+    _check(lib.nerva_set_dense_threshold(density))
 
 
 def nerva_plan_short_rows_host(rows: int, indptr):

@@ -123,17 +123,16 @@ struct nerva_layer {
     size_t partial_floats = 0;
     int64_t partial_stride = 0, partial_db_at = 0;
     int32_t partial_tiles = 0;
-    // owned, only after sparse_linear_enable_dense: zero-filled dense copies of W (rows x dense_ld)
-    // and of W^T (cols x dense_t_ld), leading dimensions padded to multiples of 32
+    // owned, only on the dense route (sparse_linear_enable_dense, or chosen when the pattern was bound): a
+    // zero-filled dense copy of W (rows x dense_ld, dense_ld = cols rounded up to kDenseLdAlign) and a dense
+    // gradient of the same shape
     bool dense_on = false;
-    float *dense = nullptr, *dense_t = nullptr;
-    int64_t dense_ld = 0, dense_t_ld = 0;
+    float *dense = nullptr, *dense_g = nullptr;
+    int64_t dense_ld = 0;
     // owned, only for a matrix that stores every entry and has at most kFullMaxRows rows
     bool full = false;               // the bound pattern is such a matrix
     float *full_scratch = nullptr;   // slice partials of the streaming product, (slices * rows, full_scratch_ld); kept once allocated
     int64_t full_scratch_ld = 0;
-    float *dense_scratch = nullptr;  // partial tiles of a K-split product: kDenseMaxSplits x max(rows, cols) x dense_scratch_ld
-    int64_t dense_scratch_ld = 0;
     // values_t lags behind values[]: a training step updated this layer as the first layer of an MLP,
     // whose mirror no product reads, and left the mirror's values alone.  Whoever reads values_t next
     // (a step that has the layer further up, sparse_linear_backward, sparse_linear_sync_values)
@@ -602,8 +601,7 @@ void free_layer_buffers(nerva_layer *l)
     (void)hipFree(l->scratch);
     (void)hipFree(l->partial);
     (void)hipFree(l->dense);
-    (void)hipFree(l->dense_t);
-    (void)hipFree(l->dense_scratch);
+    (void)hipFree(l->dense_g);
     (void)hipFree(l->full_scratch);
 }
 
@@ -739,52 +737,56 @@ int nerva_plan_staged_host(int32_t rows, int32_t cols, const int32_t *indptr_hos
     return NERVA_OK;
 }
 
-// Dense copies for the dense route: allocated zero, then filled from the stored entries.
+// Density from which a layer bound by sparse_linear_create / sparse_linear_rebind takes the dense route by
+// itself (process-wide; nerva_set_dense_threshold).  The default is the measured cut-over on the paper's MLP.
+std::atomic<float> g_dense_threshold{kDenseFromDensity};
+
+static bool dense_shape_ok(int32_t rows, int32_t cols)
+{
+    // (a thin full matrix has its own streaming kernels; the copy and the dense gradient stay below 2 GiB each)
+    return rows >= 64 && cols >= 64 && static_cast<int64_t>(rows) * round_up(cols, kDenseLdAlign) < (1ll << 29);
+}
+
+// The dense copy for the dense route: allocated zero, then filled from the stored entries; and the dense gradient.
 static hipError_t build_dense_copies(nerva_layer *l, hipStream_t s)
 {
-    l->dense_ld = round_up(l->cols, 32);
-    l->dense_t_ld = round_up(l->rows, 32);
-    const size_t bytes = static_cast<size_t>(l->rows) * l->dense_ld * 4, bytes_t = static_cast<size_t>(l->cols) * l->dense_t_ld * 4;
-    l->dense_scratch_ld = round_up(l->max_batch, 32);
-    const size_t bytes_s = static_cast<size_t>(kDenseMaxSplits) * (l->rows > l->cols ? l->rows : l->cols) * l->dense_scratch_ld * 4;
+    l->dense_ld = round_up(l->cols, kDenseLdAlign);
+    const size_t bytes = static_cast<size_t>(l->rows) * l->dense_ld * 4;
     hipError_t e = hipMalloc(&l->dense, bytes);
-    if (e == hipSuccess) e = hipMalloc(&l->dense_t, bytes_t);
-    if (e == hipSuccess) e = hipMalloc(&l->dense_scratch, bytes_s);
+    if (e == hipSuccess) e = hipMalloc(&l->dense_g, bytes);
     if (e == hipSuccess) e = hipMemsetAsync(l->dense, 0, bytes, s);
-    if (e == hipSuccess) e = hipMemsetAsync(l->dense_t, 0, bytes_t, s);
-    if (e == hipSuccess)
-        e = launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, l->dense_t, l->dense_t_ld, s);
+    if (e == hipSuccess) e = launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, s);
     return e;
 }
 
 static hipError_t refresh_dense_copies(const nerva_layer *l, hipStream_t s)
 {
-    return launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, l->dense_t, l->dense_t_ld, s);
+    return launch_dense_refresh(l->indptr, l->indices, l->values, l->rows, l->dense, l->dense_ld, s);
 }
 
-// Y = act(W X + b) through the dense copy of W^T
+// Y = act(W X + b) through the dense copy
 static hipError_t dense_forward(const nerva_layer *l, const float *X, int64_t ldx, float *Y, int64_t ldy, int32_t batch,
                                 hipStream_t s)
 {
     DenseArgs d{};
-    d.AT = l->dense_t; d.lda = l->dense_t_ld; d.X = X; d.ldx = ldx; d.Y = Y; d.ldy = ldy; d.bias = l->bias;
-    d.M = l->rows; d.K = l->cols; d.batch = batch; d.relu = l->activation == NERVA_ACT_RELU;
-    d.scratch = l->dense_scratch; d.scratch_ld = l->dense_scratch_ld;
-    return launch_dense_gemm(d, s);
+    d.W = l->dense; d.ldw = l->dense_ld; d.trans = 0; d.X = X; d.ldx = ldx; d.Y = Y; d.ldy = ldy; d.bias = l->bias;
+    d.rows = l->rows; d.cols = l->cols; d.batch = batch; d.relu = l->activation == NERVA_ACT_RELU;
+    return launch_dense_product(d, s);
 }
 
-// dX = (W^T dZ) * [mask > 0] through the dense copy of W
+// dX = (W^T dZ) * [mask > 0] through the same copy
 static hipError_t dense_transposed(const nerva_layer *l, const float *dZ, int64_t lddz, float *dX, int64_t lddx,
                                    const float *mask, int64_t ldmask, int32_t batch, hipStream_t s)
 {
     DenseArgs d{};
-    d.AT = l->dense; d.lda = l->dense_ld; d.X = dZ; d.ldx = lddz; d.Y = dX; d.ldy = lddx;
-    d.YM = mask; d.ldym = ldmask; d.M = l->cols; d.K = l->rows; d.batch = batch;
-    d.scratch = l->dense_scratch; d.scratch_ld = l->dense_scratch_ld;
-    return launch_dense_gemm(d, s);
+    d.W = l->dense; d.ldw = l->dense_ld; d.trans = 1; d.X = dZ; d.ldx = lddz; d.Y = dX; d.ldy = lddx;
+    d.YM = mask; d.ldym = ldmask; d.rows = l->rows; d.cols = l->cols; d.batch = batch;
+    return launch_dense_product(d, s);
 }
 
-// the dense route needs a batch wide enough to fill its 32-column tiles
+static int enable_dense(nerva_layer *layer, hipStream_t s);
+
+// the dense route needs a batch wide enough to fill its 16-column tiles
 static bool use_dense(const nerva_layer *l, int32_t batch) { return l->dense_on && batch >= 16; }
 
 // Message for the status word of the device-side CSR check (launch_validate_csr).
@@ -940,6 +942,15 @@ int sparse_linear_create(nerva_layer **out, int32_t rows, int32_t cols, int32_t 
         return rc;
     }
     adopt_pattern(l, nnz, indptr, indices, values, bp);
+    // the density-adaptive choice: dense products where the pattern is dense enough for them to be the faster ones
+    if (dense_shape_ok(rows, cols) && static_cast<double>(nnz) >= static_cast<double>(g_dense_threshold.load()) * rows * cols) {
+        const int rd = enable_dense(l, as_stream(stream));
+        if (rd != NERVA_OK) {
+            free_layer_buffers(l);
+            delete l;
+            return rd;
+        }
+    }
     *out = l;
     return NERVA_OK;
 }
@@ -955,35 +966,46 @@ int sparse_linear_rebind(nerva_layer *layer, int32_t nnz, const int32_t *indptr,
     const int rc = build_structures(layer, nnz, indptr, indices, values, &bp, s);
     if (rc != NERVA_OK) return rc;  // the layer keeps its old pattern: only the spare set and scratch buffers were written
     adopt_pattern(layer, nnz, indptr, indices, values, bp);
+    if (!layer->dense_on && dense_shape_ok(layer->rows, layer->cols) &&
+        static_cast<double>(nnz) >= static_cast<double>(g_dense_threshold.load()) * layer->rows * layer->cols)
+        return enable_dense(layer, s);   // (a pattern that has grown dense; a route once taken is kept)
     if (layer->dense_on) {
         // the dense copies hold the old pattern's entries: cleared and filled again
-        const size_t bytes = static_cast<size_t>(layer->rows) * layer->dense_ld * 4, bytes_t = static_cast<size_t>(layer->cols) * layer->dense_t_ld * 4;
+        const size_t bytes = static_cast<size_t>(layer->rows) * layer->dense_ld * 4;
         HIP_TRY(hipMemsetAsync(layer->dense, 0, bytes, s));
-        HIP_TRY(hipMemsetAsync(layer->dense_t, 0, bytes_t, s));
         HIP_TRY(refresh_dense_copies(layer, s));
         HIP_TRY(hipStreamSynchronize(s));
     }
     return NERVA_OK;
 }
 
-int sparse_linear_enable_dense(nerva_layer *layer, void *stream)
+static int enable_dense(nerva_layer *layer, hipStream_t s)
 {
-    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
     if (layer->dense_on) return NERVA_OK;
-    if (static_cast<int64_t>(layer->rows) * round_up(layer->cols, 32) >= (1ll << 31) ||
-        static_cast<int64_t>(layer->cols) * round_up(layer->rows, 32) >= (1ll << 31))
+    if (static_cast<int64_t>(layer->rows) * round_up(layer->cols, kDenseLdAlign) >= (1ll << 31))
         return fail(NERVA_ERR_SHAPE, "a %d x %d layer is too large for the dense route", layer->rows, layer->cols);
-    hipStream_t s = as_stream(stream);
     hipError_t e = build_dense_copies(layer, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         (void)hipFree(layer->dense);
-        (void)hipFree(layer->dense_t);
-        (void)hipFree(layer->dense_scratch);
-        layer->dense = layer->dense_t = layer->dense_scratch = nullptr;
+        (void)hipFree(layer->dense_g);
+        layer->dense = layer->dense_g = nullptr;
         return hip_fail(e, "sparse_linear_enable_dense");
     }
     layer->dense_on = true;
+    return NERVA_OK;
+}
+
+int sparse_linear_enable_dense(nerva_layer *layer, void *stream)
+{
+    if (!layer) return fail(NERVA_ERR_ARGUMENT, "layer is null");
+    return enable_dense(layer, as_stream(stream));
+}
+
+int nerva_set_dense_threshold(float density)
+{
+    if (!(density >= 0.f)) return fail(NERVA_ERR_ARGUMENT, "the density threshold must not be negative");
+    g_dense_threshold.store(density);
     return NERVA_OK;
 }
 
@@ -1396,7 +1418,7 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; g.perm = ly->perm; }  // the first layer's mirror is never read
-            if (ly->dense_on) { g.dense = ly->dense; g.dense_t = ly->dense_t; g.dense_ld = ly->dense_ld; g.dense_t_ld = ly->dense_t_ld; }
+            if (ly->dense_on) { g.dense = ly->dense; g.dense_ld = ly->dense_ld; }
             g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
         } else {
             g.g = reinterpret_cast<float *>(ws + L.g[l]);
@@ -1416,7 +1438,28 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
         // `pending`: a layer whose transposed product has run and whose S has not.  Where a layer's T and S
         // can share their gathers (backward_fused_ok) they run as one launch and nothing stays pending.
         int pending = -1;
+        // S_l through the dense gradient: for a layer on the dense route whose operands allow 16-byte accesses
+        auto dense_S_ok = [&](int l) {
+            const nerva_layer *ly = mlp->layers[l];
+            const float *in = l > 0 ? A(l - 1) : X;
+            const int64_t ldin = l > 0 ? L.ld : ldx;
+            return use_dense(ly, batch) && ly->nnz > 0 && ldin % 4 == 0 && (reinterpret_cast<uintptr_t>(in) & 15u) == 0 &&
+                   !(head && l == n - 1 && loss_out);
+        };
         auto run_S_alone = [&](int l) -> int {
+            if (dense_S_ok(l)) {
+                nerva_layer *ly = mlp->layers[l];
+                DenseUpdateArgs u{};
+                u.indptr = ly->indptr; u.indices = ly->indices; u.dZ = dZ(l); u.lddz = L.ld;
+                u.G = ly->dense_g; u.ldg = ly->dense_ld; u.D = ly->dense; u.ldw = ly->dense_ld;
+                u.values = ly->values; u.velocity = mlp->vel[l];
+                if (l > 0) { u.values_t = ly->values_t; u.pos_t = ly->pos_t; }
+                u.bias = ly->bias; u.bias_velocity = mlp->bias_vel[l];
+                u.rows = ly->rows; u.cols = ly->cols; u.batch = batch; u.nesterov = nesterov; u.lr = lr; u.momentum = momentum;
+                Timed tm(mlp->prof, s, "dense_sddmm_update", l);
+                HIP_TRY(launch_dense_sddmm_update(u, l > 0 ? A(l - 1) : X, l > 0 ? L.ld : ldx, s));
+                return NERVA_OK;
+            }
             Timed tm(mlp->prof, s, "sddmm_update", l);
             HIP_TRY(launch_sddmm(make_S(l), s));
             return NERVA_OK;
@@ -1441,7 +1484,7 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
             }
             if (pending >= 0) {
                 const SddmmArgs g = make_S(pending);
-                if (can_pair(t, g)) {
+                if (!dense_S_ok(pending) && can_pair(t, g)) {
                     Timed tm(mlp->prof, s, "spmm_transposed+sddmm_update", l);
                     HIP_TRY(launch_pair(t, g, s));
                 } else {
@@ -1457,7 +1500,7 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
         // the first layer has no transposed product: its S, with the one still pending if any
         if (pending >= 0) {
             const SddmmArgs gp = make_S(pending), g0 = make_S(0);
-            if (pending == 1 && can_pair(g0, gp)) {
+            if (pending == 1 && !dense_S_ok(0) && !dense_S_ok(1) && can_pair(g0, gp)) {
                 Timed tm(mlp->prof, s, "sddmm_update+sddmm_update", 0);
                 HIP_TRY(launch_pair(g0, gp, s));  // the larger layer's work-groups start first
             } else {

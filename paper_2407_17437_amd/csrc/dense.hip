@@ -1,0 +1,382 @@
+// Dense route of a layer whose density is high (the density-adaptive layer that the paper plans in
+// "Discussion and Conclusion" and Appendix C.3: dense computation where it is the faster one).
+// One zero-filled dense copy of the weights, D[i * ld + j] = W(i, j) (row-major, ld = cols rounded up to
+// 64, zero off the pattern and in the padding), serves three fp32 MFMA products:
+//     Y  = act(W X + b)          dense_nn_kernel      A operand = rows of D, 16 bytes per lane along k
+//     dX = (W^T dZ) * [mask > 0]  dense_tn_kernel      A operand = D read down its columns: the same copy,
+//                                                      16 bytes per lane along the output rows
+//     G  = dZ X^T                dense_nt_kernel      both operands 16 bytes per lane along the batch
+// followed, for the last one, by dense_update_kernel, which picks the entries of G that lie on the
+// pattern and applies the momentum step to values[] (the state stays sparse; the copy is derived).
+//
+// v_mfma_f32_16x16x4_f32: lane l supplies A(l % 16, l / 16) and B(l / 16, l % 16) of a 16 x 4 by 4 x 16
+// step; register r of lane l holds C(4 * (l / 16) + r, l % 16).  A lane's four k slots need not be
+// consecutive k as long as A and B agree, so one 16-byte load along k feeds four steps (slot q of
+// step s: k = base + 4 q + s), and one 16-byte load along the output rows feeds four tiles (tile u
+// holds the rows base + 4 r + u).  Small tiles (16 rows) on purpose: these products are a few hundred
+// MFLOP, and only thousands of tiles fill 1024 matrix units.  Every sum has one fixed order.
+#include "kernels.h"
+
+namespace nerva {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kDenseWaves = 4;
+constexpr int kDenseBlock = kWave * kDenseWaves;
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)); }
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ v4f mfma(float a, float b, v4f c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+
+__device__ __forceinline__ void dense_epilogue(const DenseArgs &a, int row, int col, int m_rows, float y)
+{
+    if (row >= m_rows || col >= a.batch) return;
+    if (a.bias) y += a.bias[row];
+    if (a.relu) y = y > 0.f ? y : 0.f;
+    if (a.YM) y = a.YM[static_cast<int64_t>(row) * a.ldym + col] > 0.f ? y : 0.f;
+    a.Y[static_cast<int64_t>(row) * a.ldy + col] = y;
+}
+
+// Y (rows x batch) = act(D X + b).  Work-group: 16 rows x NB * 16 columns; its kSplitWaves waves split K = cols
+// into contiguous slices (multiples of 16) and meet in LDS, where wave w adds register (w % 4) of all slices in
+// slice order for the tile columns t = w / 4, w / 4 + 4, ...  The loads of kNnDepth chunks of 16 k are all issued
+// before the first of their MFMA steps: these products are short, and their time is load latency.
+constexpr int kSplitWaves = 16;
+constexpr int kSplitBlock = kSplitWaves * kWave;
+constexpr int kNnDepth = 4;
+
+template <int NB>
+__device__ __forceinline__ void nn_chunks(const DenseArgs &a, const float *wrow, bool row_ok, const int64_t (&xcol)[NB],
+                                          const bool (&col_ok)[NB], int q, int c0, int n_chunks, v4f (&acc)[NB])
+{
+    const int K = a.cols;
+    float4 w4[kNnDepth];
+    float b[kNnDepth][4][NB];
+#pragma unroll
+    for (int d = 0; d < kNnDepth; ++d) {
+        const int kb = (c0 + (d < n_chunks ? d : 0)) * 16;   // (chunks past the end repeat the first one and are not used)
+        w4[d] = ld4(wrow + kb);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int k = kb + q * 4 + s;
+            const float *xr = a.X + static_cast<int64_t>(k < K ? k : 0) * a.ldx;
+#pragma unroll
+            for (int t = 0; t < NB; ++t) b[d][s][t] = xr[xcol[t]];
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < kNnDepth; ++d) {
+        if (d >= n_chunks) break;  // wave-uniform
+        const int kb = (c0 + d) * 16;
+        const float wv4[4] = {w4[d].x, w4[d].y, w4[d].z, w4[d].w};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bool k_ok = kb + q * 4 + s < K;
+#pragma unroll
+            for (int t = 0; t < NB; ++t)
+                acc[t] = mfma(row_ok ? wv4[s] : 0.f, (k_ok && col_ok[t]) ? b[d][s][t] : 0.f, acc[t]);
+        }
+    }
+}
+
+template <int NB>
+__global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a)
+{
+    __shared__ float part[kSplitWaves][NB][4][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wv = wave_id();
+    const int r = lane & 15, q = lane >> 4;
+    const int i0 = blockIdx.x * 16, n0 = blockIdx.y * (16 * NB);
+    const int K = a.cols;
+    const int row = i0 + r;
+    const bool row_ok = row < a.rows;
+    const float *wrow = a.W + static_cast<int64_t>(row_ok ? row : 0) * a.ldw + q * 4;
+    int64_t xcol[NB];
+    bool col_ok[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int c = n0 + 16 * t + r;
+        col_ok[t] = c < a.batch;
+        xcol[t] = col_ok[t] ? c : 0;     // lanes beyond the batch re-read column 0 and contribute 0
+    }
+    const int k16 = (K + 15) / 16;                                   // chunks of 16 k (the copy's rows are padded with zeros)
+    const int per = (k16 + kSplitWaves - 1) / kSplitWaves;
+    const int c_begin = min(wv * per, k16), c_end = min(c_begin + per, k16);
+    v4f acc[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int c = c_begin; c < c_end; c += kNnDepth) nn_chunks<NB>(a, wrow, row_ok, xcol, col_ok, q, c, min(kNnDepth, c_end - c), acc);
+#pragma unroll
+    for (int t = 0; t < NB; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) part[wv][t][g][lane] = acc[t][g];
+    __syncthreads();
+    const int g = wv & 3;
+    for (int t = wv >> 2; t < NB; t += kSplitWaves / 4) {
+        float y = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSplitWaves; ++w) y += part[w][t][g][lane];
+        dense_epilogue(a, i0 + 4 * q + g, n0 + 16 * t + r, a.rows, y);
+    }
+}
+
+// Y (cols x batch) = (D^T X) * [YM > 0].  Work-group: 64 output rows (four tiles fed by one 16-byte load along
+// the row of D: tile u holds the output rows j0 + 4 r' + u) x NB * 16 columns; the waves split K = rows, kTnDepth
+// steps of loads in flight.  Wave w adds tile (w / 4), register (w % 4) of all slices in slice order.
+constexpr int kTnDepth = 8;
+
+template <int NB>
+__global__ __launch_bounds__(kSplitBlock) void dense_tn_kernel(const DenseArgs a)
+{
+    __shared__ float part[kSplitWaves][4][NB][4][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wv = wave_id();
+    const int r = lane & 15, q = lane >> 4;
+    const int j0 = blockIdx.x * 64, n0 = blockIdx.y * (16 * NB);
+    const int K = a.rows;
+    const float *wcol = a.W + j0 + r * 4;     // (ld is a multiple of 64: the access stays inside the row)
+    int64_t xcol[NB];
+    bool col_ok[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int c = n0 + 16 * t + r;
+        col_ok[t] = c < a.batch;
+        xcol[t] = col_ok[t] ? c : 0;
+    }
+    const int k4 = (K + 3) / 4;                                     // steps of 4 k (one per slot)
+    const int per = (k4 + kSplitWaves - 1) / kSplitWaves;
+    const int c_begin = min(wv * per, k4), c_end = min(c_begin + per, k4);
+    v4f acc[4][NB];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NB; ++t) acc[u][t] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int c = c_begin; c < c_end; c += kTnDepth) {
+        const int n_steps = min(kTnDepth, c_end - c);
+        float4 w4[kTnDepth];
+        float b[kTnDepth][NB];
+#pragma unroll
+        for (int d = 0; d < kTnDepth; ++d) {
+            const int i = (c + (d < n_steps ? d : 0)) * 4 + q;       // (steps past the end repeat the first one and are not used)
+            const int64_t ii = i < K ? i : 0;
+            w4[d] = ld4(wcol + ii * a.ldw);
+#pragma unroll
+            for (int t = 0; t < NB; ++t) b[d][t] = a.X[ii * a.ldx + xcol[t]];
+        }
+#pragma unroll
+        for (int d = 0; d < kTnDepth; ++d) {
+            if (d >= n_steps) break;  // wave-uniform
+            const bool i_ok = (c + d) * 4 + q < K;
+            const float wv4[4] = {w4[d].x, w4[d].y, w4[d].z, w4[d].w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int t = 0; t < NB; ++t) acc[u][t] = mfma(i_ok ? wv4[u] : 0.f, (i_ok && col_ok[t]) ? b[d][t] : 0.f, acc[u][t]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int t = 0; t < NB; ++t)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) part[wv][u][t][g][lane] = acc[u][t][g];
+    __syncthreads();
+    const int u = wv >> 2, g = wv & 3;
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        float y = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSplitWaves; ++w) y += part[w][u][t][g][lane];
+        dense_epilogue(a, j0 + 4 * (4 * q + g) + u, n0 + 16 * t + r, a.cols, y);
+    }
+}
+
+// G (rows x ldg) = dZ X^T over the batch: G[i][j] = sum_c dZ[i, c] * X[j, c].  K = batch is short, so there
+// is no split: a wave owns 16 rows x NB * 16 columns of G.  Columns of the batch beyond `batch` inside a
+// 16-byte access are dropped (padding may hold anything).
+template <int NB>
+__global__ __launch_bounds__(kDenseBlock) void dense_nt_kernel(const float *__restrict__ dZ, int64_t lddz, const float *__restrict__ X,
+                                                              int64_t ldx, float *__restrict__ G, int64_t ldg, int rows, int cols, int batch)
+{
+    const int lane = threadIdx.x & (kWave - 1), wv = wave_id();
+    const int r = lane & 15, q = lane >> 4;
+    const int i0 = blockIdx.x * 16, j0 = (blockIdx.y * kDenseWaves + wv) * (16 * NB);
+    if (j0 >= cols) return;  // wave-uniform
+    const bool row_ok = i0 + r < rows;
+    const float *zr = dZ + static_cast<int64_t>(row_ok ? i0 + r : 0) * lddz;
+    const float *xr[NB];
+    bool x_ok[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const int j = j0 + 16 * t + r;
+        x_ok[t] = j < cols;
+        xr[t] = X + static_cast<int64_t>(x_ok[t] ? j : 0) * ldx;
+    }
+    auto masked = [&](const float *p, int c, bool ok) {
+        // the access starts inside the row's allocation when c < batch (leading dimensions are multiples of 4)
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok && c < batch) {
+            v = ld4(p + c);
+            if (c + 1 >= batch) v.y = 0.f;
+            if (c + 2 >= batch) v.z = 0.f;
+            if (c + 3 >= batch) v.w = 0.f;
+        }
+        return v;
+    };
+    v4f acc[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+    constexpr int kDepth = 4;  // chunks of 16 columns of the batch whose loads are in flight together
+    for (int kb = 0; kb < batch; kb += 16 * kDepth) {
+        float4 z4[kDepth], x4[kDepth][NB];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int c = kb + 16 * d + q * 4;
+            z4[d] = masked(zr, c, row_ok);
+#pragma unroll
+            for (int t = 0; t < NB; ++t) x4[d][t] = masked(xr[t], c, x_ok[t]);
+        }
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (kb + 16 * d >= batch) break;  // wave-uniform
+            const float zv[4] = {z4[d].x, z4[d].y, z4[d].z, z4[d].w};
+#pragma unroll
+            for (int t = 0; t < NB; ++t) {
+                const float xv[4] = {x4[d][t].x, x4[d][t].y, x4[d][t].z, x4[d][t].w};
+#pragma unroll
+                for (int s = 0; s < 4; ++s) acc[t] = mfma(zv[s], xv[s], acc[t]);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NB; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int i = i0 + 4 * q + g, j = j0 + 16 * t + r;
+            if (i < rows && j < cols) G[static_cast<int64_t>(i) * ldg + j] = acc[t][g];
+        }
+}
+
+__device__ __forceinline__ void momentum_step(float &w, float &v, float g, float lr, float mu, int nesterov)
+{
+    const float step = lr * g;
+    v = fmaf(mu, v, -step);
+    w = nesterov ? w + fmaf(mu, v, -step) : w + v;
+}
+
+// A work-group per row of W: the row's stored entries take their gradient from G, the momentum step is applied
+// to values[] / velocity[], and the new weight goes to the mirror and to the dense copy; the row sum of dZ is
+// the bias gradient (first wave).  Four strides of loads are in flight per thread.
+__global__ __launch_bounds__(kDenseBlock) void dense_update_kernel(const DenseUpdateArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    constexpr int kU = 4;
+    for (int64_t i = blockIdx.x; i < a.rows; i += gridDim.x) {
+        const int32_t b = a.indptr[i], e = a.indptr[i + 1];
+        const float *grow = a.G + i * a.ldg;
+        float *drow = a.D + i * a.ldw;
+        for (int32_t p0 = b + threadIdx.x; p0 < e; p0 += kU * kDenseBlock) {
+            int32_t p[kU], j[kU], pt[kU];
+            float w[kU], v[kU], g[kU];
+            bool ok[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                p[u] = p0 + u * kDenseBlock;
+                ok[u] = p[u] < e;
+                if (!ok[u]) p[u] = p0;
+                j[u] = a.indices[p[u]];
+                w[u] = a.values[p[u]];
+                v[u] = a.velocity[p[u]];
+                pt[u] = a.values_t ? a.pos_t[p[u]] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) g[u] = grow[j[u]];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                if (!ok[u]) continue;
+                momentum_step(w[u], v[u], g[u], a.lr, a.momentum, a.nesterov);
+                a.values[p[u]] = w[u];
+                a.velocity[p[u]] = v[u];
+                if (a.values_t) a.values_t[pt[u]] = w[u];
+                drow[j[u]] = w[u];
+            }
+        }
+        if (a.bias && wave_id() == 0) {
+            const float *zr = a.dZ + i * a.lddz;
+            float s = 0.f;
+            for (int c = lane; c < a.batch; c += kWave) s += zr[c];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, kWave);   // every lane ends with the same bits
+            if (lane == 0) {
+                float w = a.bias[i], v = a.bias_velocity[i];
+                momentum_step(w, v, s, a.lr, a.momentum, a.nesterov);
+                a.bias[i] = w;
+                a.bias_velocity[i] = v;
+            }
+        }
+    }
+}
+
+// One wave per row of the CSR matrix: scatters the row's values into the dense copy.
+__global__ __launch_bounds__(kDenseBlock) void dense_refresh_kernel(const int32_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                                   const float *__restrict__ values, int rows, float *D, int64_t ld)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int i = blockIdx.x * kDenseWaves + wave_id(); i < rows; i += gridDim.x * kDenseWaves)
+        for (int p = indptr[i] + lane; p < indptr[i + 1]; p += kWave) D[static_cast<int64_t>(i) * ld + indices[p]] = values[p];
+}
+
+inline int blocks_for_rows(int64_t rows)
+{
+    int64_t b = (rows + kDenseWaves - 1) / kDenseWaves;
+    if (b < 1) b = 1;
+    if (b > 8192) b = 8192;
+    return static_cast<int>(b);
+}
+
+}  // namespace
+
+// Columns of the batch per work-group: as many as still leave the chip's 256 compute units a work-group each.
+static int dense_nb(int64_t m_tiles, int batch)
+{
+    for (int nb = 4; nb > 1; nb >>= 1)
+        if (m_tiles * ((batch + 16 * nb - 1) / (16 * nb)) >= 256) return nb;
+    return 1;
+}
+
+hipError_t launch_dense_product(const DenseArgs &a, hipStream_t s)
+{
+    if (a.rows <= 0 || a.cols <= 0 || a.batch <= 0) return hipSuccess;
+    if (!a.trans) {
+        const int64_t mt = (a.rows + 15) / 16;
+        const int nb = dense_nb(mt, a.batch);
+        const dim3 grid(static_cast<unsigned>(mt), (a.batch + 16 * nb - 1) / (16 * nb));
+        if (nb == 4) hipLaunchKernelGGL(dense_nn_kernel<4>, grid, dim3(kSplitBlock), 0, s, a);
+        else if (nb == 2) hipLaunchKernelGGL(dense_nn_kernel<2>, grid, dim3(kSplitBlock), 0, s, a);
+        else hipLaunchKernelGGL(dense_nn_kernel<1>, grid, dim3(kSplitBlock), 0, s, a);
+    } else {
+        // (one tile column per work-group: the 16 slices of 4 x 4 registers already take 64 KiB of LDS)
+        const dim3 grid(static_cast<unsigned>((a.cols + 63) / 64), (a.batch + 15) / 16);
+        hipLaunchKernelGGL(dense_tn_kernel<1>, grid, dim3(kSplitBlock), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_sddmm_update(const DenseUpdateArgs &a, const float *X, int64_t ldx, hipStream_t s)
+{
+    if (a.rows <= 0 || a.cols <= 0 || a.batch <= 0) return hipSuccess;
+    constexpr int NB = 2;
+    const dim3 grid((a.rows + 15) / 16, (a.cols + kDenseWaves * 16 * NB - 1) / (kDenseWaves * 16 * NB));
+    hipLaunchKernelGGL(dense_nt_kernel<NB>, grid, dim3(kDenseBlock), 0, s, a.dZ, a.lddz, X, ldx, a.G, a.ldg, a.rows, a.cols, a.batch);
+    hipLaunchKernelGGL(dense_update_kernel, dim3(a.rows < 16384 ? a.rows : 16384), dim3(kDenseBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows, float *D, int64_t ld,
+                                hipStream_t s)
+{
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(dense_refresh_kernel, dim3(blocks_for_rows(rows)), dim3(kDenseBlock), 0, s, indptr, indices, values, rows, D, ld);
+    return hipGetLastError();
+}
+
+}  // namespace nerva

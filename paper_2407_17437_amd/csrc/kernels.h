@@ -153,10 +153,10 @@ struct SddmmArgs {
     int64_t partial_db_at;    // >= nnz
     int32_t partial_tiles;    // tiles the buffer has room for
     int32_t nnz;
-    // dense copies of a layer on the dense route (or nullptr): the fused update stores every new
-    // weight there too, dense[row * dense_ld + col] and dense_t[col * dense_t_ld + row]
-    float *dense, *dense_t;
-    int64_t dense_ld, dense_t_ld;
+    // dense copy of a layer on the dense route (or nullptr): the fused update stores every new
+    // weight there too, dense[row * dense_ld + col]
+    float *dense;
+    int64_t dense_ld;
 };
 // Column-tile width (in columns) the products use when their gathered operand has x_rows rows and
 // does not fit an L2; 0: no tiling.  Shared by the kernels' dispatch and by the sizing of the
@@ -206,34 +206,48 @@ hipError_t launch_softmax_ce(const float *Z, int64_t ldz, const int32_t *labels,
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t s);
 
 // Dense route of a layer whose density is high (the density-adaptive layer the paper plans in
-// "Discussion and Conclusion"): Y = epilogue(A^T X) as an fp32 MFMA product, with A stored K-major
-// -- AT[k * lda + i] = A[i][k], lda a multiple of 32, padding zero -- so that the lanes of a wave
-// read consecutive addresses of both operands.  The forward product uses the dense copy of W^T
-// (K = cols), the transposed product the dense copy of W (K = rows); both hold 0 off the pattern.
+// "Discussion and Conclusion" and Appendix C.3).  One zero-filled dense copy of the weights, row-major
+// W[i * ldw + j] with ldw = cols rounded up to kDenseLdAlign (zero off the pattern and in the padding), serves
+// the forward product, the transposed product (the same copy read down its columns) and, through a dense
+// gradient G = dZ X^T of the same shape, the update of the stored entries.
+constexpr int32_t kDenseLdAlign = 64;
+constexpr float kDenseFromDensity = 0.4f;   // layers at least this dense take the dense route by themselves (measured cut-over)
 struct DenseArgs {
-    const float *AT;     // (K, lda)
-    int64_t lda;
-    const float *X;      // (K, ldx)
+    const float *W;      // the dense copy, (rows, ldw)
+    int64_t ldw;
+    int32_t trans;       // 0: Y (rows x batch) = act(W X + b);  1: Y (cols x batch) = (W^T X) * [YM > 0]
+    const float *X;      // (cols, ldx) or, transposed, (rows, ldx)
     int64_t ldx;
-    float *Y;            // (M, ldy)
+    float *Y;
     int64_t ldy;
-    const float *bias;   // [M] or nullptr
-    const float *YM;     // optional (M, ldym): result is multiplied by [YM > 0]
+    const float *bias;   // [rows] or nullptr (forward only)
+    const float *YM;     // optional: result is multiplied by [YM > 0]
     int64_t ldym;
-    int32_t M, K, batch;
+    int32_t rows, cols, batch;
     int32_t relu;
-    // K is also split over up to kDenseMaxSplits work-groups per tile when there are too few tiles
-    // to fill the chip; their partial tiles go to scratch[(split * M + row) * scratch_ld + column]
-    // and a second kernel adds them in split order and applies the epilogue.
-    float *scratch;      // room for kDenseMaxSplits * M * scratch_ld floats, or nullptr (then no split)
-    int64_t scratch_ld;  // >= batch
 };
-constexpr int32_t kDenseMaxSplits = 8;
-hipError_t launch_dense_gemm(const DenseArgs &a, hipStream_t s);
-// dense[i * ld + j] = dense_t[j * ld_t + i] = values[p] for every stored entry p = (i, j); the
-// rest of both arrays is not touched (zero since allocation)
-hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows,
-                                float *dense, int64_t ld, float *dense_t, int64_t ld_t, hipStream_t s);
+hipError_t launch_dense_product(const DenseArgs &a, hipStream_t s);
+// G = dZ X^T (rows x cols, dense), then per stored entry the momentum step with its element of G, the new weight
+// written to values[], the mirror and the dense copy; bias gradient = row sums of dZ.  Needs 16-byte aligned
+// operands with leading dimensions that are multiples of 4.
+struct DenseUpdateArgs {
+    const int32_t *indptr, *indices;
+    const float *dZ;     // (rows, lddz)
+    int64_t lddz;
+    float *G;            // (rows, ldg) scratch
+    int64_t ldg;
+    float *D;            // the dense copy
+    int64_t ldw;
+    float *values, *velocity, *values_t;   // values_t may be nullptr
+    const int32_t *pos_t;
+    float *bias, *bias_velocity;           // may be nullptr
+    int32_t rows, cols, batch, nesterov;
+    float lr, momentum;
+};
+hipError_t launch_dense_sddmm_update(const DenseUpdateArgs &a, const float *X, int64_t ldx, hipStream_t s);
+// D[i * ld + j] = values[p] for every stored entry p = (i, j); the rest of D is not touched (zero since allocation)
+hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows, float *D, int64_t ld,
+                                hipStream_t s);
 
 // ---- binding a pattern: the work that grows with the number of stored entries, on the device ----
 // Check that device arrays hold a canonical CSR pattern.  status (device, 4 ints) receives

@@ -1198,10 +1198,7 @@ __device__ __forceinline__ void sddmm_body(const SddmmArgs &a, const int block)
                 a.values[p] = w_old;
                 a.velocity[p] = v_old;
                 if (a.values_t) a.values_t[mirror_pos] = w_old;
-                if (a.dense) {
-                    a.dense[static_cast<int64_t>(row) * a.dense_ld + my_j] = w_old;
-                    a.dense_t[static_cast<int64_t>(my_j) * a.dense_t_ld + row] = w_old;
-                }
+                if (a.dense) a.dense[static_cast<int64_t>(row) * a.dense_ld + my_j] = w_old;
             }
         }
     }
@@ -1803,145 +1800,10 @@ __global__ __launch_bounds__(kBlock) void sddmm_generic(const SddmmArgs a)
                 a.values[p] = w;
                 a.velocity[p] = v;
                 if (a.values_t) a.values_t[a.pos_t[p]] = w;
-                if (a.dense) {
-                    const int64_t j = a.indices[p];
-                    a.dense[static_cast<int64_t>(row) * a.dense_ld + j] = w;
-                    a.dense_t[j * a.dense_t_ld + row] = w;
-                }
+                if (a.dense) a.dense[static_cast<int64_t>(row) * a.dense_ld + a.indices[p]] = w;
             }
         }
     }
-}
-
-// ---------------------------------------------------------------------------------------
-// Dense route: C = A^T-major x X with v_mfma_f32_32x32x2_f32.  A work-group owns a 32 x 64 tile
-// of the result (two MFMA tiles that share the A operand); its 16 waves split K into 16 contiguous slices (one MFMA consumes two values of
-// k: lane l supplies AT[k + l/32][i0 + l%32] and X[k + l/32][n0 + l%32], both coalesced), keep 8
-// steps of loads in flight, and meet in LDS, where wave w adds accumulator register w of all
-// slices in slice order and applies bias, ReLU and the optional output mask.  Register r of lane l
-// is element (row 8*(r/4) + 4*(l/32) + r%4, column l%32) of the tile.
-// ---------------------------------------------------------------------------------------
-typedef float v16f __attribute__((ext_vector_type(16)));
-constexpr int kDenseTileN = 64;  // columns per work-group: two MFMA tiles that share the A operand
-__global__ __launch_bounds__(kBlock) void dense_gemm_kernel(const DenseArgs a, const int k_splits)
-{
-    __shared__ float part[kWavesPerBlock][16][kWave];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wv = wave_in_block();
-    const int i0 = blockIdx.x * 32, n0 = blockIdx.y * kDenseTileN;
-    const int half = lane >> 5, l32 = lane & 31;
-    int col[2];
-    bool col_ok[2];
-    int64_t xoff[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        col[t] = n0 + 32 * t + l32;
-        col_ok[t] = col[t] < a.batch;
-        xoff[t] = col_ok[t] ? col[t] : 0;           // lanes beyond the batch re-read column 0 and contribute 0
-    }
-    const int64_t aoff = i0 + l32;                  // lda is padded to whole tiles
-    // K slices in units of 2 (one MFMA), as equal as possible: first over the work-groups that
-    // share the tile (blockIdx.z), then over the waves
-    const int pairs = (a.K + 1) / 2;
-    const int per_wg = (pairs + k_splits - 1) / k_splits;
-    const int wg_begin = min(static_cast<int>(blockIdx.z) * per_wg, pairs), wg_end = min(wg_begin + per_wg, pairs);
-    const int per = (wg_end - wg_begin + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int p_begin = min(wg_begin + wv * per, wg_end), p_end = min(p_begin + per, wg_end);
-    v16f acc[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-    constexpr int U = 8;
-    int p = p_begin;
-    for (; p + U <= p_end; p += U) {
-        float av[U], xv[U][2];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int k = 2 * (p + u) + half;
-            const bool k_ok = k < a.K;
-            const int64_t kk = k_ok ? k : 0;
-            av[u] = a.AT[kk * a.lda + aoff];
-            av[u] = k_ok ? av[u] : 0.f;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                xv[u][t] = a.X[kk * a.ldx + xoff[t]];
-                xv[u][t] = col_ok[t] ? xv[u][t] : 0.f;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], xv[u][t], acc[t], 0, 0, 0);
-    }
-    for (; p < p_end; ++p) {
-        const int k = 2 * p + half;
-        const bool k_ok = k < a.K;
-        const int64_t kk = k_ok ? k : 0;
-        float av = a.AT[kk * a.lda + aoff];
-        av = k_ok ? av : 0.f;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            float xv = a.X[kk * a.ldx + xoff[t]];
-            xv = col_ok[t] ? xv : 0.f;
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, xv, acc[t], 0, 0, 0);
-        }
-    }
-    const int row = i0 + 8 * (wv >> 2) + 4 * half + (wv & 3);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        if (t) __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 16; ++r) part[wv][r][lane] = acc[t][r];
-        __syncthreads();
-        float y = 0.f;
-        for (int w = 0; w < kWavesPerBlock; ++w) y += part[w][wv][lane];
-        if (row >= a.M || !col_ok[t]) continue;
-        if (k_splits > 1) {
-            a.scratch[(static_cast<int64_t>(blockIdx.z) * a.M + row) * a.scratch_ld + col[t]] = y;
-            continue;
-        }
-        y += a.bias ? a.bias[row] : 0.f;
-        if (a.relu) y = y > 0.f ? y : 0.f;
-        if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(row) * a.ldym + col[t]]);
-        a.Y[static_cast<int64_t>(row) * a.ldy + col[t]] = y;
-    }
-}
-
-// Second pass of a K-split dense product: partial tiles added in split order, then the epilogue.
-__global__ __launch_bounds__(kEwBlock) void dense_finish_kernel(const DenseArgs a, const int k_splits)
-{
-    const int row = blockIdx.x;
-    const int col = blockIdx.y * kEwBlock + threadIdx.x;
-    if (col >= a.batch) return;
-    float v[kDenseMaxSplits];
-#pragma unroll
-    for (int q = 0; q < kDenseMaxSplits; ++q)
-        v[q] = q < k_splits ? a.scratch[(static_cast<int64_t>(q) * a.M + row) * a.scratch_ld + col] : 0.f;
-    float y = 0.f;
-#pragma unroll
-    for (int q = 0; q < kDenseMaxSplits; ++q) y += v[q];
-    y += a.bias ? a.bias[row] : 0.f;
-    if (a.relu) y = y > 0.f ? y : 0.f;
-    if (a.YM) y = keep_where_positive(y, a.YM[static_cast<int64_t>(row) * a.ldym + col]);
-    a.Y[static_cast<int64_t>(row) * a.ldy + col] = y;
-}
-
-// One wave per row of the CSR matrix: scatters the row's values into the two dense copies.
-__global__ __launch_bounds__(kEwBlock) void dense_refresh_kernel(const int32_t *__restrict__ indptr,
-                                                                const int32_t *__restrict__ indices,
-                                                                const float *__restrict__ values, int rows,
-                                                                float *dense, int64_t ld, float *dense_t, int64_t ld_t)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int waves_per_block = kEwBlock / kWave;
-    for (int i = blockIdx.x * waves_per_block + (threadIdx.x >> 6); i < rows; i += gridDim.x * waves_per_block)
-        for (int p = indptr[i] + lane; p < indptr[i + 1]; p += kWave) {
-            const int j = indices[p];
-            const float w = values[p];
-            dense[static_cast<int64_t>(i) * ld + j] = w;
-            dense_t[static_cast<int64_t>(j) * ld_t + i] = w;
-        }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -2666,34 +2528,6 @@ hipError_t launch_momentum(float *w, float *v, const float *g, int64_t n, float 
     const int vec4 = aligned16(w) && aligned16(v) && aligned16(g);
     hipLaunchKernelGGL(momentum_kernel, dim3(elementwise_blocks(vec4 ? (n + 3) / 4 : n)), dim3(kEwBlock), 0, s,
                        w, v, g, n, lr, mu, nesterov, vec4);
-    return hipGetLastError();
-}
-
-hipError_t launch_dense_gemm(const DenseArgs &a, hipStream_t s)
-{
-    if (a.M <= 0 || a.batch <= 0) return hipSuccess;
-    const int tiles = ((a.M + 31) / 32) * ((a.batch + kDenseTileN - 1) / kDenseTileN);
-    // at least two work-groups per compute unit, and at least 64 MFMA steps per work-group
-    int k_splits = 1;
-    if (a.scratch) {
-        k_splits = (512 + tiles - 1) / tiles;
-        const int by_k = (a.K + 1) / 2 / 64;
-        if (k_splits > by_k) k_splits = by_k;
-        if (k_splits > kDenseMaxSplits) k_splits = kDenseMaxSplits;
-        if (k_splits < 1) k_splits = 1;
-    }
-    hipLaunchKernelGGL(dense_gemm_kernel, dim3((a.M + 31) / 32, (a.batch + kDenseTileN - 1) / kDenseTileN, k_splits), dim3(kBlock), 0, s, a, k_splits);
-    if (k_splits > 1)
-        hipLaunchKernelGGL(dense_finish_kernel, dim3(a.M, (a.batch + kEwBlock - 1) / kEwBlock), dim3(kEwBlock), 0, s, a, k_splits);
-    return hipGetLastError();
-}
-
-hipError_t launch_dense_refresh(const int32_t *indptr, const int32_t *indices, const float *values, int32_t rows,
-                                float *dense, int64_t ld, float *dense_t, int64_t ld_t, hipStream_t s)
-{
-    if (rows <= 0) return hipSuccess;
-    hipLaunchKernelGGL(dense_refresh_kernel, dim3(elementwise_blocks(static_cast<int64_t>(rows) * kWave)), dim3(kEwBlock), 0, s,
-                       indptr, indices, values, rows, dense, ld, dense_t, ld_t);
     return hipGetLastError();
 }
 

@@ -154,3 +154,45 @@ def test_sync_values_and_rebind_keep_the_dense_copies_right(nb, torch_mod, oracl
                                         M.layers[0].bias.cpu().numpy(), True)
     check()
     M.close()
+
+
+def test_the_library_chooses_the_route_by_density(nb, torch_mod, oracle):
+    """Bound with the library's default, a layer of at least 40 % density (and at least 64 x 64) takes the dense route by
+    itself, a sparser one does not; on the dense route the SDDMM + update of a training step runs through the dense
+    gradient.  Stage parity on both networks; the pattern arrays stay bit-identical on either route."""
+    torch = torch_mod
+    sizes, batch, lr, mu = (300, 200, 100, 10), 100, 0.05, 0.9
+    for sparsity, want_dense in [(0.5, True), (0.9, False)]:
+        mlp = wl.make_mlp(sizes, sparsity=sparsity, bias_std=0.1, pattern_seed=71, value_seed=72)
+        Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 3, seed=73)
+        M = nb.MLP(mlp, batch)
+        nb.mlp_profile_enable(M.handle, 1)
+        for t in range(3):
+            before = snapshot(M)
+            M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, lr, mu)
+            torch.cuda.synchronize()
+            if t == 0:
+                names = [n for n, _ in nb.mlp_profile_read(M.handle)[1]]
+                nb.mlp_profile_enable(M.handle, 0)
+                assert ("dense_forward[0]" in names) == want_dense and ("dense_sddmm_update[0]" in names) == want_dense, names
+                assert ("dense_transposed[1]" in names) == want_dense and ("dense_sddmm_update[1]" in names) == want_dense, names
+            stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, lr, mu, False)
+        for l, lay in zip(M.layers, mlp.layers):
+            assert np.array_equal(l.indptr.cpu().numpy(), lay.indptr) and np.array_equal(l.indices.cpu().numpy(), lay.indices)
+        M.close()
+
+
+@pytest.mark.parametrize("sizes,batch", [((130, 257, 70, 10), 37), ((64, 96, 200, 10), 300), ((100, 300, 64, 10), 16)])
+def test_dense_route_training_on_ragged_shapes(nb, torch_mod, oracle, sizes, batch):
+    """Ragged tiles in every dimension of the three dense products (rows, columns, batch not multiples of 16 / 64),
+    a batch beyond one column tile, and the narrowest batch that takes the route; Nesterov momentum."""
+    torch = torch_mod
+    mlp = wl.make_mlp(sizes, sparsity=0.4, bias_std=0.1, pattern_seed=81, value_seed=82)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 2, seed=83)
+    M = nb.MLP(mlp, batch, nb.NERVA_MLP_NESTEROV)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, False, nesterov=True)
+    M.close()

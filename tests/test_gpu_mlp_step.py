@@ -31,6 +31,15 @@ def torch_mod():
     return torch
 
 
+@pytest.fixture(scope="module", autouse=True)
+def sparse_route_only(nb):
+    """These tests are about the sparse kernels: layers are bound with the automatic choice of the dense route
+    switched off (tests/test_gpu_dense.py and the full-size tests run with the library's default)."""
+    nb.nerva_set_dense_threshold(2.0)
+    yield
+    nb.nerva_set_dense_threshold(0.4)
+
+
 def snapshot(M):
     return [dict(values=l.values.cpu().numpy().copy(), bias=l.bias.cpu().numpy().copy(),
                  vel_w=l.velocity.cpu().numpy().copy(), vel_b=l.bias_velocity.cpu().numpy().copy())

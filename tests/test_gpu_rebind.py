@@ -31,6 +31,15 @@ def torch_mod():
     return torch
 
 
+@pytest.fixture(scope="module", autouse=True)
+def sparse_route_only(nb):
+    """These tests are about the sparse kernels: layers are bound with the automatic choice of the dense route
+    switched off (tests/test_gpu_dense.py and the full-size tests run with the library's default)."""
+    nb.nerva_set_dense_threshold(2.0)
+    yield
+    nb.nerva_set_dense_threshold(0.4)
+
+
 def prune_and_grow(rows, cols, indptr, indices, values, velocity, k, seed):
     """New canonical CSR with the k smallest-magnitude entries removed and k new positions added
     (value 0, velocity 0); surviving entries keep value and velocity."""
