@@ -46,7 +46,9 @@ constexpr int kSplitWaves = 16;
 constexpr int kSplitBlock = kSplitWaves * kWave;
 constexpr int kNnDepth = 4;
 
-template <int NB>
+// VECX: the NB columns of a lane are consecutive (tile t holds the columns n0 + NB * r + t), so that one
+// 8- or 16-byte load along the batch feeds the NB tiles; needs X 16-byte aligned with ldx a multiple of 4.
+template <int NB, bool VECX>
 __device__ __forceinline__ void nn_chunks(const DenseArgs &a, const float *wrow, bool row_ok, const int64_t (&xcol)[NB],
                                           const bool (&col_ok)[NB], int q, int c0, int n_chunks, v4f (&acc)[NB])
 {
@@ -61,8 +63,16 @@ __device__ __forceinline__ void nn_chunks(const DenseArgs &a, const float *wrow,
         for (int s = 0; s < 4; ++s) {
             const int k = kb + q * 4 + s;
             const float *xr = a.X + static_cast<int64_t>(k < K ? k : 0) * a.ldx;
+            if constexpr (VECX && NB == 4) {
+                const float4 x = ld4(xr + xcol[0]);
+                b[d][s][0] = x.x; b[d][s][1] = x.y; b[d][s][2] = x.z; b[d][s][3] = x.w;
+            } else if constexpr (VECX && NB == 2) {
+                const float2 x = *reinterpret_cast<const float2 *>(xr + xcol[0]);
+                b[d][s][0] = x.x; b[d][s][1] = x.y;
+            } else {
 #pragma unroll
-            for (int t = 0; t < NB; ++t) b[d][s][t] = xr[xcol[t]];
+                for (int t = 0; t < NB; ++t) b[d][s][t] = xr[xcol[t]];
+            }
         }
     }
 #pragma unroll
@@ -80,7 +90,7 @@ __device__ __forceinline__ void nn_chunks(const DenseArgs &a, const float *wrow,
     }
 }
 
-template <int NB>
+template <int NB, bool VECX>
 __global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a)
 {
     __shared__ float part[kSplitWaves][NB][4][kWave];
@@ -93,19 +103,21 @@ __global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a
     const float *wrow = a.W + static_cast<int64_t>(row_ok ? row : 0) * a.ldw + q * 4;
     int64_t xcol[NB];
     bool col_ok[NB];
+    int col[NB];
 #pragma unroll
     for (int t = 0; t < NB; ++t) {
-        const int c = n0 + 16 * t + r;
-        col_ok[t] = c < a.batch;
-        xcol[t] = col_ok[t] ? c : 0;     // lanes beyond the batch re-read column 0 and contribute 0
+        col[t] = VECX ? n0 + NB * r + t : n0 + 16 * t + r;
+        col_ok[t] = col[t] < a.batch;
+        xcol[t] = col_ok[t] ? col[t] : 0;     // lanes beyond the batch re-read column 0 and contribute 0
     }
+    if constexpr (VECX) xcol[0] = col_ok[0] ? col[0] : 0;  // (the access of NB columns starts inside the row when its first column does)
     const int k16 = (K + 15) / 16;                                   // chunks of 16 k (the copy's rows are padded with zeros)
     const int per = (k16 + kSplitWaves - 1) / kSplitWaves;
     const int c_begin = min(wv * per, k16), c_end = min(c_begin + per, k16);
     v4f acc[NB];
 #pragma unroll
     for (int t = 0; t < NB; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
-    for (int c = c_begin; c < c_end; c += kNnDepth) nn_chunks<NB>(a, wrow, row_ok, xcol, col_ok, q, c, min(kNnDepth, c_end - c), acc);
+    for (int c = c_begin; c < c_end; c += kNnDepth) nn_chunks<NB, VECX>(a, wrow, row_ok, xcol, col_ok, q, c, min(kNnDepth, c_end - c), acc);
 #pragma unroll
     for (int t = 0; t < NB; ++t)
 #pragma unroll
@@ -116,7 +128,7 @@ __global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a
         float y = 0.f;
 #pragma unroll
         for (int w = 0; w < kSplitWaves; ++w) y += part[w][t][g][lane];
-        dense_epilogue(a, i0 + 4 * q + g, n0 + 16 * t + r, a.rows, y);
+        dense_epilogue(a, i0 + 4 * q + g, VECX ? n0 + NB * r + t : n0 + 16 * t + r, a.rows, y);
     }
 }
 
@@ -191,20 +203,24 @@ __global__ __launch_bounds__(kSplitBlock) void dense_tn_kernel(const DenseArgs a
 }
 
 // G (rows x ldg) = dZ X^T over the batch: G[i][j] = sum_c dZ[i, c] * X[j, c].  K = batch is short, so there
-// is no split: a wave owns 16 rows x NB * 16 columns of G.  Columns of the batch beyond `batch` inside a
+// is no split: a wave owns MB * 16 rows x NB * 16 columns of G.  Columns of the batch beyond `batch` inside a
 // 16-byte access are dropped (padding may hold anything).
-template <int NB>
+template <int MB, int NB>
 __global__ __launch_bounds__(kDenseBlock) void dense_nt_kernel(const float *__restrict__ dZ, int64_t lddz, const float *__restrict__ X,
                                                               int64_t ldx, float *__restrict__ G, int64_t ldg, int rows, int cols, int batch)
 {
     const int lane = threadIdx.x & (kWave - 1), wv = wave_id();
     const int r = lane & 15, q = lane >> 4;
-    const int i0 = blockIdx.x * 16, j0 = (blockIdx.y * kDenseWaves + wv) * (16 * NB);
+    const int i0 = blockIdx.x * (16 * MB), j0 = (blockIdx.y * kDenseWaves + wv) * (16 * NB);
     if (j0 >= cols) return;  // wave-uniform
-    const bool row_ok = i0 + r < rows;
-    const float *zr = dZ + static_cast<int64_t>(row_ok ? i0 + r : 0) * lddz;
-    const float *xr[NB];
-    bool x_ok[NB];
+    const float *zr[MB], *xr[NB];
+    bool z_ok[MB], x_ok[NB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const int i = i0 + 16 * m + r;
+        z_ok[m] = i < rows;
+        zr[m] = dZ + static_cast<int64_t>(z_ok[m] ? i : 0) * lddz;
+    }
 #pragma unroll
     for (int t = 0; t < NB; ++t) {
         const int j = j0 + 16 * t + r;
@@ -222,38 +238,46 @@ __global__ __launch_bounds__(kDenseBlock) void dense_nt_kernel(const float *__re
         }
         return v;
     };
-    v4f acc[NB];
+    v4f acc[MB][NB];
 #pragma unroll
-    for (int t = 0; t < NB; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int t = 0; t < NB; ++t) acc[m][t] = v4f{0.f, 0.f, 0.f, 0.f};
     constexpr int kDepth = 4;  // chunks of 16 columns of the batch whose loads are in flight together
     for (int kb = 0; kb < batch; kb += 16 * kDepth) {
-        float4 z4[kDepth], x4[kDepth][NB];
+        float4 z4[kDepth][MB], x4[kDepth][NB];
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
             const int c = kb + 16 * d + q * 4;
-            z4[d] = masked(zr, c, row_ok);
+#pragma unroll
+            for (int m = 0; m < MB; ++m) z4[d][m] = masked(zr[m], c, z_ok[m]);
 #pragma unroll
             for (int t = 0; t < NB; ++t) x4[d][t] = masked(xr[t], c, x_ok[t]);
         }
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
             if (kb + 16 * d >= batch) break;  // wave-uniform
-            const float zv[4] = {z4[d].x, z4[d].y, z4[d].z, z4[d].w};
 #pragma unroll
-            for (int t = 0; t < NB; ++t) {
-                const float xv[4] = {x4[d][t].x, x4[d][t].y, x4[d][t].z, x4[d][t].w};
+            for (int m = 0; m < MB; ++m) {
+                const float zv[4] = {z4[d][m].x, z4[d][m].y, z4[d][m].z, z4[d][m].w};
 #pragma unroll
-                for (int s = 0; s < 4; ++s) acc[t] = mfma(zv[s], xv[s], acc[t]);
+                for (int t = 0; t < NB; ++t) {
+                    const float xv[4] = {x4[d][t].x, x4[d][t].y, x4[d][t].z, x4[d][t].w};
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) acc[m][t] = mfma(zv[s], xv[s], acc[m][t]);
+                }
             }
         }
     }
 #pragma unroll
-    for (int t = 0; t < NB; ++t)
+    for (int m = 0; m < MB; ++m)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int i = i0 + 4 * q + g, j = j0 + 16 * t + r;
-            if (i < rows && j < cols) G[static_cast<int64_t>(i) * ldg + j] = acc[t][g];
-        }
+        for (int t = 0; t < NB; ++t)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int i = i0 + 16 * m + 4 * q + g, j = j0 + 16 * t + r;
+                if (i < rows && j < cols) G[static_cast<int64_t>(i) * ldg + j] = acc[m][t][g];
+            }
 }
 
 __device__ __forceinline__ void momentum_step(float &w, float &v, float g, float lr, float mu, int nesterov)
@@ -350,9 +374,12 @@ hipError_t launch_dense_product(const DenseArgs &a, hipStream_t s)
         const int64_t mt = (a.rows + 15) / 16;
         const int nb = dense_nb(mt, a.batch);
         const dim3 grid(static_cast<unsigned>(mt), (a.batch + 16 * nb - 1) / (16 * nb));
-        if (nb == 4) hipLaunchKernelGGL(dense_nn_kernel<4>, grid, dim3(kSplitBlock), 0, s, a);
-        else if (nb == 2) hipLaunchKernelGGL(dense_nn_kernel<2>, grid, dim3(kSplitBlock), 0, s, a);
-        else hipLaunchKernelGGL(dense_nn_kernel<1>, grid, dim3(kSplitBlock), 0, s, a);
+        const bool vec = a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0;
+        if (nb == 4 && vec) hipLaunchKernelGGL((dense_nn_kernel<4, true>), grid, dim3(kSplitBlock), 0, s, a);
+        else if (nb == 4) hipLaunchKernelGGL((dense_nn_kernel<4, false>), grid, dim3(kSplitBlock), 0, s, a);
+        else if (nb == 2 && vec) hipLaunchKernelGGL((dense_nn_kernel<2, true>), grid, dim3(kSplitBlock), 0, s, a);
+        else if (nb == 2) hipLaunchKernelGGL((dense_nn_kernel<2, false>), grid, dim3(kSplitBlock), 0, s, a);
+        else hipLaunchKernelGGL((dense_nn_kernel<1, false>), grid, dim3(kSplitBlock), 0, s, a);
     } else {
         // (one tile column per work-group: the 16 slices of 4 x 4 registers already take 64 KiB of LDS)
         const dim3 grid(static_cast<unsigned>((a.cols + 63) / 64), (a.batch + 15) / 16);
@@ -364,9 +391,9 @@ hipError_t launch_dense_product(const DenseArgs &a, hipStream_t s)
 hipError_t launch_dense_sddmm_update(const DenseUpdateArgs &a, const float *X, int64_t ldx, hipStream_t s)
 {
     if (a.rows <= 0 || a.cols <= 0 || a.batch <= 0) return hipSuccess;
-    constexpr int NB = 2;
-    const dim3 grid((a.rows + 15) / 16, (a.cols + kDenseWaves * 16 * NB - 1) / (kDenseWaves * 16 * NB));
-    hipLaunchKernelGGL(dense_nt_kernel<NB>, grid, dim3(kDenseBlock), 0, s, a.dZ, a.lddz, X, ldx, a.G, a.ldg, a.rows, a.cols, a.batch);
+    constexpr int MB = 2, NB = 2;
+    const dim3 grid((a.rows + 16 * MB - 1) / (16 * MB), (a.cols + kDenseWaves * 16 * NB - 1) / (kDenseWaves * 16 * NB));
+    hipLaunchKernelGGL((dense_nt_kernel<MB, NB>), grid, dim3(kDenseBlock), 0, s, a.dZ, a.lddz, X, ldx, a.G, a.ldg, a.rows, a.cols, a.batch);
     hipLaunchKernelGGL(dense_update_kernel, dim3(a.rows < 16384 ? a.rows : 16384), dim3(kDenseBlock), 0, s, a);
     return hipGetLastError();
 }
