@@ -531,7 +531,12 @@ HostPlan make_plan(int32_t rows, const int32_t *indptr_host, const RowsByLength 
     if (!staged_partial) H = plan_staged(rows, other_rows, indptr_host, by_len, max_batch);
     RowPlan Q, Z;
     if (n_short > 0) Q = plan_rows(rows, indptr_host, by_len, kPackMaxLen);
-    if (staged_partial) Z = plan_rows(rows, indptr_host, by_len, -1, kPackMaxLen);  // the short rows' partition for the SDDMM
+    // the short rows' partition: for the SDDMM beside a partial staged plan, and for the launches that serve the
+    // long rows inside column tiles and the short ones outside (operands beyond the L2s)
+    if (n_short > 0 && n_short < rows) Z = plan_rows(rows, indptr_host, by_len, -1, kPackMaxLen);
+    int64_t long_nnz = 0;
+    for (int32_t r = 0; r < rows; ++r)
+        if (indptr_host[r + 1] - indptr_host[r] > kPackMaxLen) long_nnz += indptr_host[r + 1] - indptr_host[r];
     // 16-byte records first so that they stay 16-byte aligned
     std::vector<int32_t> &st = hp.staging;
     st.reserve(P.blocks.size() + P.huge_rows.size() + P.waves.size() + H.rows.size() + Q.waves.size() + Z.waves.size() +
@@ -561,6 +566,7 @@ HostPlan make_plan(int32_t rows, const int32_t *indptr_host, const RowsByLength 
     v.staged_longest_row = longest_row;
     v.staged_partial = staged_partial;
     v.n_rest_blocks = Z.n_blocks();
+    v.long_nnz = static_cast<int32_t>(long_nnz);
     v.staged_row_count = H.n_rows;
     v.staged_nnz = static_cast<int32_t>(H.nnz);
     return hp;

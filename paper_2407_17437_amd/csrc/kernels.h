@@ -53,8 +53,9 @@ struct RowBlocks {
     int32_t staged_partial;        // the plan covers the rows of more than kPackMaxLen entries only: the others are
                                    // short_rows and take the packed kernel
     int32_t staged_row_count;      // rows the plan covers
-    const int4 *rest_waves;        // with staged_partial: partition of the rows it leaves out, records as in `waves`
-    int32_t n_rest_blocks;         //   (the SDDMM's; the products serve those rows through short_rows)
+    const int4 *rest_waves;        // where there are both short and longer rows: partition of the rows of at most kPackMaxLen
+    int32_t n_rest_blocks;         //   entries alone, records as in `waves` (no huge rows among them)
+    int32_t long_nnz;              // stored entries of the rows beyond kPackMaxLen (those of long_waves)
     int32_t staged_nnz;            // and their stored entries
     int32_t staged_preferred;      // measurement aid: take the staged kernels wherever they can run
 };

@@ -2099,6 +2099,8 @@ hipError_t spmm_tiled_go(const SpmmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+constexpr int64_t kMaxGridIds = (1ll << 31) - 1;
+
 // Work-groups of the packed launch for lane groups of gs lanes: those that serve the short rows, and
 // the launch's grid size (tiles rounded up to whole rounds of the 8 XCDs when the ids are decoded
 // XCD-first).  One place, so that the launch and the checks that the grid fits agree.
@@ -2118,8 +2120,6 @@ PackedGrid packed_grid(const SpmmArgs &a, int gs, bool with_long_rows)
     g.ids = (g.spread ? static_cast<int64_t>((g.n_tiles + 7) / 8) * 8 : g.n_tiles) * nrb;
     return g;
 }
-constexpr int64_t kMaxGridIds = (1ll << 31) - 1;
-
 template <int GS>
 hipError_t spmm_packed_go(const SpmmArgs &a, hipStream_t s)
 {
@@ -2186,6 +2186,29 @@ bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch, int32_t
 
 int spmm_tile_group(const SpmmArgs &a);
 bool spmm_offsets_ok(const SpmmArgs &a);
+constexpr int64_t kSplitMinOperand = 48ll << 20;  // operand bytes from which long rows go into column tiles of their own: beyond the eight L2s
+
+// Lanes per row (4 columns each) of the column tiles in which the LONG rows of a matrix run while its short rows run
+// untiled: for an operand that the L2s together cannot hold, gathered about evenly, on a matrix whose long rows
+// (beyond kPackMaxLen entries; they have a partition of their own) hold most of the stored entries.  0: no split.
+int spmm_split_group(const SpmmArgs &a)
+{
+    if (a.blocks.n_long_blocks <= 0 || a.blocks.n_rest_blocks <= 0 || a.batch < 128) return 0;
+    if (static_cast<int64_t>(a.x_rows) * a.batch * 4 < kSplitMinOperand || a.blocks.hot_share >= 0.5f) return 0;
+    if (static_cast<int64_t>(a.blocks.long_nnz) * 2 < a.nnz) return 0;
+    const int64_t budget = (a.XM ? 5 : 10) * (1 << 18), row_bytes = static_cast<int64_t>(a.x_rows) * 4;
+    // 64-column tiles as long as a tile of the operand fits an L2 at all (measured on a 16384-row operand at 1024
+    // columns: 137 us with 64-column tiles, 150 with 128, 174 with 32 -- a pass over the long rows per tile
+    // costs more than the misses of a tile that fills the L2 -- and 173 us unsplit)
+    int g = 0;
+    if (row_bytes * 128 <= budget) g = 32;
+    else if (row_bytes * 64 <= (a.XM ? (2ll << 20) : (4ll << 20))) g = 16;
+    else if (row_bytes * 32 <= budget) g = 8;
+    if (g == 0) return 0;
+    const int64_t n_tiles = (a.batch + g * 4 - 1) / (g * 4);
+    if ((n_tiles + 8) * a.blocks.n_long_blocks > kMaxGridIds) return 0;
+    return g;
+}
 
 bool spmm_staged_ok(const SpmmArgs &a)
 {
@@ -2439,6 +2462,28 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
     if (spmm_vec_ok(a)) {
         if (spmm_offsets_ok(a)) {
             const int tg = spmm_tile_group(a);
+            const int sg = tg == 0 ? spmm_split_group(a) : 0;
+            if (sg != 0) {
+                // Long rows inside column tiles (their gathers are most of the traffic and then hit in the L2s),
+                // short rows outside (a pass over them per tile would cost more than their gathers): two launches.
+                SpmmArgs longs = a, rest = a;
+                longs.blocks.waves = a.blocks.long_waves;
+                longs.blocks.n_blocks = a.blocks.n_long_blocks;
+                longs.blocks.n_short = 0;
+                rest.blocks.waves = a.blocks.rest_waves;
+                rest.blocks.n_blocks = a.blocks.n_rest_blocks;
+                rest.blocks.n_huge_rows = 0;
+                rest.blocks.n_short = 0;
+                rest.blocks.n_long_blocks = 0;   // (nothing left to split off)
+                rest.blocks.staged_rows = nullptr;
+                const hipError_t e = launch_spmm(rest, s);
+                if (e != hipSuccess) return e;
+                switch (sg) {
+                    case 32: return spmm_tiled_go<32>(longs, s);
+                    case 16: return spmm_tiled_go<16>(longs, s);
+                    default: return spmm_tiled_go<8>(longs, s);
+                }
+            }
             if (a.blocks.n_short > 0 && tg != 0 && packed_grid(a, tg, true).ids <= kMaxGridIds) {
                 switch (tg) {
                     case 32: return spmm_packed_go<32>(a, s);
