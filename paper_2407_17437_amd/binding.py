@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libnerva_sparse.so")
+LIB_PATH = os.environ.get("NERVA_SPARSE_LIB") or os.path.join(_PKG, "libnerva_sparse.so")   # (the variable: another build of the same library, for A/B timings)
 
 NERVA_OK = 0
 NERVA_ERR_ARGUMENT, NERVA_ERR_SHAPE, NERVA_ERR_CSR, NERVA_ERR_WORKSPACE, NERVA_ERR_HIP = -1, -2, -3, -4, -5

@@ -1562,7 +1562,8 @@ __global__ __launch_bounds__(kEwBlock) void sddmm_finish_kernel(const SddmmArgs 
 // output X is).  The per-tile partial products, in mirror order, are added in tile order by
 // backward_finish_kernel, which applies the momentum step through perm (mirror -> CSR position)
 // and also forms the bias gradient (row sums of dZ).  Every mirror row must be short (packed).
-constexpr int kBwdWaves = 8;  // waves per work-group (no sums across waves: smaller groups schedule finer)
+constexpr int kBwdWaves = 4;  // waves per work-group: no sums across waves, and smaller groups schedule finer (measured on the wide MLP:
+                              // 134 / 138 / 142 us with 4 / 8 / 16 waves; gather depth 4 instead of 8 and a register cap of 64 change nothing)
 
 template <int U, int GS>
 __device__ __forceinline__ void bwd_pass(gmem_ptr Zg, int src, int my_ro, float my_w, uint32_t off, const float4 &ax, int it0, int lig,

@@ -213,6 +213,74 @@ def test_mirror_is_the_transposed_pattern_bit_exact(nb, torch_mod, rows, cols, d
     L.close()
 
 
+def _mirror_check(nb, torch, rows, cols, indptr, indices):
+    nnz = int(indptr[-1])
+    lay = wl.SparseLayerData(rows, cols, np.asarray(indptr, np.int32), np.asarray(indices, np.int32),
+                             np.arange(1, nnz + 1, dtype=np.float32), np.zeros(rows, np.float32), False)
+    L = nb.SparseLinear(lay, max_batch=64)
+    ip_t, ix_t, v_t, perm = nb.sparse_linear_mirror(L.handle)
+    row_of = np.repeat(np.arange(rows, dtype=np.int32), np.diff(lay.indptr))
+    order = np.argsort(lay.indices, kind="stable")
+    exp_indptr = np.zeros(cols + 1, dtype=np.int32)
+    np.cumsum(np.bincount(lay.indices, minlength=cols), out=exp_indptr[1:])
+    assert np.array_equal(raw_i32(nb, torch, ip_t, cols + 1), exp_indptr)
+    assert np.array_equal(raw_i32(nb, torch, ix_t, nnz), row_of[order])
+    assert np.array_equal(raw_i32(nb, torch, perm, nnz), order.astype(np.int32))
+    assert np.array_equal(raw_f32(nb, torch, v_t, nnz), lay.values[order])
+    L.close()
+
+
+def test_mirror_build_on_awkward_patterns(nb, torch_mod):
+    """The mirror is built on the device by a counting sort over row tiles: patterns that stress it -- every row
+    in one column (all tiles meet in one counter column), one row holding every column, rows far longer than a tile's
+    share next to thousands of rows with one entry, trailing and leading empty rows, a power-law matrix of 300 k
+    entries cut into hundreds of tiles -- each compared bit for bit with a stable sort by column."""
+    torch = torch_mod
+    rows, cols = 5000, 37
+    _mirror_check(nb, torch, rows, cols, np.arange(rows + 1), np.full(rows, 11))                       # one column
+    _mirror_check(nb, torch, 3, 9000, [0, 0, 9000, 9000], np.arange(9000))                            # one full row, two empty
+    lens = np.ones(6000, dtype=np.int64); lens[[5, 3000, 5999]] = 4000; lens[:3] = 0; lens[-2:] = [0, 4000][::-1]
+    ip, ix = wl.pattern_from_row_nnz(lens, 4000, seed=3)
+    _mirror_check(nb, torch, 6000, 4000, ip, ix)
+    z = wl.make_zipf_matrix(4096, 0.02, seed=7)
+    _mirror_check(nb, torch, 4096, 4096, z.indptr, z.indices)
+    _mirror_check(nb, torch, 40, 30, np.zeros(41, np.int32), np.zeros(0, np.int32))                    # empty
+
+
+def test_invalid_patterns_are_rejected_by_the_device_side_check(nb, torch_mod):
+    """Every way a pattern can fail to be canonical CSR, found by the kernels that check it where it lives; nothing
+    outside the arrays is read (the row pointers are checked before they are used as positions)."""
+    torch = torch_mod
+    lay = layer_case(40, 30, 0.3, seed=6)
+    rows, cols, nnz = 40, 30, lay.nnz
+
+    def rejected(indptr, indices, word):
+        bad = wl.SparseLayerData(rows, cols, np.asarray(indptr, np.int32), np.asarray(indices, np.int32), lay.values, lay.bias, False)
+        with pytest.raises(nb.NervaError) as e:
+            nb.SparseLinear(bad)
+        assert e.value.code == nb.NERVA_ERR_CSR and word in str(e.value), str(e.value)
+
+    ip = lay.indptr.copy(); ip[0] = 1
+    rejected(ip, lay.indices, "indptr[0]")
+    ip = lay.indptr.copy(); ip[7], ip[8] = ip[8] + 1, ip[7]
+    rejected(ip, lay.indices, "decreases")
+    ip = lay.indptr.copy(); ip[20] = 10 ** 9                         # far beyond nnz: must not be used as a position
+    rejected(ip, lay.indices, "indptr")
+    ip = lay.indptr.copy(); ip[20] = -5
+    rejected(ip, lay.indices, "indptr")
+    ix = lay.indices.copy(); ix[17] = cols
+    rejected(lay.indptr, ix, "out of range")
+    ix = lay.indices.copy(); ix[17] = -1
+    rejected(lay.indptr, ix, "out of range")
+    row = int(np.argmax(np.diff(lay.indptr) >= 2)); p = int(lay.indptr[row])
+    ix = lay.indices.copy(); ix[p + 1] = ix[p]
+    rejected(lay.indptr, ix, "ascending")
+    ix = lay.indices.copy(); ix[p], ix[p + 1] = ix[p + 1], ix[p]
+    rejected(lay.indptr, ix, "ascending")
+    L = nb.SparseLinear(lay)                                         # the untouched pattern is accepted
+    L.close()
+
+
 def test_invalid_pattern_is_rejected_on_create(nb, torch_mod):
     torch = torch_mod
     lay = layer_case(16, 16, 0.3, seed=3)
