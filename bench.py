@@ -32,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+DENSE_FROM_DENSITY = 0.4  # the library's own threshold for the dense route (kDenseFromDensity)
 
 WORKLOADS = {
     # name: (sizes, sparsity | None, er_density | None, batch, pool batches, description)
@@ -381,12 +382,23 @@ def main() -> int:
         pts = []
         for s in SWEEP:
             r = measure_mlp(env, f"sweep{s}", Ks, Ws, 0, args, copy_gbs)
-            pts.append({"sparsity": s, "nnz": sum(r["layer_nnz"]), "us_per_step": round(r["ms_per_step"] * 1e3, 3),
-                        "samples_per_s": round(r["samples_per_s"], 1)})
-        a, b, r2 = fit_line([p["nnz"] / 1e6 for p in pts], [p["us_per_step"] for p in pts])
+            pt = {"sparsity": s, "nnz": sum(r["layer_nnz"]), "us_per_step": round(r["ms_per_step"] * 1e3, 3),
+                  "samples_per_s": round(r["samples_per_s"], 1), "route": "sparse"}
+            if 1.0 - s >= DENSE_FROM_DENSITY and args.dense_from_density is None:
+                # the library put the large layers on the dense route by itself: the sparse route on the same network too
+                pt["route"] = "dense products and dense gradient (the library's choice at this density)"
+                nb.nerva_set_dense_threshold(2.0)
+                try:
+                    r2_ = measure_mlp(env, f"sweep{s}", Ks, Ws, 0, args, copy_gbs)
+                finally:
+                    nb.nerva_set_dense_threshold(DENSE_FROM_DENSITY)
+                pt["us_per_step_sparse_route"] = round(r2_["ms_per_step"] * 1e3, 3)
+            pts.append(pt)
+        sparse_us = [p.get("us_per_step_sparse_route", p["us_per_step"]) for p in pts]
+        a, b, r2 = fit_line([p["nnz"] / 1e6 for p in pts], sparse_us)
         extras["sweep"] = {"workload": "MLP 3072-1024-512-10, batch 100, per-layer sparsity 50 ... 99.9 %",
                            "steps": Ks, "warmup": Ws, "points": pts,
-                           "fit": {"model": "us_per_step = a + b * (stored entries / 1e6)", "a_us": round(a, 3),
+                           "fit": {"model": "us_per_step on the sparse route = a + b * (stored entries / 1e6)", "a_us": round(a, 3),
                                    "b_us_per_million_entries": round(b, 3), "r2": round(r2, 5)}}
         # the three kernels alone on 16384 x 16384 power-law matrices
         from paper_2407_17437_amd import kernel_bench

@@ -44,48 +44,60 @@ __device__ __forceinline__ void dense_epilogue(const DenseArgs &a, int row, int 
 // before the first of their MFMA steps: these products are short, and their time is load latency.
 constexpr int kSplitWaves = 16;
 constexpr int kSplitBlock = kSplitWaves * kWave;
-constexpr int kNnDepth = 4;
+constexpr int kNnDepth = 2;
 
 // VECX: the NB columns of a lane are consecutive (tile t holds the columns n0 + NB * r + t), so that one
 // 8- or 16-byte load along the batch feeds the NB tiles; needs X 16-byte aligned with ldx a multiple of 4.
-template <int NB, bool VECX>
-__device__ __forceinline__ void nn_chunks(const DenseArgs &a, const float *wrow, bool row_ok, const int64_t (&xcol)[NB],
-                                          const bool (&col_ok)[NB], int q, int c0, int n_chunks, v4f (&acc)[NB])
-{
-    const int K = a.cols;
+// A batch of kNnDepth chunks: its loads (nn_load) are issued while the MFMA steps of the batch before (nn_mfma)
+// run -- the waves of a work-group start together and would otherwise all load, then all multiply.
+template <int NB>
+struct NnBatch {
     float4 w4[kNnDepth];
     float b[kNnDepth][4][NB];
+};
+
+template <int NB, bool VECX>
+__device__ __forceinline__ void nn_load(const DenseArgs &a, const float *wrow, const int64_t (&xcol)[NB], int q, int c0, int n_chunks,
+                                        NnBatch<NB> &B)
+{
+    const int K = a.cols;
 #pragma unroll
     for (int d = 0; d < kNnDepth; ++d) {
         const int kb = (c0 + (d < n_chunks ? d : 0)) * 16;   // (chunks past the end repeat the first one and are not used)
-        w4[d] = ld4(wrow + kb);
+        B.w4[d] = ld4(wrow + kb);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int k = kb + q * 4 + s;
             const float *xr = a.X + static_cast<int64_t>(k < K ? k : 0) * a.ldx;
             if constexpr (VECX && NB == 4) {
                 const float4 x = ld4(xr + xcol[0]);
-                b[d][s][0] = x.x; b[d][s][1] = x.y; b[d][s][2] = x.z; b[d][s][3] = x.w;
+                B.b[d][s][0] = x.x; B.b[d][s][1] = x.y; B.b[d][s][2] = x.z; B.b[d][s][3] = x.w;
             } else if constexpr (VECX && NB == 2) {
                 const float2 x = *reinterpret_cast<const float2 *>(xr + xcol[0]);
-                b[d][s][0] = x.x; b[d][s][1] = x.y;
+                B.b[d][s][0] = x.x; B.b[d][s][1] = x.y;
             } else {
 #pragma unroll
-                for (int t = 0; t < NB; ++t) b[d][s][t] = xr[xcol[t]];
+                for (int t = 0; t < NB; ++t) B.b[d][s][t] = xr[xcol[t]];
             }
         }
     }
+}
+
+template <int NB>
+__device__ __forceinline__ void nn_mfma(int K, bool row_ok, const bool (&col_ok)[NB], int q, int c0, int n_chunks, const NnBatch<NB> &B,
+                                        v4f (&acc)[NB])
+{
 #pragma unroll
     for (int d = 0; d < kNnDepth; ++d) {
         if (d >= n_chunks) break;  // wave-uniform
         const int kb = (c0 + d) * 16;
-        const float wv4[4] = {w4[d].x, w4[d].y, w4[d].z, w4[d].w};
+        const float wv4[4] = {B.w4[d].x, B.w4[d].y, B.w4[d].z, B.w4[d].w};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const bool k_ok = kb + q * 4 + s < K;
 #pragma unroll
             for (int t = 0; t < NB; ++t)
-                acc[t] = mfma(row_ok ? wv4[s] : 0.f, (k_ok && col_ok[t]) ? b[d][s][t] : 0.f, acc[t]);
+                acc[t] = mfma(row_ok ? wv4[s] : 0.f, (k_ok && col_ok[t]) ? B.b[d][s][t] : 0.f, acc[t]);
         }
     }
 }
@@ -96,7 +108,13 @@ __global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a
     __shared__ float part[kSplitWaves][NB][4][kWave];
     const int lane = threadIdx.x & (kWave - 1), wv = wave_id();
     const int r = lane & 15, q = lane >> 4;
-    const int i0 = blockIdx.x * 16, n0 = blockIdx.y * (16 * NB);
+    // Work-group ids go round the 8 XCDs: the column tiles of one row tile get ids 8 apart, so that they run on one
+    // XCD and the rows of the copy they all read come out of its L2 after the first of them has fetched them.
+    const int n_col_tiles = (a.batch + 16 * NB - 1) / (16 * NB);
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int m_tile = (slot / n_col_tiles) * 8 + xcd;
+    if (m_tile * 16 >= a.rows) return;  // (the grid is padded to whole rounds of the XCDs)
+    const int i0 = m_tile * 16, n0 = (slot % n_col_tiles) * (16 * NB);
     const int K = a.cols;
     const int row = i0 + r;
     const bool row_ok = row < a.rows;
@@ -117,7 +135,15 @@ __global__ __launch_bounds__(kSplitBlock) void dense_nn_kernel(const DenseArgs a
     v4f acc[NB];
 #pragma unroll
     for (int t = 0; t < NB; ++t) acc[t] = v4f{0.f, 0.f, 0.f, 0.f};
-    for (int c = c_begin; c < c_end; c += kNnDepth) nn_chunks<NB, VECX>(a, wrow, row_ok, xcol, col_ok, q, c, min(kNnDepth, c_end - c), acc);
+    NnBatch<NB> B0, B1;
+    if (c_begin < c_end) nn_load<NB, VECX>(a, wrow, xcol, q, c_begin, min(kNnDepth, c_end - c_begin), B0);
+    for (int c = c_begin; c < c_end; c += 2 * kNnDepth) {
+        const int c1 = c + kNnDepth, c2 = c + 2 * kNnDepth;
+        if (c1 < c_end) nn_load<NB, VECX>(a, wrow, xcol, q, c1, min(kNnDepth, c_end - c1), B1);
+        nn_mfma<NB>(K, row_ok, col_ok, q, c, min(kNnDepth, c_end - c), B0, acc);
+        if (c2 < c_end) nn_load<NB, VECX>(a, wrow, xcol, q, c2, min(kNnDepth, c_end - c2), B0);
+        if (c1 < c_end) nn_mfma<NB>(K, row_ok, col_ok, q, c1, min(kNnDepth, c_end - c1), B1, acc);
+    }
 #pragma unroll
     for (int t = 0; t < NB; ++t)
 #pragma unroll
@@ -373,7 +399,7 @@ hipError_t launch_dense_product(const DenseArgs &a, hipStream_t s)
     if (!a.trans) {
         const int64_t mt = (a.rows + 15) / 16;
         const int nb = dense_nb(mt, a.batch);
-        const dim3 grid(static_cast<unsigned>(mt), (a.batch + 16 * nb - 1) / (16 * nb));
+        const dim3 grid(static_cast<unsigned>((mt + 7) / 8 * 8 * ((a.batch + 16 * nb - 1) / (16 * nb))));
         const bool vec = a.ldx % 4 == 0 && (reinterpret_cast<uintptr_t>(a.X) & 15u) == 0;
         if (nb == 4 && vec) hipLaunchKernelGGL((dense_nn_kernel<4, true>), grid, dim3(kSplitBlock), 0, s, a);
         else if (nb == 4) hipLaunchKernelGGL((dense_nn_kernel<4, false>), grid, dim3(kSplitBlock), 0, s, a);
