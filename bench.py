@@ -85,6 +85,20 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
     return 0.0
 
 
+GATHER_PEAK_TBS = 256 * 64 * 2.4e9 / 1e12   # 256 compute units x 64 bytes per clock through the texture-address path at 2.4 GHz
+
+
+def slot_gather_bytes(name: str, layer, batch: int) -> float:
+    """Bytes a launch gathers out of the caches: one row of the dense operand (batch floats) per stored entry.  The
+    fused backward pass gathers a row once for its two products; the dense route gathers nothing."""
+    kind = name.split("[")[0]
+    if kind in ("spmm_forward", "spmm_transposed", "sddmm_update", "sddmm", "backward_fused"):
+        return 4.0 * layer.nnz * batch
+    if kind == "spmm_forward+softmax_ce+spmm_transposed":
+        return 8.0 * layer.nnz * batch
+    return 0.0
+
+
 def csrc_digest() -> str:
     """Digest of the kernel sources: what a stored counter reading must have been taken with to count."""
     h = hashlib.sha256()
@@ -203,9 +217,13 @@ def measure_mlp(env, name: str, K: int, W: int, profile_steps: int, args, copy_g
             byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
             if len(kinds) == 2:
                 byt += slot_bytes(kinds[1], M.layers[l + 1], batch, has_mirror_scatter=True)
+            gat = slot_gather_bytes(kinds[0], M.layers[l], batch)
+            if len(kinds) == 2:
+                gat += slot_gather_bytes(kinds[1], M.layers[l + 1], batch)
             us = ms * 1e3 / max(steps_done, 1)
             kernels.append({"kernel": slot, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),
-                            "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None})
+                            "gbs": round(byt / (us * 1e-6) / 1e9, 1) if us > 0 else None,
+                            "gather_bytes": int(gat), "gather_tbs": round(gat / (us * 1e-6) / 1e12, 2) if us > 0 else None})
         dom = max(kernels, key=lambda r: r["avg_us"])
         plain = not graphs and not args.unfused and not args.separate_head and args.dense_from_density is None and not args.prefer_staged
         traffic, source = stored_traffic(name, dom["kernel"]) if plain else (None, "not the default launch configuration")
@@ -213,6 +231,10 @@ def measure_mlp(env, name: str, K: int, W: int, profile_steps: int, args, copy_g
                     "unit": "GB/s", "frac": round(dom["gbs"] / HBM_PEAK_GBS, 5), "avg_us": dom["avg_us"],
                     "algorithmic_bytes": dom["algorithmic_bytes"], "traffic": traffic, "traffic_source": source,
                     "copy_kernel_gbs": round(copy_gbs, 1), "frac_of_copy_kernel": round(dom["gbs"] / copy_gbs, 5),
+                    "gather": {"what": "rows of the dense operand fetched once per stored entry, served by the L2s: the stream that "
+                                       "bounds this kernel (texture-address units about 70 % busy in the counter tables under profiles/)",
+                               "bytes": dom["gather_bytes"], "tbs": dom["gather_tbs"], "path_peak_tbs": round(GATHER_PEAK_TBS, 1),
+                               "frac_of_path_peak": round((dom["gather_tbs"] or 0.0) / GATHER_PEAK_TBS, 4)},
                     "step_algorithmic_bytes": int(sum(r["algorithmic_bytes"] for r in kernels)),
                     "step_frac": round(sum(r["algorithmic_bytes"] for r in kernels) / (sec / K) / 1e9 / HBM_PEAK_GBS, 5),
                     "timing": f"HIP events between the launches of a step on the step's stream, {steps_done} steps"}
@@ -292,6 +314,31 @@ def inference(args, env) -> int:
                       "cpu_baseline": cpu}))
     M.close()
     return 0
+
+
+def rebind_times(env):
+    """Wall time of sparse_linear_rebind (the C call with its synchronisations; pattern already in device memory):
+    validation, mirror, position maps and partitions of a new pattern of the same shape."""
+    np, torch, nb, wl = env.np, env.torch, env.nb, env.wl
+    cases = [("1024 x 3072, 90 % sparsity", wl.make_mlp(wl.CIFAR_MLP, sparsity=0.9).layers[0], 100),
+             ("8192 x 8192, config 4's second layer", wl.make_mlp(wl.WIDE_MLP, er_density=0.01).layers[1], 1024),
+             ("16384 x 16384, 1 %, power-law rows", wl.make_zipf_matrix(16384, 0.01, seed=11), 1024)]
+    out = []
+    for label, lay, max_batch in cases:
+        L = nb.SparseLinear(lay, max_batch=max_batch)
+        ip, ix, v = (torch.as_tensor(a).cuda() for a in (lay.indptr, lay.indices, lay.values))
+        ts = []
+        for _ in range(5):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nb.sparse_linear_rebind(L.handle, lay.nnz, ip, ix, v)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        L.indptr, L.indices, L.values = ip, ix, v   # the layer reads the caller's arrays: keep them alive until it is closed
+        L.close()
+        out.append({"matrix": label, "nnz": int(lay.nnz), "ms_median": round(float(np.median(ts)) * 1e3, 3), "ms_min": round(min(ts) * 1e3, 3)})
+        log(f"rebind {label}: {out[-1]['ms_median']} ms")
+    return {"what": "sparse_linear_rebind, wall clock around the C call, 5 calls", "cases": out}
 
 
 def fit_line(x, y):
@@ -411,6 +458,7 @@ def main() -> int:
             "table": [{k: r[k] for k in ("kernel", "density", "batch", "nnz", "us_cold", "us_back_to_back", "algorithmic_MB",
                                          "gbs_cold", "frac_hbm_cold", "gbs_back_to_back", "frac_hbm_back_to_back",
                                          "tflops_back_to_back")} for r in rows]}
+        extras["rebind"] = rebind_times(env)
         extras["seconds"] = round(time.perf_counter() - t_extra, 1)
 
     out = {
