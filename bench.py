@@ -63,6 +63,8 @@ def slot_bytes(name: str, layer, batch: int, has_mirror_scatter: bool) -> float:
     if kind == "backward_fused":      # transposed product and SDDMM + update of one layer on one gather stream: mirror pattern,
         # values and position map, dZ in once, the layer's input in once (mask and second operand), dX out, the update
         return 12 * nnz + 4 * (k + 1) + 4 * n * m + 4 * n * k + 4 * n * k + 16 * nnz + 4 * nnz + 16 * m
+    if kind == "backward_full":       # the same for a full matrix of few rows, streamed: dZ in, the layer's input in once, dX out, the update
+        return 4 * n * m + 4 * n * k + 4 * n * k + 16 * nnz + 8 * nnz + 16 * m
     if kind == "sddmm":
         return 4 * nnz + 4 * (m + 1) + 4 * n * (m + k) + 4 * nnz + 4 * m
     if kind == "momentum_values":

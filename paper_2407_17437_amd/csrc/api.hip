@@ -1481,6 +1481,13 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
                 continue;
             }
             const SddmmArgs g_same = make_S(l);
+            if (full_backward_ok(t, g_same)) {
+                if (pending >= 0 && (rc = run_S_alone(pending)) != NERVA_OK) return rc;
+                pending = -1;
+                Timed tm(mlp->prof, s, "backward_full", l);
+                HIP_TRY(launch_full_backward(t, g_same, s));
+                continue;
+            }
             if (backward_fused_ok(t, g_same)) {
                 if (pending >= 0 && (rc = run_S_alone(pending)) != NERVA_OK) return rc;
                 pending = -1;

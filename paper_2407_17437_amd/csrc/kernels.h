@@ -190,6 +190,8 @@ struct BackwardArgs {
 };
 bool backward_fused_ok(const SpmmArgs &t, const SddmmArgs &g);
 hipError_t launch_backward_fused(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s);
+bool full_backward_ok(const SpmmArgs &t, const SddmmArgs &g);
+hipError_t launch_full_backward(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s);
 
 // Two independent launches in one grid (both on the 16-byte path, batch <= 1024, one column tile).
 bool can_pair(const SpmmArgs &a, const SddmmArgs &b);

@@ -1445,7 +1445,12 @@ __global__ __launch_bounds__(kStageWaves * kWave) void sddmm_staged_kernel(const
 // multiplies its columns of the X row with the same columns of every dZ row, the row's `rows`
 // products are summed over the wave by the transposing butterfly, and lane i stores (or applies the
 // momentum step to) entry (i, row of X).  The first work-group also sums the rows of dZ for db.
-__global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, const int n_chunks)
+// WITH_T: the layer's transposed product in the same pass -- row j of W^T is column j of the full matrix,
+// the very entries this wave updates, and its result is masked by the row of X the wave holds:
+//     dX[j, :] = (sum_i W(i, j) dZ[i, :]) * [X[j, :] > 0],  i ascending, the weights of the step's start
+// (read before the update; no other wave touches column j).  X is read once for both.
+template <bool WITH_T>
+__global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, const int n_chunks, float *__restrict__ dX, const int lddx)
 {
     extern __shared__ float4 dz_s[];  // [rows][n_chunks][kWave]
     const int lane = threadIdx.x & (kWave - 1);
@@ -1483,16 +1488,29 @@ __global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, c
 #pragma unroll
         for (int i = 0; i < 16; ++i) d[i] = 0.f;
         const float *xr = a.X + static_cast<int64_t>(j) * a.ldx;
+        float w_own = 0.f;  // lane i: W(i, j)
+        if constexpr (WITH_T)
+            if (lane < R) w_own = a.values[static_cast<int64_t>(lane) * K + j];
         for (int ch = 0; ch < n_chunks; ++ch) {
             const int col = (ch * kWave + lane) * 4;
             const float4 x = col < a.batch ? ld4(xr + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
             for (int i = 0; i < kFullMaxRows; ++i) {
                 if (i < R) {  // uniform
                     const float4 z = dz_s[(i * n_chunks + ch) * kWave + lane];
                     d[i] = fmaf(x.w, z.w, fmaf(x.z, z.z, fmaf(x.y, z.y, fmaf(x.x, z.x, d[i]))));
+                    if constexpr (WITH_T) {
+                        const float wi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_own), i));
+                        t.x = fmaf(wi, z.x, t.x);
+                        t.y = fmaf(wi, z.y, t.y);
+                        t.z = fmaf(wi, z.z, t.z);
+                        t.w = fmaf(wi, z.w, t.w);
+                    }
                 }
             }
+            if constexpr (WITH_T)
+                if (col < a.batch) st4(dX + static_cast<int64_t>(j) * lddx + col, keep_where_positive(t, x));  // (batch % 4 == 0)
         }
         // lane i of each row of 16 lanes gets that row's sum of product i; then the four rows: (0 + 1) + (2 + 3)
         float g = row16_transpose_sum(d, lane & 15);
@@ -1502,7 +1520,7 @@ __global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, c
             const int64_t p = static_cast<int64_t>(lane) * K + j;
             if (a.g) a.g[p] = g;
             if (a.fused) {
-                float w = a.values[p], v = a.velocity[p];
+                float w = WITH_T ? w_own : a.values[p], v = a.velocity[p];
                 momentum_step(w, v, g, a.lr, a.momentum, a.nesterov);
                 a.values[p] = w;
                 a.velocity[p] = v;
@@ -2385,6 +2403,25 @@ bool backward_fused_ok(const SpmmArgs &t, const SddmmArgs &g)
     return ((n_tiles + 7) / 8) * 8 * ((sets + kBwdWaves - 1) / kBwdWaves) <= kMaxGridIds;
 }
 
+// The same sharing for a full matrix of few rows (a saturated output layer): its SDDMM streams the layer's
+// input once, a wave per input row, and that row is also the mask of the transposed product's result row.
+bool full_backward_ok(const SpmmArgs &t, const SddmmArgs &g)
+{
+    if (!sddmm_full_ok(g) || !g.fused || g.ZM || !g.values || !g.velocity) return false;
+    if (t.batch != g.batch || t.XM || t.bias || t.relu || !t.YM || t.YM != g.X || t.ldym != g.ldx || t.X != g.dZ || t.ldx != g.lddz) return false;
+    if (t.rows != g.x_rows || t.x_rows != g.rows || t.nnz != g.nnz || !t.Y) return false;
+    return t.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(t.Y) & 15u) == 0;
+}
+
+hipError_t launch_full_backward(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s)
+{
+    const int n_chunks = (g.batch + 255) / 256;
+    const int groups = (g.x_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(full_sddmm_kernel<true>, dim3(groups < 1024 ? groups : 1024), dim3(kBlock),
+                       static_cast<size_t>(g.rows) * n_chunks * kWave * sizeof(float4), s, g, n_chunks, t.Y, static_cast<int>(t.ldy));
+    return hipGetLastError();
+}
+
 hipError_t launch_backward_fused(const SpmmArgs &t, const SddmmArgs &g, hipStream_t s)
 {
     BackwardArgs a{};
@@ -2530,8 +2567,8 @@ hipError_t launch_sddmm(const SddmmArgs &a, hipStream_t s)
     if (sddmm_full_ok(a)) {
         const int n_chunks = (a.batch + 255) / 256;
         const int groups = (a.x_rows + kWavesPerBlock - 1) / kWavesPerBlock;  // one row of X per wave, up to two rounds of work-groups
-        hipLaunchKernelGGL(full_sddmm_kernel, dim3(groups < 1024 ? groups : 1024), dim3(kBlock),
-                           static_cast<size_t>(a.rows) * n_chunks * kWave * sizeof(float4), s, a, n_chunks);
+        hipLaunchKernelGGL(full_sddmm_kernel<false>, dim3(groups < 1024 ? groups : 1024), dim3(kBlock),
+                           static_cast<size_t>(a.rows) * n_chunks * kWave * sizeof(float4), s, a, n_chunks, static_cast<float *>(nullptr), 0);
         return hipGetLastError();
     }
     if (sddmm_staged_ok(a)) {

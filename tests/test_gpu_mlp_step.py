@@ -445,3 +445,42 @@ def test_stage_parity_backward_on_one_gather_stream(nb, torch_mod, oracle, sizes
                 assert sum(n.startswith("backward_fused") for n in names) == len(sizes) - 3, names
         stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused)
     M.close()
+
+
+@pytest.mark.parametrize("batch,unfused", [(256, False), (192, False), (1024, False), (256, True)])
+def test_stage_parity_backward_of_a_saturated_output_layer(nb, torch_mod, oracle, batch, unfused):
+    """An output layer that stores every entry (Erdos-Renyi split of a small global density: the 10-row layer
+    saturates, as in the wide MLP) and is too large for the fused head: its transposed product, SDDMM and update run
+    as one streaming launch that reads the layer's input once (Section 4: A = S^T B and S = A B^T); every stage of
+    two steps against the oracle, and the same state, to rounding, as the pipeline of separate kernels."""
+    torch = torch_mod
+    sizes = (96, 1500, 1200, 10)
+    nnz = [int(0.05 * 1500 * 96), int(0.03 * 1200 * 1500), 10 * 1200]
+    mlp = wl.make_mlp(sizes, layer_nnz=nnz, bias_std=0.1, pattern_seed=140, value_seed=240)
+    assert mlp.layers[2].nnz == 10 * 1200
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 2, seed=340)
+    M = nb.MLP(mlp, batch, nb.NERVA_MLP_UNFUSED if unfused else 0)
+    nb.mlp_profile_enable(M.handle, 1)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        if t == 0:
+            names = [n for n, _ in nb.mlp_profile_read(M.handle)[1]]
+            nb.mlp_profile_enable(M.handle, 0)
+            assert ("backward_full[2]" in names) == (not unfused), names
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused)
+    if not unfused:
+        # the pipeline of separate kernels from the same start.  Its transposed product adds a row's terms in another
+        # order (lane groups first), so the two states agree to rounding, not bit for bit
+        mlp2 = wl.make_mlp(sizes, layer_nnz=nnz, bias_std=0.1, pattern_seed=140, value_seed=240)
+        M2 = nb.MLP(mlp2, batch, nb.NERVA_MLP_UNFUSED)
+        for t in range(2):
+            M2.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        for a, b in zip(M.layers, M2.layers):
+            for u, v in ((a.values, b.values), (a.velocity, b.velocity), (a.bias, b.bias)):
+                u, v = u.cpu().numpy(), v.cpu().numpy()
+                assert np.all(np.abs(u - v) <= 1e-5 * (np.abs(v) + 1e-2))
+        M2.close()
+    M.close()
