@@ -484,3 +484,49 @@ def test_stage_parity_backward_of_a_saturated_output_layer(nb, torch_mod, oracle
                 assert np.all(np.abs(u - v) <= 1e-5 * (np.abs(v) + 1e-2))
         M2.close()
     M.close()
+
+
+@pytest.mark.parametrize("static", [False, True])
+@pytest.mark.parametrize("sizes,kw,batch", [
+    ((3072, 1024, 512, 10), dict(sparsity=0.95), 100),                          # fused head, paired launches
+    ((96, 1500, 1200, 10), dict(layer_nnz=(7200, 54000, 12000)), 256),           # column tiles, partial buffers, streaming output layer
+])
+def test_training_steps_replayed_from_a_hip_graph(nb, torch_mod, sizes, kw, batch, static):
+    """A training step only enqueues kernels, so it can be captured: three steps (three batches) recorded into one HIP
+    graph, replayed three times with eager work of the same process and synchronisations in between; after every
+    replay the weights, momentum buffers and the loss equal, bit for bit, those of a twin trained by plain launches."""
+    torch = torch_mod
+    lr, mu = 0.05, 0.9
+    mlp = wl.make_mlp(sizes, pattern_seed=150, value_seed=250, bias_std=0.1, **kw)
+    G = nb.MLP(mlp, batch); E = nb.MLP(mlp, batch)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 3, seed=350)
+    Xd = [nb.to_dense(x) for x in Xs]; Td = [torch.as_tensor(t).cuda() for t in Ts]
+    loss_g = torch.zeros(1, device="cuda")
+
+    def step(M, k, loss):
+        if static:
+            nb.mlp_train_step_static(M.handle, Xd[k], Xd[k].stride(0), Td[k], batch, lr, mu, loss)
+        else:
+            nb.mlp_train_step(M.handle, Xd[k], Xd[k].stride(0), Td[k], batch, lr, mu, M.workspace, loss)
+
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for k in range(3):
+            step(G, k, loss_g)
+    # (capture has run nothing: both twins are still at the start)
+    other = torch.zeros(1 << 20, device="cuda")
+    for r in range(3):
+        g.replay()
+        other.add_(1.0)                                   # eager work of the process between the replays
+        for k in range(3):
+            step(E, k, E.loss)
+        torch.cuda.synchronize()
+        assert float(other.sum().item()) == (r + 1) * other.numel()
+        for a, b in zip(G.layers, E.layers):
+            assert torch.equal(a.values, b.values) and torch.equal(a.velocity, b.velocity), f"replay {r}"
+            assert torch.equal(a.bias, b.bias) and torch.equal(a.bias_velocity, b.bias_velocity), f"replay {r}"
+        assert float(loss_g.item()) == float(E.loss.item()) and np.isfinite(float(loss_g.item()))
+    del g
+    G.close(); E.close()
