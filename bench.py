@@ -217,10 +217,11 @@ def measure_mlp(env, name: str, K: int, W: int, profile_steps: int, args, copy_g
             if len(kinds) == 3:
                 kinds = ["+".join(kinds)]
             byt = slot_bytes(kinds[0], M.layers[l], batch, has_mirror_scatter=(l > 0))
-            if len(kinds) == 2:
-                byt += slot_bytes(kinds[1], M.layers[l + 1], batch, has_mirror_scatter=True)
             gat = slot_gather_bytes(kinds[0], M.layers[l], batch)
-            if len(kinds) == 2:
+            if len(kinds) == 2 and kinds[1] == "softmax_ce":      # the loss gradient formed by the product's finish pass: same layer
+                byt += slot_bytes(kinds[1], M.layers[l], batch, has_mirror_scatter=False)
+            elif len(kinds) == 2:
+                byt += slot_bytes(kinds[1], M.layers[l + 1], batch, has_mirror_scatter=True)
                 gat += slot_gather_bytes(kinds[1], M.layers[l + 1], batch)
             us = ms * 1e3 / max(steps_done, 1)
             kernels.append({"kernel": slot, "avg_us": round(us, 3), "algorithmic_bytes": int(byt),

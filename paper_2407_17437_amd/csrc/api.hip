@@ -1181,7 +1181,7 @@ int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers, fl
     m->flags = flags;
     const nerva_layer *last = layers[n_layers - 1];
     m->head = n_layers >= 2 && !(flags & NERVA_MLP_SEPARATE_HEAD) && head_ok(last->rows, last->cols, last->nnz);
-    if (m->head) {
+    if (m->head || (n_layers >= 2 && last->full && last->rows <= kFullMaxRows)) {   // per-column losses between two launches of a step
         const size_t bytes = static_cast<size_t>(max_batch) * 4;
         hipError_t e = hipMalloc(&m->head_scratch, bytes);
         if (e == hipSuccess) e = hipMemset(m->head_scratch, 0, bytes);
@@ -1285,6 +1285,18 @@ static int check_step_args(const nerva_mlp *mlp, const float *X, int32_t ldx, in
     return NERVA_OK;
 }
 
+// Y = act(W X + b) of one layer of a step
+static SpmmArgs forward_args(const nerva_layer *ly, const float *in, int64_t ldin, float *out, int64_t ldout, int32_t batch)
+{
+    SpmmArgs a{};
+    a.blocks = ly->plan; a.nnz = ly->nnz; a.scratch = ly->scratch; a.scratch_ld = ly->scratch_ld;
+    a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
+    a.X = in; a.ldx = ldin; a.Y = out; a.ldy = ldout;
+    a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
+    a.full_scratch = ly->full ? ly->full_scratch : nullptr; a.full_scratch_ld = ly->full_scratch_ld;
+    return a;
+}
+
 static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t batch, char *ws, const Layout &L,
                          hipStream_t s, size_t n_layers)
 {
@@ -1293,12 +1305,7 @@ static int forward_chain(nerva_mlp *mlp, const float *X, int32_t ldx, int32_t ba
     for (size_t l = 0; l < n_layers; ++l) {
         const nerva_layer *ly = mlp->layers[l];
         float *A = reinterpret_cast<float *>(ws + L.A[l]);
-        SpmmArgs a{};
-        a.blocks = ly->plan; a.nnz = ly->nnz; a.scratch = ly->scratch; a.scratch_ld = ly->scratch_ld;
-        a.indptr = ly->indptr; a.indices = ly->indices; a.values = ly->values; a.bias = ly->bias;
-        a.X = in; a.ldx = ldin; a.Y = A; a.ldy = L.ld;
-        a.rows = ly->rows; a.x_rows = ly->cols; a.batch = batch; a.relu = ly->activation == NERVA_ACT_RELU;
-        a.full_scratch = ly->full ? ly->full_scratch : nullptr; a.full_scratch_ld = ly->full_scratch_ld;
+        const SpmmArgs a = forward_args(ly, in, ldin, A, L.ld, batch);
         if (use_dense(ly, batch)) {
             Timed tm(mlp->prof, s, "dense_forward", static_cast<int>(l));
             HIP_TRY(dense_forward(ly, in, ldin, A, L.ld, batch, s));
@@ -1377,24 +1384,8 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
     // feedforward, then the loss gradient / batch size
     const nerva_layer *last = mlp->layers[n - 1];
     const bool head = mlp->head && head_ok(last->rows, last->cols, last->nnz);  // (a rebind may have grown the layer)
-    rc = forward_chain(mlp, X, ldx, batch, ws, L, s, head ? n - 1 : n);
-    if (rc != NERVA_OK) return rc;
-    if (head) {
-        // output layer, loss and the gradient handed to layer n-2 in one launch
-        HeadArgs h{};
-        h.indptr = last->indptr; h.indices = last->indices; h.values = last->values; h.bias = last->bias;
-        h.indptr_t = last->indptr_t; h.indices_t = last->indices_t; h.values_t = last->values_t;
-        h.rows = last->rows; h.cols = last->cols; h.batch = batch;
-        h.X = A(n - 2); h.ldx = L.ld; h.Z = A(n - 1); h.ldz = L.ld; h.labels = labels;
-        h.dZ = dZ(n - 1); h.lddz = L.ld; h.dX = dZ(n - 2); h.lddx = L.ld;
-        h.loss_cols = mlp->head_scratch;  // their mean is taken by the launch that runs S_{n-1}
-        Timed tm(mlp->prof, s, "spmm_forward+softmax_ce+spmm_transposed", n - 1);
-        HIP_TRY(launch_head(h, s));
-    } else {
-        Timed tm(mlp->prof, s, "softmax_ce", n - 1);
-        HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
-    }
-
+    bool ce_fused = false;  // softmax cross-entropy in the finish pass of the output layer's forward product
+    int bias_done = -1;     // a layer whose biases the launch that formed its dZ has already updated
     // backpropagate and optimize, last layer first.  Layer l's transposed product T_l runs before
     // anything updates layer l's weights, so every gradient sees the weights of the step's start.
     auto make_T = [&](int l) {
@@ -1419,19 +1410,50 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
         g.rows = ly->rows; g.x_rows = ly->cols; g.batch = batch; g.nnz = ly->nnz;
         g.partial = ly->partial; g.partial_stride = ly->partial_stride;
         g.partial_db_at = ly->partial_db_at; g.partial_tiles = ly->partial_tiles;
-        if (head && l == n - 1 && loss_out) { g.loss_cols = mlp->head_scratch; g.loss_out = loss_out; g.loss_n = batch; }
+        if ((head || ce_fused) && l == n - 1 && loss_out) { g.loss_cols = mlp->head_scratch; g.loss_out = loss_out; g.loss_n = batch; }
         if (fused) {
             g.fused = 1; g.nesterov = nesterov; g.lr = lr; g.momentum = momentum;
             g.values = ly->values; g.velocity = mlp->vel[l];
             if (l > 0) { g.values_t = ly->values_t; g.pos_t = ly->pos_t; g.perm = ly->perm; }  // the first layer's mirror is never read
             if (ly->dense_on) { g.dense = ly->dense; g.dense_ld = ly->dense_ld; }
-            g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l];
+            if (l != bias_done) { g.bias = ly->bias; g.bias_velocity = mlp->bias_vel[l]; }
         } else {
             g.g = reinterpret_cast<float *>(ws + L.g[l]);
             g.db = reinterpret_cast<float *>(ws + L.db[l]);
         }
         return g;
     };
+
+    // A saturated output layer too large for the head: its forward product streams the operand, and the finish pass of
+    // that product can form the loss gradient as it stores the logits, when the layer's backward pass (one streaming
+    // launch as well) is there to take the mean of the per-column losses.
+    SpmmArgs last_F{};
+    if (!head && fused && n >= 2 && mlp->head_scratch && !use_dense(last, batch)) {
+        last_F = forward_args(last, A(n - 2), L.ld, A(n - 1), L.ld, batch);
+        last_F.ce_labels = labels; last_F.ce_dZ = dZ(n - 1); last_F.ce_lddz = L.ld; last_F.ce_loss_cols = mlp->head_scratch;
+        ce_fused = true;  // (make_S then asks for the mean of the losses)
+        ce_fused = spmm_softmax_epilogue_ok(last_F) && full_backward_ok(make_T(n - 1), make_S(n - 1));
+    }
+    rc = forward_chain(mlp, X, ldx, batch, ws, L, s, head || ce_fused ? n - 1 : n);
+    if (rc != NERVA_OK) return rc;
+    if (ce_fused) {
+        Timed tm(mlp->prof, s, "spmm_forward+softmax_ce", n - 1);
+        HIP_TRY(launch_spmm(last_F, s));
+    } else if (head) {
+        // output layer, loss and the gradient handed to layer n-2 in one launch
+        HeadArgs h{};
+        h.indptr = last->indptr; h.indices = last->indices; h.values = last->values; h.bias = last->bias;
+        h.indptr_t = last->indptr_t; h.indices_t = last->indices_t; h.values_t = last->values_t;
+        h.rows = last->rows; h.cols = last->cols; h.batch = batch;
+        h.X = A(n - 2); h.ldx = L.ld; h.Z = A(n - 1); h.ldz = L.ld; h.labels = labels;
+        h.dZ = dZ(n - 1); h.lddz = L.ld; h.dX = dZ(n - 2); h.lddx = L.ld;
+        h.loss_cols = mlp->head_scratch;  // their mean is taken by the launch that runs S_{n-1}
+        Timed tm(mlp->prof, s, "spmm_forward+softmax_ce+spmm_transposed", n - 1);
+        HIP_TRY(launch_head(h, s));
+    } else {
+        Timed tm(mlp->prof, s, "softmax_ce", n - 1);
+        HIP_TRY(launch_softmax_ce(A(n - 1), L.ld, labels, last->rows, batch, dZ(n - 1), L.ld, loss_out, s));
+    }
 
     if (fused) {
         // Launch order T_{n-1} | T_{n-2} + S_{n-1} | ... | T_1 + S_2 | S_1 + S_0: the fused
@@ -1460,7 +1482,7 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
                 u.G = ly->dense_g; u.ldg = ly->dense_ld; u.D = ly->dense; u.ldw = ly->dense_ld;
                 u.values = ly->values; u.velocity = mlp->vel[l];
                 if (l > 0) { u.values_t = ly->values_t; u.pos_t = ly->pos_t; }
-                u.bias = ly->bias; u.bias_velocity = mlp->bias_vel[l];
+                if (l != bias_done) { u.bias = ly->bias; u.bias_velocity = mlp->bias_vel[l]; }
                 u.rows = ly->rows; u.cols = ly->cols; u.batch = batch; u.nesterov = nesterov; u.lr = lr; u.momentum = momentum;
                 Timed tm(mlp->prof, s, "dense_sddmm_update", l);
                 HIP_TRY(launch_dense_sddmm_update(u, l > 0 ? A(l - 1) : X, l > 0 ? L.ld : ldx, s));
@@ -1484,8 +1506,14 @@ static int train_step(nerva_mlp *mlp, const float *X, int32_t ldx, const int32_t
             if (full_backward_ok(t, g_same)) {
                 if (pending >= 0 && (rc = run_S_alone(pending)) != NERVA_OK) return rc;
                 pending = -1;
+                SddmmArgs g_full = g_same;
+                if (bias_done < 0 && mlp->layers[l - 1]->bias) {
+                    // dZ_{l-1} is formed a whole row per wave: the bias gradient of layer l-1 is that row's sum
+                    g_full.below_bias = mlp->layers[l - 1]->bias; g_full.below_bias_velocity = mlp->bias_vel[l - 1];
+                    bias_done = l - 1;
+                }
                 Timed tm(mlp->prof, s, "backward_full", l);
-                HIP_TRY(launch_full_backward(t, g_same, s));
+                HIP_TRY(launch_full_backward(t, g_full, s));
                 continue;
             }
             if (backward_fused_ok(t, g_same)) {

@@ -106,7 +106,15 @@ struct SpmmArgs {
     // kFullSlice-column slices of W: full_scratch[(slice * rows + row) * full_scratch_ld + column].
     float *full_scratch;     // or nullptr: the matrix is not full, or has too many rows
     int64_t full_scratch_ld;
+    // Optional epilogue for an output layer served that way (spmm_softmax_epilogue_ok): the softmax
+    // cross-entropy of the logits Y against ce_labels -- ce_dZ = (softmax(Y) - onehot) / batch, one
+    // loss per column into ce_loss_cols (their mean is taken by a later launch, SddmmArgs::loss_cols).
+    const int32_t *ce_labels;  // [batch] or nullptr: no epilogue
+    float *ce_dZ;              // (rows, ce_lddz)
+    int64_t ce_lddz;
+    float *ce_loss_cols;       // [batch]
 };
+bool spmm_softmax_epilogue_ok(const SpmmArgs &a);
 constexpr int32_t kFullMaxRows = 16;
 constexpr int32_t kFullSlice = 128;   // columns of W (rows of the operand) per work-group
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s);
@@ -143,6 +151,11 @@ struct SddmmArgs {
     // by-product, unrelated to the layer: *loss_out = mean(loss_cols[0..loss_n)), summed in one fixed
     // order by the first wave of the launch.  The head kernel leaves one loss per batch column; a
     // grid-wide sum inside it would need device-scope fences, which write back and invalidate the L2s.
+    // launch_full_backward only: the biases of the layer BELOW and their momentum buffer, or nullptr.  That layer's
+    // bias gradient is the row sum of the dX this launch forms, a wave per row, so its update can ride along
+    // (the caller then leaves the biases out of that layer's own update).
+    float *below_bias;
+    float *below_bias_velocity;
     const float *loss_cols;  // or nullptr
     float *loss_out;
     int32_t loss_n;

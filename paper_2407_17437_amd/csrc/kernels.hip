@@ -737,6 +737,55 @@ __global__ __launch_bounds__(kEwBlock) void full_rows_finish_kernel(const SpmmAr
     a.Y[static_cast<int64_t>(r) * a.ldy + c] = y;
 }
 
+// The same finish pass for an output layer, with the softmax cross-entropy on top: wave r of a work-group adds the
+// slices of row r for 64 columns, the rows meet in LDS, and every wave then forms its own row of the loss gradient
+// (each lane repeats the column's maximum and sum over the <= 16 rows, in the order of softmax_ce_kernel, so the
+// gradient has the same bits); wave 0 also stores the column's loss.
+__global__ __launch_bounds__(kBlock) void full_rows_finish_softmax_kernel(const SpmmArgs a, const int n_slices)
+{
+    __shared__ float zs[kWavesPerBlock][kWave];
+    static_assert(kFullMaxRows <= kWavesPerBlock, "one wave per row");
+    const int lane = threadIdx.x & (kWave - 1);
+    const int r = wave_in_block();
+    const int c = blockIdx.x * kWave + lane;
+    const bool on = r < a.rows && c < a.batch;
+    float y = 0.f;
+    if (on) {
+        const float *p = a.full_scratch + static_cast<int64_t>(r) * a.full_scratch_ld + c;
+        const int64_t step = static_cast<int64_t>(a.rows) * a.full_scratch_ld;
+        int q = 0;
+        for (; q + 8 <= n_slices; q += 8) {  // eight loads in flight, added in slice order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[(q + u) * step];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) y += v[u];
+        }
+        for (; q < n_slices; ++q) y += p[q * step];
+        y += a.bias ? a.bias[r] : 0.f;
+        a.Y[static_cast<int64_t>(r) * a.ldy + c] = y;
+    }
+    zs[r][lane] = y;
+    __syncthreads();
+    if (!on) return;
+    const int t = a.ce_labels[c];
+    float z[kFullMaxRows];
+#pragma unroll
+    for (int i = 0; i < kFullMaxRows; ++i) z[i] = i < a.rows ? zs[i][lane] : -INFINITY;
+    float m = z[0];
+#pragma unroll
+    for (int i = 1; i < kFullMaxRows; ++i) m = fmaxf(m, z[i]);
+    float sum = 0.f, zt = 0.f;
+#pragma unroll
+    for (int i = 0; i < kFullMaxRows; ++i) {
+        if (i < a.rows) sum += expf(z[i] - m);
+        zt = i == t ? z[i] : zt;
+    }
+    const float lse = m + logf(sum);
+    a.ce_dZ[static_cast<int64_t>(r) * a.ce_lddz + c] = (expf(y - lse) - (r == t ? 1.f : 0.f)) * (1.0f / static_cast<float>(a.batch));
+    if (r == 0) a.ce_loss_cols[c] = lse - zt;
+}
+
 // ---- staged product ----------------------------------------------------------------------
 // For wide batches and matrices with many entries per operand row the gathers are served from
 // LDS instead of the L2, and the results stay in registers until they are complete.  A
@@ -1466,6 +1515,7 @@ __global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, c
         dz_s[idx] = v;
     }
     __syncthreads();
+    mean_loss_task(a, blockIdx.x);
     if (blockIdx.x == 0 && wv < R && (a.db || (a.fused && a.bias))) {
         float sum = 0.f;
         for (int ch = 0; ch < n_chunks; ++ch) {
@@ -1489,6 +1539,7 @@ __global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, c
         for (int i = 0; i < 16; ++i) d[i] = 0.f;
         const float *xr = a.X + static_cast<int64_t>(j) * a.ldx;
         float w_own = 0.f;  // lane i: W(i, j)
+        float below = 0.f;  // the lane's share of the row sum of dX[j, :]
         if constexpr (WITH_T)
             if (lane < R) w_own = a.values[static_cast<int64_t>(lane) * K + j];
         for (int ch = 0; ch < n_chunks; ++ch) {
@@ -1509,8 +1560,22 @@ __global__ __launch_bounds__(kBlock) void full_sddmm_kernel(const SddmmArgs a, c
                     }
                 }
             }
-            if constexpr (WITH_T)
-                if (col < a.batch) st4(dX + static_cast<int64_t>(j) * lddx + col, keep_where_positive(t, x));  // (batch % 4 == 0)
+            if constexpr (WITH_T) {
+                const float4 o = keep_where_positive(t, x);  // (columns beyond the batch: x = 0, so o = 0)
+                if (col < a.batch) st4(dX + static_cast<int64_t>(j) * lddx + col, o);  // (batch % 4 == 0)
+                below += (o.x + o.y) + (o.z + o.w);
+            }
+        }
+        if constexpr (WITH_T) {
+            if (a.below_bias) {  // uniform
+                below = group_sum<kWave>(below);
+                if (lane == 0) {
+                    float w = a.below_bias[j], v = a.below_bias_velocity[j];
+                    momentum_step(w, v, below, a.lr, a.momentum, a.nesterov);
+                    a.below_bias[j] = w;
+                    a.below_bias_velocity[j] = v;
+                }
+            }
         }
         // lane i of each row of 16 lanes gets that row's sum of product i; then the four rows: (0 + 1) + (2 + 3)
         float g = row16_transpose_sum(d, lane & 15);
@@ -2407,7 +2472,9 @@ bool backward_fused_ok(const SpmmArgs &t, const SddmmArgs &g)
 // input once, a wave per input row, and that row is also the mask of the transposed product's result row.
 bool full_backward_ok(const SpmmArgs &t, const SddmmArgs &g)
 {
-    if (!sddmm_full_ok(g) || !g.fused || g.ZM || !g.values || !g.velocity) return false;
+    SddmmArgs plain = g;
+    plain.loss_cols = nullptr;  // (this launch can carry the mean of the losses, the plain one is not asked to)
+    if (!sddmm_full_ok(plain) || !g.fused || g.ZM || !g.values || !g.velocity) return false;
     if (t.batch != g.batch || t.XM || t.bias || t.relu || !t.YM || t.YM != g.X || t.ldym != g.ldx || t.X != g.dZ || t.ldx != g.lddz) return false;
     if (t.rows != g.x_rows || t.x_rows != g.rows || t.nnz != g.nnz || !t.Y) return false;
     return t.ldy % 4 == 0 && (reinterpret_cast<uintptr_t>(t.Y) & 15u) == 0;
@@ -2448,6 +2515,16 @@ hipError_t launch_backward_fused(const SpmmArgs &t, const SddmmArgs &g, hipStrea
     return hipGetLastError();
 }
 
+// whether launch_spmm serves `a` by streaming (full matrix of few rows), where the softmax epilogue can ride along
+static bool spmm_full_rows_ok(const SpmmArgs &a)
+{
+    return a.batch > 4 && a.full_scratch && !a.XM && a.batch >= 64 && a.rows <= kFullMaxRows && spmm_vec_ok(a) && a.full_scratch_ld % 4 == 0;
+}
+bool spmm_softmax_epilogue_ok(const SpmmArgs &a)
+{
+    return a.rows > 0 && a.blocks.n_blocks > 0 && spmm_full_rows_ok(a) && !a.relu && !a.YM && a.ce_labels && a.ce_dZ && a.ce_loss_cols;
+}
+
 hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
 {
     if (a.rows <= 0 || a.batch <= 0 || a.blocks.n_blocks <= 0) return hipSuccess;
@@ -2460,12 +2537,14 @@ hipError_t launch_spmm(const SpmmArgs &a, hipStream_t s)
             hipLaunchKernelGGL(spmm_finish_kernel, dim3(a.blocks.n_huge_rows, 1), dim3(256), 0, s, a);
         return hipGetLastError();
     }
-    if (a.full_scratch && !a.XM && a.batch >= 64 && a.rows <= kFullMaxRows && spmm_vec_ok(a) &&
-        a.full_scratch_ld % 4 == 0) {
+    if (spmm_full_rows_ok(a)) {
         const int n_slices = (a.x_rows + kFullSlice - 1) / kFullSlice;
         hipLaunchKernelGGL(full_rows_kernel, dim3(n_slices, (a.batch + 255) / 256), dim3(kFullWaves * kWave),
                            static_cast<size_t>(kFullWaves) * a.rows * kWave * sizeof(float4), s, a);
-        hipLaunchKernelGGL(full_rows_finish_kernel, dim3(a.rows, (a.batch + kEwBlock - 1) / kEwBlock), dim3(kEwBlock), 0, s, a, n_slices);
+        if (a.ce_labels)
+            hipLaunchKernelGGL(full_rows_finish_softmax_kernel, dim3((a.batch + kWave - 1) / kWave), dim3(kBlock), 0, s, a, n_slices);
+        else
+            hipLaunchKernelGGL(full_rows_finish_kernel, dim3(a.rows, (a.batch + kEwBlock - 1) / kEwBlock), dim3(kEwBlock), 0, s, a, n_slices);
         return hipGetLastError();
     }
     if (spmm_staged_ok(a)) {

@@ -469,6 +469,7 @@ def test_stage_parity_backward_of_a_saturated_output_layer(nb, torch_mod, oracle
             names = [n for n, _ in nb.mlp_profile_read(M.handle)[1]]
             nb.mlp_profile_enable(M.handle, 0)
             assert ("backward_full[2]" in names) == (not unfused), names
+            assert ("spmm_forward+softmax_ce[2]" in names) == (not unfused), names   # loss gradient formed by the product's finish pass
         stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused)
     if not unfused:
         # the pipeline of separate kernels from the same start.  Its transposed product adds a row's terms in another
