@@ -447,7 +447,7 @@ def test_stage_parity_backward_on_one_gather_stream(nb, torch_mod, oracle, sizes
     M.close()
 
 
-@pytest.mark.parametrize("batch,unfused", [(256, False), (192, False), (1024, False), (256, True)])
+@pytest.mark.parametrize("batch,unfused", [(256, False), (192, False), (1024, False), (256, True), (40, False), (66, False)])
 def test_stage_parity_backward_of_a_saturated_output_layer(nb, torch_mod, oracle, batch, unfused):
     """An output layer that stores every entry (Erdos-Renyi split of a small global density: the 10-row layer
     saturates, as in the wide MLP) and is too large for the fused head: its transposed product, SDDMM and update run
@@ -468,8 +468,9 @@ def test_stage_parity_backward_of_a_saturated_output_layer(nb, torch_mod, oracle
         if t == 0:
             names = [n for n, _ in nb.mlp_profile_read(M.handle)[1]]
             nb.mlp_profile_enable(M.handle, 0)
-            assert ("backward_full[2]" in names) == (not unfused), names
-            assert ("spmm_forward+softmax_ce[2]" in names) == (not unfused), names   # loss gradient formed by the product's finish pass
+            streaming = not unfused and batch >= 64 and batch % 4 == 0      # (narrow or ragged batches take the ordinary kernels)
+            assert ("backward_full[2]" in names) == streaming, names
+            assert ("spmm_forward+softmax_ce[2]" in names) == streaming, names   # loss gradient formed by the product's finish pass
         stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused)
     if not unfused:
         # the pipeline of separate kernels from the same start.  Its transposed product adds a row's terms in another
