@@ -532,3 +532,41 @@ def test_training_steps_replayed_from_a_hip_graph(nb, torch_mod, sizes, kw, batc
         assert float(loss_g.item()) == float(E.loss.item()) and np.isfinite(float(loss_g.item()))
     del g
     G.close(); E.close()
+
+
+def _random_case(seed):
+    """A seeded draw of a network and a batch: depths 2-4, widths from a few to 1500, per-layer densities from 2 %
+    to full (a layer may also be empty), batches from 1 to 512 including odd ones, every pipeline flag."""
+    rng = np.random.default_rng(7000 + seed)
+    depth = int(rng.integers(2, 5))
+    widths = [int(rng.choice([7, 33, 64, 120, 300, 700, 1500])) for _ in range(depth)] + [int(rng.choice([3, 10, 16, 40]))]
+    dens = [float(rng.choice([0.0, 0.02, 0.1, 0.3, 0.6, 1.0], p=[0.05, 0.25, 0.25, 0.2, 0.15, 0.1])) for _ in range(depth)]
+    nnz = [int(round(d * widths[l] * widths[l + 1])) for l, d in enumerate(dens)]
+    batch = int(rng.choice([1, 3, 8, 33, 64, 100, 132, 256, 512]))
+    return tuple(widths), nnz, batch, bool(rng.integers(2)), bool(rng.integers(2)), bool(rng.integers(2)), bool(rng.integers(2))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_stage_parity_random_networks(nb, torch_mod, oracle, seed):
+    """Which kernels serve a step depends on shapes, densities, the batch and the flags (packed, tiled, paired, fused
+    backward passes, streaming kernels for saturated layers, the head, the dense route): random draws of all of these,
+    every stage of two steps against the oracle."""
+    torch = torch_mod
+    sizes, nnz, batch, unfused, separate_head, nesterov, dense_route = _random_case(seed)
+    mlp = wl.make_mlp(sizes, layer_nnz=nnz, bias_std=0.1, pattern_seed=160 + seed, value_seed=260 + seed)
+    Xs, Ts = wl.make_batches(sizes[0], sizes[-1], batch, 2, seed=360 + seed)
+    flags = (nb.NERVA_MLP_UNFUSED if unfused else 0) | (nb.NERVA_MLP_SEPARATE_HEAD if separate_head else 0) | \
+            (nb.NERVA_MLP_NESTEROV if nesterov else 0)
+    print(f"case {seed}: sizes {sizes} nnz {nnz} batch {batch} unfused {unfused} separate_head {separate_head} "
+          f"nesterov {nesterov} dense_route {dense_route}", flush=True)
+    nb.nerva_set_dense_threshold(0.4 if dense_route else 2.0)
+    try:
+        M = nb.MLP(mlp, batch, flags)
+    finally:
+        nb.nerva_set_dense_threshold(2.0)
+    for t in range(2):
+        before = snapshot(M)
+        M.train_step(nb.to_dense(Xs[t]), torch.as_tensor(Ts[t]).cuda(), batch, 0.05, 0.9)
+        torch.cuda.synchronize()
+        stage_parity(nb, torch, oracle, M, mlp, before, Xs[t], Ts[t], batch, 0.05, 0.9, unfused, nesterov=nesterov)
+    M.close()
