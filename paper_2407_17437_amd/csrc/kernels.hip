@@ -2404,12 +2404,22 @@ int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float
     // tiles when they fill a whole L2: config 4's 8192-row operand, 120 -> 113 us, where the product loses 7 %)
     if (row_bytes * 128 <= (for_sddmm ? (4ll << 20) : budget) && batch > 128) return 128;
     if (row_bytes * 64 <= budget && batch > 64) return 64;
-    // Narrower tiles multiply the per-wave set-up (one pass over the row partition per tile) by 32 or
-    // more.  Measured on 16384^2 matrices at batch 1024: they pay from about 128 entries per row on
-    // (1 % density: 1.48 -> 1.18 ms, 10 %: 1.4x) unless a few operand rows take most of the gathers
-    // (the transposed product of a power-law matrix: 0.58 -> 1.08 ms); at 16 entries per row they lose,
-    // and so they do on an 8 MiB operand (batch 128), half of which an L2 holds anyway.
     if (batch <= 32) return 0;
+    // Short rows on an operand whose 64-column tile (up to 4 MiB) no longer fits beside the rest in an L2: wide tiles
+    // still pay at wide batches, because they cut the set of operand rows in flight by 8 to 16 and what misses the L2
+    // then hits the infinity cache.  Measured on 16384^2 matrices at batch 1024 (512): uniform rows at 0.1 / 0.3 %,
+    // products 165 -> 83 and 458 -> 197 us with 64 columns (109 / 282 with 128), SDDMM 156 -> 111 and 442 -> 271 with
+    // 128; power-law rows at 0.1 %, forward 142 -> 110 (85 -> 60), SDDMM 165 -> 134 (80 -> 69; 147 with 64 columns).
+    // Where a few operand rows take most gathers (the transposed product of the power-law matrix) 64 columns lose
+    // (57 -> 63, 554 -> 597 us at 0.1 / 1 %) and 128 do not (58, 475).
+    // (Beside the staged long rows of the power-law matrix at 1 % the short rows then run in 64- instead of 32-column
+    // tiles: forward 495 -> 450 us.)
+    if (batch >= 512 && row_bytes * 64 <= (4ll << 20)) return for_sddmm || hot_share >= 0.5f ? 128 : 64;
+    // Narrower tiles, for operands larger still or batches below 512: they multiply the per-wave set-up (one pass
+    // over the row partition per tile) by 32 or more.  Measured on 16384^2 matrices at batch 1024 against untiled
+    // launches: they pay from about 128 entries per row on (1 % density: 1.48 -> 1.18 ms, 10 %: 1.4x) unless a few
+    // operand rows take most of the gathers (the transposed product of a power-law matrix: 0.58 -> 1.08 ms); at 16
+    // entries per row they lose, and so they do on an 8 MiB operand (batch 128), half of which an L2 holds anyway.
     if (nnz >= static_cast<int64_t>(rows) * 1024) return 32;
     if (nnz >= static_cast<int64_t>(rows) * 128 && hot_share < 0.5f && row_bytes * batch >= (16ll << 20)) return 32;
     return 0;
