@@ -70,7 +70,8 @@ constexpr float kStageMinReuse = 2.f;    // stored entries per staged operand ro
 constexpr int32_t kStageLongSegment = 10;       // mean entries per segment from which staging pays whatever the operand's size: products
 constexpr int32_t kStageLongSegmentSddmm = 20;  // ... and the SDDMM (measured on 8192 x 8192 uniform at batch 1024, 1 / 2 / 3 / 5 % density:
                                                 // products 142 / 301 / 407 / - us against 235 / 278 / 349 / 442 staged, SDDMM 162 / 289 / 407 / - against 317 / 369 / 460 / 584)
-constexpr int64_t kStageBigOperand = 48ll << 20;  // operand bytes no set of L2s holds: staging pays for short segments too
+constexpr int64_t kStageBigOperand = 48ll << 20;  // operand bytes no set of L2s holds: staging pays for shorter segments,
+constexpr int32_t kStageSegmentBigOperand = 7;    // ... from this many entries per segment on
 constexpr int32_t kHotRows = 1024;
 constexpr int32_t kHugeFlag = 0x40000000;
 constexpr int32_t kPackMaxLen = 128;     // longest row served by the packed path

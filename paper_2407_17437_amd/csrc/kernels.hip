@@ -2258,14 +2258,16 @@ bool staged_pays(const RowBlocks &blocks, int32_t x_rows, int32_t batch, int32_t
     if (groups < (blocks.staged_partial ? kStageTargetGroups / 2 : kStageTargetGroups * 3 / 4)) return false;
     if (static_cast<double>(nnz) < static_cast<double>(kStageMinReuse) * blocks.staged_ranges * x_rows) return false;
     if (static_cast<int64_t>(blocks.staged_longest_share) * 4096 > nnz * n_tiles) return false;
-    const bool long_segments = nnz >= static_cast<int64_t>(long_segment) * rows * blocks.staged_cblocks;
-    // (a few hot operand rows that take most gathers stay cached on the other paths)
-    // ... and short segments only pay on rows of similar length: on a power-law matrix most (row, block)
-    // pairs hold one entry or none and cost a visit all the same (measured: 1 % power-law at batch 1024,
-    // forward 1.00 -> 1.06 ms, SDDMM 0.99 -> 1.33 ms; 1 % uniform, 1.18 -> 0.76 ms)
+    // An operand beyond the L2s, evenly used, on rows of similar length: shorter segments already pay, because the other
+    // kernels' gathers partly go to memory there (a few hot operand rows that take most gathers would stay cached on
+    // the other paths; on a power-law matrix most (row, block) pairs hold one entry or none and cost a visit all the
+    // same).  Measured on 16384^2 uniform matrices at batch 1024 against the column-tiled kernels, product / SDDMM:
+    // 0.7 % (3.6 entries per segment) 648 / 851 us staged against 429 / 595; 1 % (5.1) 692 / 1012 against 662 / 836;
+    // 2 % (10.2) 880 / 1259 against 1341 / 1642.
     const bool big_operand = static_cast<int64_t>(x_rows) * batch * 4 >= kStageBigOperand && blocks.hot_share < 0.5f &&
                              static_cast<int64_t>(blocks.staged_longest_row) * rows <= 4 * nnz;
-    return long_segments || big_operand;
+    const int64_t segment = big_operand ? std::min(long_segment, kStageSegmentBigOperand) : long_segment;
+    return nnz >= segment * rows * blocks.staged_cblocks;
 }
 
 int spmm_tile_group(const SpmmArgs &a);
