@@ -2417,7 +2417,15 @@ int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float
     // (Beside the staged long rows of the power-law matrix at 1 % the short rows then run in 64- instead of 32-column
     // tiles: forward 495 -> 450 us.)
     if (batch >= 512 && row_bytes * 64 <= (4ll << 20)) return for_sddmm || hot_share >= 0.5f ? 128 : 64;
-    // Narrower tiles, for operands larger still or batches below 512: they multiply the per-wave set-up (one pass
+    // Narrower batches (128 .. 511) on such an operand: 64-column tiles from about 128 entries per row on, unless a few
+    // operand rows take most gathers.  16384^2 at 1 %, batch 128 / 256: uniform rows, products 105 -> 90 and 252 -> 173 us
+    // (32-column tiles: 136, 250), SDDMM 108 -> 97 and 225 -> 181; power-law rows, forward 96 -> 81 and 210 -> 154,
+    // SDDMM 93 -> 89 and 204 -> 164, transposed (hot rows) 83 -> 100 and 131 -> 171: left untiled.  At 16 entries per
+    // row tiles lose at these batches (power-law 0.1 %, batch 128: forward 24 -> 36 us).
+    if (batch >= 128 && row_bytes * 64 <= (4ll << 20) && row_bytes * batch >= (8ll << 20) && hot_share < 0.5f &&
+        nnz >= static_cast<int64_t>(rows) * 128)
+        return 64;
+    // Narrower tiles, for operands larger still: they multiply the per-wave set-up (one pass
     // over the row partition per tile) by 32 or more.  Measured on 16384^2 matrices at batch 1024 against untiled
     // launches: they pay from about 128 entries per row on (1 % density: 1.48 -> 1.18 ms, 10 %: 1.4x) unless a few
     // operand rows take most of the gathers (the transposed product of a power-law matrix: 0.58 -> 1.08 ms); at 16
