@@ -421,8 +421,9 @@ def test_layer_trained_as_first_layer_then_chained_further_up(nb, torch_mod, ora
 
 
 @pytest.mark.parametrize("sizes,sparsity,batch,unfused", [
-    ((100, 2100, 5200, 10), 0.985, 256, False),     # 64-column tiles (16 lanes per mirror row)
-    ((100, 2100, 5200, 10), 0.985, 200, True),      # ragged last tile; gradients stored, separate momentum kernels
+    ((100, 2100, 8600, 10), 0.992, 256, False),     # 64-column tiles (16 lanes per mirror row): a 128-column tile of dZ would exceed an L2
+    ((100, 2100, 5200, 10), 0.985, 200, False),     # 128-column tiles, ragged last tile
+    ((100, 2100, 5200, 10), 0.985, 200, True),      # gradients stored, separate momentum kernels
     ((100, 2304, 2304, 2304, 10), 0.98, 512, False),  # 128-column tiles (32 lanes per mirror row), two hidden layers fused in a row
 ])
 def test_stage_parity_backward_on_one_gather_stream(nb, torch_mod, oracle, sizes, sparsity, batch, unfused):
