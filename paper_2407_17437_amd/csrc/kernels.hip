@@ -2407,7 +2407,7 @@ int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float
     if (row_bytes * 128 <= (for_sddmm ? (4ll << 20) : budget) && batch > 128) return 128;
     if (row_bytes * 64 <= budget && batch > 64) return 64;
     if (batch <= 32) return 0;
-    // Short rows on an operand whose 64-column tile (up to 4 MiB) no longer fits beside the rest in an L2: wide tiles
+    // Short rows on an operand whose 64-column tile (4 MiB for 16384 rows) no longer fits beside the rest in an L2: wide tiles
     // still pay at wide batches, because they cut the set of operand rows in flight by 8 to 16 and what misses the L2
     // then hits the infinity cache.  Measured on 16384^2 matrices at batch 1024 (512): uniform rows at 0.1 / 0.3 %,
     // products 165 -> 83 and 458 -> 197 us with 64 columns (109 / 282 with 128), SDDMM 156 -> 111 and 442 -> 271 with
@@ -2416,7 +2416,9 @@ int tile_columns(int32_t x_rows, int32_t batch, int64_t nnz, int32_t rows, float
     // (57 -> 63, 554 -> 597 us at 0.1 / 1 %) and 128 do not (58, 475).
     // (Beside the staged long rows of the power-law matrix at 1 % the short rows then run in 64- instead of 32-column
     // tiles: forward 495 -> 450 us.)
-    if (batch >= 512 && row_bytes * 64 <= (4ll << 20)) return for_sddmm || hot_share >= 0.5f ? 128 : 64;
+    // (The same holds with tiles twice that size: 32768^2 at batch 1024, uniform rows at 0.1 / 0.5 %, products 629 -> 478
+    // and 2577 -> 1814 us; 12288^2: 94 -> 49 and 395 -> 163.)
+    if (batch >= 512 && row_bytes * 64 <= (8ll << 20)) return for_sddmm || hot_share >= 0.5f ? 128 : 64;
     // Narrower batches (128 .. 511) on such an operand: 64-column tiles from about 128 entries per row on, unless a few
     // operand rows take most gathers.  16384^2 at 1 %, batch 128 / 256: uniform rows, products 105 -> 90 and 252 -> 173 us
     // (32-column tiles: 136, 250), SDDMM 108 -> 97 and 225 -> 181; power-law rows, forward 96 -> 81 and 210 -> 154,
