@@ -298,7 +298,9 @@ enum {
     /* A small output layer (at most 32 rows and 8192 stored entries, as the 10-class layers
      * of Section 5.1) normally runs its forward product, the softmax cross-entropy and its
      * transposed product in one launch, each work-group owning four columns of the batch.
-     * This flag keeps the three separate launches that larger output layers always use. */
+     * This flag keeps them in separate launches, as the output layers beyond those limits always
+     * run (where a saturated one has the loss gradient formed by the finish pass of its forward
+     * product and its whole backward pass in one streaming launch). */
     NERVA_MLP_SEPARATE_HEAD = 4
 };
 int mlp_create(nerva_mlp **out, int32_t n_layers, nerva_layer *const *layers,
