@@ -612,6 +612,43 @@ def test_random_shapes_staged_kernels(nb, torch_mod, oracle, k):
     _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged=True)
 
 
+@pytest.mark.parametrize("rows,cols,kind,batch", [
+    (2500, 20000, "uniform", 1024),   # forward and SDDMM gather a 20000-row operand: 64- and 128-column tiles beyond an L2
+    (2500, 20000, "zipf", 512),
+    (20000, 2500, "uniform", 1024),   # the transposed product gathers it
+    (20000, 2500, "zipf", 640),       # ... with a few hot operand rows: 128-column tiles
+    (2500, 14000, "uniform", 200),    # batches below 512: 64-column tiles from about 128 entries per row on
+    (14000, 2500, "uniform", 132),
+])
+def test_wide_tiles_on_operands_beyond_an_l2(nb, torch_mod, oracle, rows, cols, kind, batch):
+    """Operands of more rows than a column tile can keep L2-resident are tiled all the same at wide batches (the tile
+    cuts the rows in flight); all three products on such operands, in both orientations, against the oracle."""
+    torch = torch_mod
+    rng = np.random.default_rng(rows + cols + batch)
+    if kind == "uniform":
+        lens = rng.binomial(cols, 150.0 / cols, size=rows)
+    else:
+        lens = np.minimum(cols, (4 * cols * rng.permutation(np.arange(1, rows + 1)) ** -1.2).astype(np.int64))
+    indptr, indices = wl.pattern_from_row_nnz(lens.astype(np.int64), cols, seed=rows + batch)
+    lay = wl.SparseLayerData(rows, cols, indptr, indices, rng.standard_normal(int(indptr[-1])).astype(np.float32),
+                             rng.standard_normal(rows).astype(np.float32), False)
+    X = rng.standard_normal((cols, batch)).astype(np.float32)
+    dY = rng.standard_normal((rows, batch)).astype(np.float32)
+    L = nb.SparseLinear(lay, max_batch=batch)
+    Xd = nb.to_dense(X); Yd = nb.dense(rows, batch); dYd = nb.to_dense(dY); dXd = nb.dense(cols, batch)
+    g = torch.full((lay.nnz,), float("nan"), device="cuda"); db = torch.full((rows,), float("nan"), device="cuda")
+    nb.sparse_linear_forward(L.handle, Xd, Yd, batch)
+    nb.sparse_linear_backward(L.handle, Xd, None, dYd, dXd, g, db, batch)
+    torch.cuda.synchronize()
+    Y, S = oracle.spmm(rows, cols, lay.indptr, lay.indices, lay.values, lay.bias, X, False)
+    close(Yd.cpu().numpy(), Y, S, what="Y")
+    dX, SdX = oracle.spmm_t(rows, cols, lay.indptr, lay.indices, lay.values, dY)
+    close(dXd.cpu().numpy(), dX, SdX, what="dX")
+    gr, Sg, dbr, Sdb = oracle.sddmm(rows, cols, lay.indptr, lay.indices, dY, X)
+    close(g.cpu().numpy(), gr, Sg, what="dvalues"); close(db.cpu().numpy(), dbr, Sdb, what="dbias")
+    L.close()
+
+
 def _random_shape_parity(nb, torch_mod, oracle, k, prefer_staged):
     torch = torch_mod
     rows, cols, lens, batch, ld, relu = _random_case(k)
