@@ -344,6 +344,34 @@ def rebind_times(env):
     return {"what": "sparse_linear_rebind, wall clock around the C call, 5 calls", "cases": out}
 
 
+def launch_floor(env):
+    """Time per launch of a chain of dependent launches that do next to nothing: 256 calls of the library's copy kernel on
+    4 floats, recorded into one HIP graph (so that the host's call overhead is out of the picture) and replayed."""
+    torch, nb = env.torch, env.nb
+    a = torch.zeros(64, device="cuda"); b = torch.zeros(64, device="cuda")
+    n_launch, reps = 256, 20
+    nb.nerva_copy_f32(b, a, 4)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        for k in range(n_launch):
+            if k % 2 == 0:
+                nb.nerva_copy_f32(b, a, 4)      # (each launch reads what the one before wrote)
+            else:
+                nb.nerva_copy_f32(a, b, 4)
+    g.replay(); torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record(); e1.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * n_launch)
+    log(f"dependent launch of a 16-byte copy: {us:.2f} us")
+    return {"what": "microseconds per launch in a chain of 256 dependent launches of a 16-byte copy kernel, replayed from a HIP graph",
+            "us_per_launch": round(us, 3)}
+
+
 def fit_line(x, y):
     """Least squares y = a + b x and the coefficient of determination."""
     n = len(x)
@@ -462,6 +490,7 @@ def main() -> int:
                                          "gbs_cold", "frac_hbm_cold", "gbs_back_to_back", "frac_hbm_back_to_back",
                                          "tflops_back_to_back")} for r in rows]}
         extras["rebind"] = rebind_times(env)
+        extras["launch_floor"] = launch_floor(env)
         extras["seconds"] = round(time.perf_counter() - t_extra, 1)
 
     out = {
